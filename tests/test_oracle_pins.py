@@ -1,0 +1,373 @@
+"""Pins for the CPU oracle: each test checks the oracle against something other than itself —
+hand-derived bitmaps (tests/golden/), a library attention routine, closed forms, invariants.
+
+Paper passages: Sec. 3.1 (attention definition, causal prefill), Sec. 3.2 (head classes;
+text tokens attend to all previous tokens), App. kernel Alg. 4 (online-softmax recurrence),
+App. D.2 remark that Intra-Image+Sink masks are a superset of the other two.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import workloads as W
+from golden_masks import all_fixtures, load
+
+D, S, I, IS = 0, 1, 2, 3
+
+
+def np_token_arrays(spans, L, sink_len):
+    """Independent (numpy slicing) construction of imgid / issink from the span table."""
+    imgid = np.zeros(L, dtype=np.int32)
+    issink = np.zeros(L, dtype=np.uint8)
+    issink[:sink_len] = 1
+    for g, (s, e, k) in enumerate(np.asarray(spans).reshape(-1, 3)):
+        imgid[s:e] = g + 1
+        issink[s:s + k] = 1
+    return imgid, issink
+
+
+def small_prompt(seed=0, classes=(D, S, I, IS), n_kv=2, d=16, dtype="f32", sink_len=3):
+    rng = np.random.default_rng(seed)
+    runs = [("T", int(rng.integers(0, 9)))]
+    for _ in range(int(rng.integers(2, 6))):
+        runs.append(("I", int(rng.integers(1, 70))))
+        runs.append(("T", int(rng.integers(0, 12))))
+    return W.custom_prompt(runs, classes, n_kv, d, dtype=dtype, sink_len=sink_len,
+                           name=f"small{seed}")
+
+
+# ----------------------------------------------------------------------------- mask predicate
+
+@pytest.mark.parametrize("path", all_fixtures())
+def test_mask_matches_hand_derived_bitmaps(path):
+    L, spans, sink_len, expected = load(path)
+    imgid, issink = oracle.token_arrays(spans, L, sink_len)
+    for cls, want in expected.items():
+        got = oracle.mask(cls, imgid, issink)
+        assert np.array_equal(got, want), f"{path} class {cls}\n{got}\n{want}"
+
+
+def test_token_arrays_match_numpy_slicing():
+    for seed in range(5):
+        p = small_prompt(seed)
+        a, b = oracle.token_arrays(p.spans, p.seq_len, p.sink_len)
+        c, d_ = np_token_arrays(p.spans, p.seq_len, p.sink_len)
+        assert np.array_equal(a, c) and np.array_equal(b, d_)
+
+
+@pytest.mark.parametrize("bad", [
+    [(0, 0, 0)], [(5, 3, 0)], [(0, 4, 5)], [(0, 4, -1)], [(0, 40, 0)], [(4, 8, 0), (6, 9, 0)],
+    [(4, 8, 0), (0, 2, 0)],
+])
+def test_token_arrays_reject_bad_spans(bad):
+    with pytest.raises(ValueError):
+        oracle.token_arrays(np.asarray(bad, dtype=np.int32), 32, 0)
+
+
+def test_mask_set_identities():
+    """IS = I u S; every class within Dense; Dense = lower triangle; text rows equal in all classes."""
+    for seed in range(6):
+        p = small_prompt(seed, sink_len=seed % 3)
+        imgid, issink = oracle.token_arrays(p.spans, p.seq_len, p.sink_len)
+        m = [oracle.mask(c, imgid, issink).astype(bool) for c in range(4)]
+        L = p.seq_len
+        assert np.array_equal(m[D], np.tril(np.ones((L, L), dtype=bool)))
+        assert np.array_equal(m[IS], m[I] | m[S])
+        for c in (S, I, IS):
+            assert not (m[c] & ~m[D]).any()
+            assert np.array_equal(m[c][imgid == 0], m[D][imgid == 0])
+            # text keys are visible to every query (vertical bands)
+            assert np.array_equal(m[c][:, imgid == 0], m[D][:, imgid == 0])
+        # Intra-Image heads never cross images; Sink heads never see a non-sink image key
+        ii, jj = np.nonzero(m[I])
+        cross = (imgid[ii] > 0) & (imgid[jj] > 0) & (imgid[ii] != imgid[jj])
+        assert not cross.any()
+        ii, jj = np.nonzero(m[S])
+        bad = (imgid[ii] > 0) & (imgid[jj] > 0) & (issink[jj] == 0)
+        assert not bad.any()
+
+
+def closed_form_pair_counts(spans, L, sink_len):
+    """Pair counts per class from prefix sums over the span table (no per-pair enumeration)."""
+    imgid, issink = np_token_arrays(spans, L, sink_len)
+    text = imgid == 0
+    text_cum = np.cumsum(text)                       # text keys in [0..i]
+    snt = (issink == 1) & ~text
+    snt_cum = np.cumsum(snt)                         # sink-and-image keys in [0..i]
+    idx = np.arange(L)
+    start = np.zeros(L, dtype=np.int64)
+    for s, e, _ in np.asarray(spans).reshape(-1, 3):
+        start[s:e] = s
+    own = idx - start + 1                            # own-image keys in [start..i]
+    snt_before = np.where(start > 0, snt_cum[np.maximum(start - 1, 0)], 0)
+    own_sink = snt_cum - snt_before                  # of which sinks
+    counts = {D: L * (L + 1) // 2}
+    per_row = {S: text_cum + snt_cum, I: text_cum + own, IS: text_cum + snt_cum + own - own_sink}
+    for c, r in per_row.items():
+        counts[c] = int(np.where(text, idx + 1, r).sum())
+    return counts
+
+
+def test_pair_counts_match_closed_form():
+    for seed in range(6):
+        p = small_prompt(seed, sink_len=2 * (seed % 2))
+        imgid, issink = oracle.token_arrays(p.spans, p.seq_len, p.sink_len)
+        want = closed_form_pair_counts(p.spans, p.seq_len, p.sink_len)
+        for c in range(4):
+            assert oracle.pair_count(c, imgid, issink) == want[c]
+            assert int(oracle.mask(c, imgid, issink).sum()) == want[c]
+    p = W.tiny_config("paper10")
+    imgid, issink = oracle.token_arrays(p.spans, p.seq_len, p.sink_len)
+    want = closed_form_pair_counts(p.spans, p.seq_len, p.sink_len)
+    for c in range(4):
+        assert oracle.pair_count(c, imgid, issink) == want[c]
+
+
+def test_tile_states_from_bitmap():
+    """The tile reduction equals a numpy block reduction of the dense bitmap (out-of-range = masked)."""
+    for seed, (bm, bn) in enumerate([(8, 4), (16, 8), (128, 64), (4, 4)]):
+        p = small_prompt(seed)
+        imgid, issink = oracle.token_arrays(p.spans, p.seq_len, p.sink_len)
+        L = p.seq_len
+        M, N = -(-L // bm), -(-L // bn)
+        for c in range(4):
+            full = np.zeros((M * bm, N * bn), dtype=np.int64)
+            full[:L, :L] = oracle.mask(c, imgid, issink)
+            cnt = full.reshape(M, bm, N, bn).sum(axis=(1, 3))
+            want = np.where(cnt == 0, 0, np.where(cnt == bm * bn, 2, 1)).astype(np.uint8)
+            got = oracle.tile_states(c, imgid, issink, bm, bn)
+            assert np.array_equal(got, want)
+            sub = np.array([M - 1, 0], dtype=np.int32)
+            assert np.array_equal(oracle.tile_states(c, imgid, issink, bm, bn, sub), want[sub])
+
+
+# ----------------------------------------------------------------------------- softmax . V numerics
+
+def sdpa_fp64(q, k, v, G, scale, mask=None):
+    """Library attention on CPU in fp64: causal when mask is None, else an explicit boolean mask."""
+    qt, kt, vt = (torch.from_numpy(np.asarray(x, dtype=np.float64)) for x in (q, k, v))
+    kt = kt.repeat_interleave(G, dim=0)
+    vt = vt.repeat_interleave(G, dim=0)
+    if mask is None:
+        o = torch.nn.functional.scaled_dot_product_attention(qt, kt, vt, is_causal=True, scale=scale)
+    else:
+        o = torch.nn.functional.scaled_dot_product_attention(
+            qt, kt, vt, attn_mask=torch.from_numpy(mask.astype(bool)), scale=scale)
+    return o.numpy()
+
+
+def test_all_dense_equals_library_causal_attention():
+    p = W.custom_prompt([("T", 7), ("I", 300), ("T", 5), ("I", 211), ("T", 40)], [D] * 6, 2, 32,
+                        dtype="f32", scale=0.31)
+    q, k, v = (t.numpy() for t in W.make_qkv(p, 3))
+    got = oracle.attention_for_prompt(p, q, k, v)
+    want = sdpa_fp64(q, k, v, p.gqa_group, p.scale)
+    assert np.abs(got - want).max() < 1e-12
+
+
+def test_tiny_config_dense_head_equals_library_causal_attention():
+    p = W.tiny_config("paper10")
+    q, k, v = (t.numpy() for t in W.make_qkv(p, 0))
+    got = oracle.attention_for_prompt(p, q, k, v)
+    want = sdpa_fp64(q, k, v, p.gqa_group, p.scale)
+    assert p.head_class[0] == D
+    assert np.abs(got[0] - want[0]).max() < 1e-11
+    assert np.abs(got[1] - want[1]).max() > 1e-3      # the sparse head really differs
+
+
+def test_sparse_classes_equal_library_attention_with_explicit_mask():
+    """Checks the numerics (scale, GQA head mapping, operand order) for every class; the mask
+    itself is pinned by the bitmap / identity / perturbation tests."""
+    p = W.custom_prompt([("T", 5), ("I", 90), ("T", 3), ("I", 120), ("I", 40), ("T", 9)],
+                        [D, S, I, IS, IS, I, S, D], 4, 24, dtype="f32", sink_len=2, scale=0.4)
+    q, k, v = (t.numpy() for t in W.make_qkv(p, 1))
+    imgid, issink = np_token_arrays(p.spans, p.seq_len, p.sink_len)
+    got = oracle.attention_for_prompt(p, q, k, v)
+    for h, c in enumerate(p.head_class):
+        m = oracle.mask(int(c), imgid, issink)
+        assert m.any(axis=1).all()
+        want = sdpa_fp64(q[h:h + 1], k[h // 2:h // 2 + 1], v[h // 2:h // 2 + 1], 1, p.scale, m[None])
+        assert np.abs(got[h] - want[0]).max() < 1e-12, h
+
+
+def test_rows_sum_to_one_and_empty_rows_are_zero():
+    # first image has no sink and no text before it: Sink-head rows there are empty
+    p = W.custom_prompt([("I", 20), ("T", 4), ("I", 30)], [S, I, IS, D], 1, 8, dtype="f32",
+                        sink_mode="prefix")
+    q, k, v = (t.numpy() for t in W.make_qkv(p, 2))
+    v1 = np.ones_like(v)
+    o = oracle.attention_for_prompt(p, q, k, v1)
+    imgid, issink = oracle.token_arrays(p.spans, p.seq_len, p.sink_len)
+    for h, c in enumerate(p.head_class):
+        nonempty = oracle.mask(int(c), imgid, issink).any(axis=1)
+        assert np.allclose(o[h][nonempty], 1.0, atol=1e-13)
+        assert np.all(o[h][~nonempty] == 0.0)
+    assert (~oracle.mask(S, imgid, issink).any(axis=1)).sum() == 20
+
+
+def test_key_shift_invariance():
+    p = small_prompt(4, d=16)
+    q, k, v = (t.numpy().astype(np.float64) for t in W.make_qkv(p, 4))
+    c = np.random.default_rng(0).standard_normal(16)
+    # exactly representable inputs keep the fp32 interface exact
+    q, k, v, c = (np.round(x * 64) / 64 for x in (q, k, v, c))
+    a = oracle.attention_for_prompt(p, q, k, v)
+    b = oracle.attention_for_prompt(p, q, k + c, v)
+    assert np.abs(a - b).max() < 1e-11
+
+
+def test_row_subset_equals_full():
+    p = small_prompt(5)
+    q, k, v = (t.numpy() for t in W.make_qkv(p, 5))
+    full = oracle.attention_for_prompt(p, q, k, v)
+    rows = np.array([p.seq_len - 1, 0, 7, 7, 3], dtype=np.int32)
+    sub = oracle.attention_for_prompt(p, q, k, v, rows)
+    assert np.array_equal(sub, full[:, rows])
+
+
+# ----------------------------------------------------------------------------- mask seen through the output
+
+def test_perturbation_invariances():
+    runs = [("T", 6), ("I", 50), ("T", 4), ("I", 60), ("T", 3), ("I", 40), ("T", 5)]
+    p = W.custom_prompt(runs, [I, S, IS, D], 1, 16, dtype="f32", sink_len=0, span_sink=5)
+    q, k, v = (t.numpy() for t in W.make_qkv(p, 6))
+    base = oracle.attention_for_prompt(p, q, k, v)
+    (s1, e1, _), (s2, e2, k2), (s3, e3, _) = (tuple(int(x) for x in r) for r in p.spans)
+    rng = np.random.default_rng(1)
+
+    def perturbed(lo, hi):
+        kk, vv = k.copy(), v.copy()
+        kk[:, lo:hi] = rng.standard_normal(kk[:, lo:hi].shape)
+        vv[:, lo:hi] = rng.standard_normal(vv[:, lo:hi].shape)
+        return oracle.attention_for_prompt(p, q, kk, vv)
+
+    rows2 = np.arange(s2, e2)
+    # other images' keys (non-sink part for the sink classes) do not matter to image 2's queries
+    o = perturbed(s1, e1)
+    assert np.array_equal(o[0][rows2], base[0][rows2])                  # Intra: whole image 1
+    o = perturbed(s1 + 5, e1)
+    assert np.array_equal(o[1][rows2], base[1][rows2])                  # Sink: non-sink part of image 1
+    assert np.array_equal(o[2][rows2], base[2][rows2])                  # Intra+Sink likewise
+    assert np.abs(o[3][rows2] - base[3][rows2]).max() > 1e-6            # Dense notices
+    # the sink part of image 1 matters to Sink and Intra+Sink, not to Intra
+    o = perturbed(s1, s1 + 5)
+    assert np.array_equal(o[0][rows2], base[0][rows2])
+    assert np.abs(o[1][rows2] - base[1][rows2]).max() > 1e-6
+    assert np.abs(o[2][rows2] - base[2][rows2]).max() > 1e-6
+    # a Sink head ignores the non-sink keys of the query's own image
+    o = perturbed(s2 + 5, e2)
+    assert np.array_equal(o[1][rows2], base[1][rows2])
+    late = np.arange(s2 + 6, e2)
+    assert np.abs(o[0][late] - base[0][late]).max() > 1e-6
+    # earlier text matters to everyone; later tokens to no one (causality)
+    o = perturbed(e1, s2)
+    for h in range(4):
+        assert np.abs(o[h][rows2] - base[h][rows2]).max() > 1e-6
+    o = perturbed(e2, p.seq_len)
+    for h in range(4):
+        assert np.array_equal(o[h][: e2], base[h][: e2])
+
+
+def uniform_attention_closed_form(p, v):
+    """With q = 0 every allowed key gets the same weight: out[i] = mean of v over the allowed
+    set, from per-category prefix sums of v (O(L d), no pair enumeration)."""
+    L = p.seq_len
+    imgid, issink = np_token_arrays(p.spans, L, p.sink_len)
+    text = imgid == 0
+    snt = (issink == 1) & ~text
+    start = np.zeros(L, dtype=np.int64)
+    for s, e, _ in p.spans:
+        start[s:e] = s
+    idx = np.arange(L)
+
+    def csum(w):  # inclusive prefix sums with a leading zero row
+        return np.concatenate([np.zeros((1,) + w.shape[1:]), np.cumsum(w, axis=0)])
+
+    out = np.zeros((p.n_q_heads, L, v.shape[-1]))
+    for h, c in enumerate(p.head_class):
+        vh = v[h // p.gqa_group].astype(np.float64)
+        ones = np.ones((L, 1))
+        acc, cnt = {}, {}
+        for name, sel in (("all", np.ones(L, bool)), ("text", text), ("snt", snt), ("img", ~text),
+                          ("img_nonsink", ~text & ~snt)):
+            acc[name] = csum(vh * sel[:, None])
+            cnt[name] = csum(ones * sel[:, None])
+
+        def rng_sum(tab, lo, hi):   # keys in [lo, hi]
+            return tab[hi + 1] - tab[lo]
+
+        num = rng_sum(acc["all"], 0 * idx, idx)
+        den = rng_sum(cnt["all"], 0 * idx, idx)
+        if c != D:
+            n2 = rng_sum(acc["text"], 0 * idx, idx)
+            d2 = rng_sum(cnt["text"], 0 * idx, idx)
+            if c in (S, IS):
+                n2 = n2 + rng_sum(acc["snt"], 0 * idx, idx)
+                d2 = d2 + rng_sum(cnt["snt"], 0 * idx, idx)
+            if c == I:
+                n2 = n2 + rng_sum(acc["img"], start, idx)
+                d2 = d2 + rng_sum(cnt["img"], start, idx)
+            if c == IS:
+                n2 = n2 + rng_sum(acc["img_nonsink"], start, idx)
+                d2 = d2 + rng_sum(cnt["img_nonsink"], start, idx)
+            num = np.where(text[:, None], num, n2)
+            den = np.where(text[:, None], den, d2)
+        out[h] = np.where(den > 0, num / np.maximum(den, 1), 0.0)
+    return out
+
+
+def test_uniform_attention_closed_form():
+    for seed in range(4):
+        p = small_prompt(seed + 10, classes=(D, S, I, IS), n_kv=2, sink_len=seed)
+        q, k, v = (t.numpy() for t in W.make_qkv(p, seed))
+        got = oracle.attention_for_prompt(p, np.zeros_like(q), k, v)
+        want = uniform_attention_closed_form(p, v)
+        assert np.abs(got - want).max() < 1e-12
+    p = W.tiny_config("paper10").with_classes([S, I])
+    q, k, v = (t.numpy() for t in W.make_qkv(p, 0))
+    got = oracle.attention_for_prompt(p, np.zeros_like(q), k, v)
+    assert np.abs(got - uniform_attention_closed_form(p, v)).max() < 1e-12
+
+
+# ----------------------------------------------------------------------------- tiled recurrence
+
+def tiled_online_softmax(q, k, v, mask, scale, bm, bn):
+    """fp64 re-statement of the flash recurrence (running max, running sum, rescaled output;
+    App. kernel Alg. 4) with a final division by the running sum."""
+    L, d = q.shape
+    out = np.zeros((L, d))
+    for m0 in range(0, L, bm):
+        rows = slice(m0, min(m0 + bm, L))
+        nr = rows.stop - rows.start
+        acc = np.zeros((nr, d))
+        l = np.zeros(nr)
+        mx = np.full(nr, -np.inf)
+        for n0 in range(0, rows.stop, bn):
+            cols = slice(n0, min(n0 + bn, L))
+            s = (q[rows] @ k[cols].T) * scale
+            s = np.where(mask[rows, cols] > 0, s, -np.inf)
+            mx_n = s.max(axis=1)
+            new = np.maximum(mx, mx_n)
+            safe = np.where(np.isinf(new), 0.0, new)
+            pmat = np.exp(s - safe[:, None])
+            alpha = np.exp(np.where(np.isinf(mx), -np.inf, mx - safe))
+            l = alpha * l + pmat.sum(axis=1)
+            acc = alpha[:, None] * acc + pmat @ v[cols]
+            mx = new
+        out[rows] = np.where(l[:, None] > 0, acc / np.where(l > 0, l, 1.0)[:, None], 0.0)
+    return out
+
+
+@pytest.mark.parametrize("bm,bn", [(128, 64), (16, 8)])
+def test_tile_size_independence(bm, bn):
+    p = W.custom_prompt([("T", 9), ("I", 150), ("T", 2), ("I", 77), ("T", 20)], [D, S, I, IS], 2, 16,
+                        dtype="f32", sink_len=4)
+    q, k, v = (t.numpy().astype(np.float64) for t in W.make_qkv(p, 8))
+    k[0, 0] *= 8.0
+    imgid, issink = oracle.token_arrays(p.spans, p.seq_len, p.sink_len)
+    got = oracle.attention_for_prompt(p, q, k, v)
+    for h, c in enumerate(p.head_class):
+        m = oracle.mask(int(c), imgid, issink)
+        want = tiled_online_softmax(q[h], k[h // 2], v[h // 2], m, p.scale, bm, bn)
+        assert np.abs(got[h] - want).max() < 1e-12
