@@ -1,0 +1,131 @@
+/*
+ * blindsight.h — C ABI of the MI355X sparse prefill-attention library.
+ *
+ * The library computes causal prefill attention over an interleaved text/image prompt in
+ * which every query head carries one of four offline-assigned sparsity classes and the mask
+ * follows from the prompt's image-span table alone (paper Sec. 3.2, Sec. 5, App. "BlindSight
+ * Attention Kernel").  Two steps:
+ *
+ *   bs_build_tilemap   host, integer only: span table + class vector -> for every class and
+ *                      every query tile the list of key tiles to run, each FULL (no masking
+ *                      needed) or PARTIAL (element predicate needed); all other tiles are
+ *                      skipped.  This replaces the paper kernel's per-tile metadata
+ *                      (sink_end[M], first_image[M], the all/any(istext) tests of Alg. 3).
+ *   bs_attn_prefill    device: one flash-style pass over the listed tiles (Alg. 3-7 folded
+ *                      into one loop with a single running softmax per row).
+ *
+ * All functions return BS_OK (0) or a negative BS_E* code; nothing throws or aborts across
+ * this boundary.  No function synchronises the device except where stated.
+ */
+#ifndef BLINDSIGHT_H
+#define BLINDSIGHT_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define BS_OK            0
+#define BS_EINVAL       (-1)  /* null pointer, negative size, malformed span table, bad class   */
+#define BS_EUNSUPPORTED (-2)  /* tile size / head_dim / dtype the kernels do not implement      */
+#define BS_ENOMEM       (-3)  /* host or device allocation failed                              */
+#define BS_EHIP         (-4)  /* a HIP runtime call failed (no device, launch error, ...)      */
+
+/* Head classes (paper Sec. 3.2; "headtype" in Alg. 3).  Bit 0 = sink keys visible,
+ * bit 1 = own-image keys visible. */
+typedef enum {
+    BS_DENSE      = 0,  /* every earlier key                                        */
+    BS_SINK       = 1,  /* text keys + sink keys                                    */
+    BS_INTRA      = 2,  /* text keys + keys of the query's own image                */
+    BS_INTRA_SINK = 3   /* union of the two                                         */
+} bs_head_class;
+
+/* Element types of q/k/v/out. */
+#define BS_BF16 0
+#define BS_F32  1
+
+/* One image: tokens [start, end) of the prompt; its first `sink` tokens are sink keys
+ * (paper Sec. 6.1 "Sparse Mask Generation": sinks sit at the start of an image).
+ * Tokens outside every span are text (imgid = 0 in the paper's notation). */
+typedef struct { int32_t start, end, sink; } bs_span;
+
+typedef struct bs_tilemap bs_tilemap;   /* opaque; owns its host arrays and device buffers */
+
+/*
+ * Build the tile map of one prompt.
+ *   spans        host pointer, n_spans rows sorted by start, non-overlapping, inside
+ *                [0, seq_len), 0 <= sink <= end - start (may be NULL when n_spans == 0)
+ *   seq_len      L > 0
+ *   head_class   host pointer, n_q_heads values in 0..3
+ *   sink_len     positions [0, sink_len) are sink keys too (0 <= sink_len <= L)
+ *   block_m/n    query / key tile edge (the paper's block_m, block_n).  The builder accepts
+ *                any positive sizes; the attention kernels need 128 x 64.
+ *   out          receives the new map; untouched on failure.  Free with bs_tilemap_destroy.
+ * Tile (m, n) covers queries [m*block_m, +block_m) x keys [n*block_n, +block_n); positions
+ * >= L count as masked.  SKIP = no allowed pair, FULL = every pair allowed, else PARTIAL.
+ * A pair (i, j) is allowed iff j <= i and ( query i is text, or class is Dense, or key j is
+ * text, or (class has the sink bit and j is a sink key), or (class has the intra bit and
+ * i, j belong to the same image) ).
+ * Host only: needs no GPU.  Errors: BS_EINVAL, BS_ENOMEM.
+ */
+int bs_build_tilemap(const bs_span *spans, int32_t n_spans, int32_t seq_len,
+                     const uint8_t *head_class, int32_t n_q_heads, int32_t sink_len,
+                     int32_t block_m, int32_t block_n, bs_tilemap **out);
+
+/* Frees host arrays and (if uploaded) device buffers.  NULL is allowed.  The caller must
+ * make sure no bs_attn_prefill using the map is still in flight. */
+void bs_tilemap_destroy(bs_tilemap *tm);
+
+/* Geometry: any output pointer may be NULL. */
+int bs_tilemap_dims(const bs_tilemap *tm, int32_t *seq_len, int32_t *n_q_tiles,
+                    int32_t *n_k_tiles, int32_t *n_q_heads);
+
+/* Expand the range lists of class `cls` for query tiles [q_tile_begin, +q_tile_count) into
+ * states[q_tile_count][n_k_tiles] (host, row-major): 0 skip, 1 partial, 2 full. */
+int bs_tilemap_tile_states(const bs_tilemap *tm, int32_t cls, int32_t q_tile_begin,
+                           int32_t q_tile_count, uint8_t *states);
+
+/* Per-class accounting (any output pointer may be NULL):
+ *   visited = full + partial tiles over all query tiles; allowed_pairs = number of allowed
+ *   (i, j) pairs, from span geometry (the bench's "4 d FLOP per unmasked pair" counts these);
+ *   empty_rows = query rows whose allowed set is empty (their output is zero);
+ *   n_ranges = entries in the class's range list. */
+int bs_tilemap_stats(const bs_tilemap *tm, int32_t cls, int64_t *visited, int64_t *full,
+                     int64_t *partial, int64_t *allowed_pairs, int64_t *empty_rows,
+                     int64_t *n_ranges);
+
+/* Copy the map to the current HIP device (hipMalloc + synchronous hipMemcpy).  Optional:
+ * bs_attn_prefill does it on first use.  Not thread-safe against concurrent calls on the
+ * same map.  Errors: BS_EHIP, BS_ENOMEM. */
+int bs_tilemap_upload(bs_tilemap *tm);
+
+/*
+ * Sparse causal prefill attention (paper Sec. 3.1 for the definition, App. kernel Alg. 3-7
+ * for the tiled form):  for query head h with class head_class[h] and KV head h / gqa_group,
+ *   out[h, i, :] = sum_j softmax_j( scale * <q[h,i], k[h/G,j]> over allowed j ) * v[h/G, j, :]
+ * and zeros for a row with no allowed key.
+ *   q, out   device pointers, [n_q_heads][L][head_dim], contiguous
+ *   k, v     device pointers, [n_q_heads / gqa_group][L][head_dim], contiguous
+ *   tm       map built for this prompt with block 128 x 64 and the same n_q_heads
+ *   dtype    BS_BF16 (bf16 MFMA, fp32 accumulate, P rounded to bf16 before P.V) or
+ *            BS_F32 (fp32 MFMA throughout)
+ *   head_dim 64 or 128
+ *   scale    finite and > 0 (1/sqrt(d_k) in the paper)
+ *   stream   hipStream_t (NULL = default stream).  The call only enqueues work; the caller
+ *            owns q/k/v/out and keeps them alive until the stream has drained.
+ * The first call on a map uploads it (see bs_tilemap_upload), which synchronises once.
+ * Errors: BS_EINVAL (null pointers, head counts that do not match), BS_EUNSUPPORTED,
+ * BS_EHIP, BS_ENOMEM.  Nothing is launched on error.
+ */
+int bs_attn_prefill(const void *q, const void *k, const void *v, void *out, bs_tilemap *tm,
+                    int32_t dtype, int32_t n_q_heads, int32_t gqa_group, int32_t head_dim,
+                    float scale, void *stream);
+
+/* Static description of an error code. */
+const char *bs_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BLINDSIGHT_H */

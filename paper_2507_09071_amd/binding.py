@@ -1,0 +1,153 @@
+"""ctypes binding with the same names as the C ABI declared in include/blindsight.h.
+
+PyTorch is used only by callers, for device memory and streams: this module takes raw
+device pointers (or objects with .data_ptr()) and never computes anything itself.  If the
+shared library is missing it is built once; if it cannot be loaded the import of a symbol
+fails loudly — there is no fallback path.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import numpy as np
+
+from . import build as _build
+
+BS_BF16, BS_F32 = 0, 1
+DENSE, SINK, INTRA, INTRA_SINK = 0, 1, 2, 3
+
+EXPORTS = ("bs_build_tilemap", "bs_tilemap_destroy", "bs_tilemap_dims", "bs_tilemap_tile_states",
+           "bs_tilemap_stats", "bs_tilemap_upload", "bs_attn_prefill", "bs_strerror")
+
+
+class BlindsightError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where}: {_strerror(code)} ({code})")
+
+
+class _Span(ctypes.Structure):
+    _fields_ = [("start", ctypes.c_int32), ("end", ctypes.c_int32), ("sink", ctypes.c_int32)]
+
+
+_lib = None
+
+
+def library_path() -> str:
+    return _build.LIB
+
+
+def load_library():
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_build.LIB):
+        _build.build(verbose=False)
+    lib = ctypes.CDLL(_build.LIB)
+    i32, i64p = ctypes.c_int32, ctypes.POINTER(ctypes.c_int64)
+    i32p, u8p, vp = ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_uint8), ctypes.c_void_p
+    lib.bs_build_tilemap.argtypes = [ctypes.POINTER(_Span), i32, i32, u8p, i32, i32, i32, i32,
+                                     ctypes.POINTER(vp)]
+    lib.bs_build_tilemap.restype = ctypes.c_int
+    lib.bs_tilemap_destroy.argtypes = [vp]
+    lib.bs_tilemap_destroy.restype = None
+    lib.bs_tilemap_dims.argtypes = [vp, i32p, i32p, i32p, i32p]
+    lib.bs_tilemap_dims.restype = ctypes.c_int
+    lib.bs_tilemap_tile_states.argtypes = [vp, i32, i32, i32, u8p]
+    lib.bs_tilemap_tile_states.restype = ctypes.c_int
+    lib.bs_tilemap_stats.argtypes = [vp, i32, i64p, i64p, i64p, i64p, i64p, i64p]
+    lib.bs_tilemap_stats.restype = ctypes.c_int
+    lib.bs_tilemap_upload.argtypes = [vp]
+    lib.bs_tilemap_upload.restype = ctypes.c_int
+    lib.bs_attn_prefill.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, ctypes.c_float, vp]
+    lib.bs_attn_prefill.restype = ctypes.c_int
+    lib.bs_strerror.argtypes = [ctypes.c_int]
+    lib.bs_strerror.restype = ctypes.c_char_p
+    _lib = lib
+    return lib
+
+
+def _strerror(code: int) -> str:
+    return load_library().bs_strerror(int(code)).decode()
+
+
+def _check(code: int, where: str):
+    if code != 0:
+        raise BlindsightError(code, where)
+
+
+class TileMap:
+    """Owner of one bs_tilemap*.  Immutable after construction; reusable for every call on
+    the same prompt and class vector."""
+
+    def __init__(self, handle: int):
+        self._h = ctypes.c_void_p(handle)
+        lib = load_library()
+        vals = [ctypes.c_int32() for _ in range(4)]
+        _check(lib.bs_tilemap_dims(self._h, *[ctypes.byref(v) for v in vals]), "bs_tilemap_dims")
+        self.seq_len, self.n_q_tiles, self.n_k_tiles, self.n_q_heads = (int(v.value) for v in vals)
+
+    @property
+    def handle(self):
+        return self._h
+
+    def tile_states(self, cls: int, q_tile_begin: int = 0, q_tile_count: int | None = None) -> np.ndarray:
+        if q_tile_count is None:
+            q_tile_count = self.n_q_tiles - q_tile_begin
+        out = np.empty((max(q_tile_count, 0), self.n_k_tiles), dtype=np.uint8)
+        _check(load_library().bs_tilemap_tile_states(
+            self._h, cls, q_tile_begin, q_tile_count,
+            out.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8))), "bs_tilemap_tile_states")
+        return out
+
+    def stats(self, cls: int) -> dict:
+        v = [ctypes.c_int64() for _ in range(6)]
+        _check(load_library().bs_tilemap_stats(self._h, cls, *[ctypes.byref(x) for x in v]),
+               "bs_tilemap_stats")
+        names = ("visited", "full", "partial", "allowed_pairs", "empty_rows", "n_ranges")
+        return {n: int(x.value) for n, x in zip(names, v)}
+
+    def upload(self):
+        _check(load_library().bs_tilemap_upload(self._h), "bs_tilemap_upload")
+
+    def close(self):
+        if self._h is not None and self._h.value:
+            load_library().bs_tilemap_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def bs_build_tilemap(spans, seq_len: int, head_class, sink_len: int = 0,
+                     block_m: int = 128, block_n: int = 64) -> TileMap:
+    """spans: int array [G,3] of (start, end, sink); head_class: uint8 [n_q_heads]."""
+    lib = load_library()
+    sp = np.ascontiguousarray(np.asarray(spans, dtype=np.int32).reshape(-1, 3))
+    hc = np.ascontiguousarray(head_class, dtype=np.uint8)
+    handle = ctypes.c_void_p()
+    sp_ptr = sp.ctypes.data_as(ctypes.POINTER(_Span)) if len(sp) else None
+    rc = lib.bs_build_tilemap(sp_ptr, len(sp), int(seq_len),
+                              hc.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8)), len(hc),
+                              int(sink_len), int(block_m), int(block_n), ctypes.byref(handle))
+    _check(rc, "bs_build_tilemap")
+    return TileMap(handle.value)
+
+
+def _ptr(x) -> int:
+    return int(x.data_ptr()) if hasattr(x, "data_ptr") else int(x)
+
+
+def bs_attn_prefill(q, k, v, out, tilemap: TileMap, dtype: int, n_q_heads: int, gqa_group: int,
+                    head_dim: int, scale: float, stream=None) -> None:
+    """q/k/v/out: device pointers (ints) or tensors exposing .data_ptr(); stream: hipStream_t
+    handle as int (e.g. torch.cuda.current_stream().cuda_stream) or None for the default stream.
+    Enqueues only."""
+    rc = load_library().bs_attn_prefill(_ptr(q), _ptr(k), _ptr(v), _ptr(out), tilemap.handle,
+                                        int(dtype), int(n_q_heads), int(gqa_group), int(head_dim),
+                                        float(scale), ctypes.c_void_p(int(stream) if stream else 0))
+    _check(rc, "bs_attn_prefill")

@@ -1,0 +1,347 @@
+// Host-side tile-map builder: span table + head classes -> per-class, per-query-tile lists of
+// key-tile ranges (FULL / PARTIAL), by interval arithmetic on the span geometry.
+//
+// Mask definition: paper Sec. 3.2 (head classes; text queries see every earlier token; text
+// keys stay visible to every class) and Sec. 3.1 (causal prefill).  The lists take the place
+// of the paper kernel's sink_end[M] / first_image[M] arrays and its all/any(istext_m) dispatch
+// (App. kernel, Notation and Alg. 3): a query tile that holds a text row walks every causal
+// key tile, an image-only query tile walks only tiles that hold a text key, an enabled sink
+// key, or a key of its own image.
+#include <algorithm>
+#include <cstring>
+#include <new>
+
+#include "tilemap_internal.h"
+
+namespace {
+
+using bs::ClassLists;
+using bs::TileRange;
+
+struct Segment { int32_t g, a, b; };  // rows [a, b) of the query tile lie in image g (0-based)
+
+struct Geometry {
+    int32_t L, bm, bn, M, N;
+    const std::vector<bs_span> *spans;
+    std::vector<int32_t> n_text;       // L+1: text tokens in [0, t)
+    std::vector<int32_t> n_free_sink;  // L+1: tokens in [0, t) that are text or sink
+    std::vector<int32_t> last_text;    // L: largest text position <= t, or -1
+    std::vector<int32_t> next_text;    // L+1: smallest text position >= t, or L
+    std::vector<int32_t> next_free_sink;  // L+1: smallest (text or sink) position >= t, or L
+
+    const std::vector<int32_t> &free_count(int cls) const { return (cls & 1) ? n_free_sink : n_text; }
+    const std::vector<int32_t> &next_free(int cls) const { return (cls & 1) ? next_free_sink : next_text; }
+};
+
+struct QueryTile {
+    int32_t r0, r1;       // rows [r0, r1), clipped to L
+    bool ragged;          // fewer than bm rows
+    int32_t last_text;    // last text row inside, or -1
+    std::vector<Segment> segs;
+};
+
+void describe_query_tile(const Geometry &G, int32_t m, QueryTile &qt)
+{
+    qt.r0 = m * G.bm;
+    qt.r1 = std::min(qt.r0 + G.bm, G.L);
+    qt.ragged = (qt.r1 - qt.r0) < G.bm;
+    int32_t lt = G.last_text[qt.r1 - 1];
+    qt.last_text = (lt >= qt.r0) ? lt : -1;
+    qt.segs.clear();
+    const auto &sp = *G.spans;
+    // first span whose end lies beyond r0
+    size_t lo = std::upper_bound(sp.begin(), sp.end(), qt.r0,
+                                 [](int32_t r, const bs_span &s) { return r < s.end; }) - sp.begin();
+    for (size_t g = lo; g < sp.size() && sp[g].start < qt.r1; ++g)
+        qt.segs.push_back({(int32_t)g, std::max(sp[g].start, qt.r0), std::min(sp[g].end, qt.r1)});
+}
+
+// Exact state of tile (query tile qt, key tile n) for class cls: 0 skip, 1 partial, 2 full.
+int tile_state(const Geometry &G, const QueryTile &qt, int cls, int32_t n)
+{
+    const int32_t c0 = n * G.bn, c1 = std::min(c0 + G.bn, G.L);
+    if (c0 > qt.r1 - 1) return 0;  // wholly above the diagonal
+    const auto &sp = *G.spans;
+    const auto &freec = G.free_count(cls);
+
+    bool any = false;
+    if (cls == BS_DENSE || qt.last_text >= c0) {
+        any = true;
+    } else {
+        for (const Segment &s : qt.segs) {
+            int32_t hi = std::min(c1, s.b);  // keys j <= s.b - 1
+            if (hi <= c0) continue;
+            if (freec[hi] - freec[c0] > 0) { any = true; break; }
+            if (cls & 2) {
+                int32_t lo2 = std::max(c0, sp[s.g].start), hi2 = std::min(hi, sp[s.g].end);
+                if (hi2 > lo2) { any = true; break; }
+            }
+        }
+    }
+    if (!any) return 0;
+
+    bool all;
+    if (qt.ragged || (c1 - c0) < G.bn || c1 - 1 > qt.r0) {
+        all = false;  // masked out-of-range positions, or the diagonal cuts through
+    } else if (cls == BS_DENSE || qt.segs.empty()) {
+        all = true;
+    } else {
+        int32_t nonfree = G.bn - (freec[c1] - freec[c0]);
+        if (nonfree == 0) {
+            all = true;
+        } else if (!(cls & 2) || qt.segs.size() > 1) {
+            all = false;  // a masked image key, or two images that cannot both own it
+        } else {
+            const bs_span &own = sp[qt.segs[0].g];
+            int32_t lo2 = std::max(c0, own.start), hi2 = std::min(c1, own.end);
+            int32_t nonfree_own = (hi2 > lo2) ? (hi2 - lo2) - (freec[hi2] - freec[lo2]) : 0;
+            all = (nonfree_own == nonfree);
+        }
+    }
+    return all ? 2 : 1;
+}
+
+// Key tiles that can hold an allowed pair for this query tile (a superset is fine; sorted, unique).
+void candidate_tiles(const Geometry &G, const QueryTile &qt, int cls, std::vector<int32_t> &cand)
+{
+    cand.clear();
+    const int32_t n_last = (qt.r1 - 1) / G.bn;
+    if (cls == BS_DENSE || qt.last_text >= 0) {
+        cand.resize(n_last + 1);
+        for (int32_t n = 0; n <= n_last; ++n) cand[n] = n;
+        return;
+    }
+    // image-only query tile of a sparse class: tiles with a free key (text / enabled sink) ...
+    const auto &nf = G.next_free(cls);
+    for (int32_t pos = 0; pos < qt.r1;) {
+        int32_t j = nf[pos];
+        if (j >= qt.r1) break;
+        int32_t n = j / G.bn;
+        cand.push_back(n);
+        pos = (n + 1) * G.bn;
+        if (pos > G.L) break;
+    }
+    // ... and tiles overlapping the part of an own image that lies at or before the tile's rows
+    if (cls & 2) {
+        const auto &sp = *G.spans;
+        for (const Segment &s : qt.segs)
+            for (int32_t n = sp[s.g].start / G.bn; n <= (s.b - 1) / G.bn; ++n) cand.push_back(n);
+        std::sort(cand.begin(), cand.end());
+        cand.erase(std::unique(cand.begin(), cand.end()), cand.end());
+    }
+}
+
+void build_class(const Geometry &G, int cls, ClassLists &out)
+{
+    out.row_ptr.assign(G.M + 1, 0);
+    out.row_tiles.assign(G.M, 0);
+    out.ranges.clear();
+    QueryTile qt;
+    std::vector<int32_t> cand;
+    for (int32_t m = 0; m < G.M; ++m) {
+        describe_query_tile(G, m, qt);
+        candidate_tiles(G, qt, cls, cand);
+        int32_t run_begin = -1, run_end = -1, run_state = 0;
+        auto flush = [&]() {
+            if (run_begin >= 0) out.ranges.push_back({run_begin, (run_end << 1) | (run_state == 2)});
+            run_begin = -1;
+        };
+        for (int32_t n : cand) {
+            int st = tile_state(G, qt, cls, n);
+            if (st == 0) continue;
+            if (run_begin >= 0 && n == run_end && st == run_state) {
+                ++run_end;
+            } else {
+                flush();
+                run_begin = n; run_end = n + 1; run_state = st;
+            }
+            ++out.row_tiles[m];
+            if (st == 2) ++out.full; else ++out.partial;
+        }
+        flush();
+        out.row_ptr[m + 1] = (int64_t)out.ranges.size();
+    }
+    out.visited = out.full + out.partial;
+}
+
+// Allowed pairs and empty rows per class, from prefix counts (no pair enumeration).
+void count_pairs(const Geometry &G, const std::vector<uint32_t> &code, ClassLists lists[4])
+{
+    const auto &sp = *G.spans;
+    int64_t pairs[4] = {0, 0, 0, 0}, empty[4] = {0, 0, 0, 0};
+    size_t g = 0;
+    for (int32_t i = 0; i < G.L; ++i) {
+        if (code[i] & bs::kCodeText) {
+            for (int c = 0; c < 4; ++c) pairs[c] += i + 1;
+            continue;
+        }
+        while (sp[g].end <= i) ++g;
+        const int64_t text = G.n_text[i + 1];
+        const int64_t sink_img = G.n_free_sink[i + 1] - text;  // image tokens that are sinks, <= i
+        const int64_t own = i - sp[g].start + 1;
+        const int64_t own_sink = (G.n_free_sink[i + 1] - G.n_free_sink[sp[g].start]) -
+                                 (G.n_text[i + 1] - G.n_text[sp[g].start]);
+        const int64_t row[4] = {i + 1, text + sink_img, text + own, text + sink_img + own - own_sink};
+        for (int c = 0; c < 4; ++c) {
+            pairs[c] += row[c];
+            if (row[c] == 0) ++empty[c];
+        }
+    }
+    for (int c = 0; c < 4; ++c) { lists[c].allowed_pairs = pairs[c]; lists[c].empty_rows = empty[c]; }
+}
+
+bool spans_valid(const bs_span *spans, int32_t n, int32_t L)
+{
+    int32_t prev_end = 0;
+    for (int32_t g = 0; g < n; ++g) {
+        const bs_span &s = spans[g];
+        if (s.start < prev_end || s.end <= s.start || s.end > L) return false;
+        if (s.sink < 0 || s.sink > s.end - s.start) return false;
+        prev_end = s.end;
+    }
+    return true;
+}
+
+}  // namespace
+
+extern "C" int bs_build_tilemap(const bs_span *spans, int32_t n_spans, int32_t seq_len,
+                                const uint8_t *head_class, int32_t n_q_heads, int32_t sink_len,
+                                int32_t block_m, int32_t block_n, bs_tilemap **out)
+{
+    if (!out || !head_class || n_q_heads <= 0 || seq_len <= 0 || n_spans < 0) return BS_EINVAL;
+    if (n_spans > 0 && !spans) return BS_EINVAL;
+    if (sink_len < 0 || sink_len > seq_len || block_m <= 0 || block_n <= 0) return BS_EINVAL;
+    if ((int64_t)n_spans >= (int64_t)bs::kCodeImgMask) return BS_EINVAL;
+    for (int32_t h = 0; h < n_q_heads; ++h)
+        if (head_class[h] > 3) return BS_EINVAL;
+    if (!spans_valid(spans, n_spans, seq_len)) return BS_EINVAL;
+
+    bs_tilemap *tm = nullptr;
+    try {
+        tm = new bs_tilemap();
+        const int32_t L = seq_len;
+        tm->L = L; tm->bm = block_m; tm->bn = block_n; tm->sink_len = sink_len;
+        tm->M = (L + block_m - 1) / block_m;
+        tm->N = (L + block_n - 1) / block_n;
+        tm->n_q_heads = n_q_heads;
+        tm->spans.assign(spans, spans + n_spans);
+        tm->head_class.assign(head_class, head_class + n_q_heads);
+
+        // per-token codes
+        tm->code.assign(L, bs::kCodeText);
+        for (int32_t t = 0; t < sink_len; ++t) tm->code[t] |= bs::kCodeSink;
+        for (int32_t g = 0; g < n_spans; ++g)
+            for (int32_t t = spans[g].start; t < spans[g].end; ++t) {
+                uint32_t c = (uint32_t)(g + 1);
+                if (t - spans[g].start < spans[g].sink || t < sink_len) c |= bs::kCodeSink;
+                tm->code[t] = c;
+            }
+
+        Geometry G;
+        G.L = L; G.bm = block_m; G.bn = block_n; G.M = tm->M; G.N = tm->N; G.spans = &tm->spans;
+        G.n_text.assign(L + 1, 0);
+        G.n_free_sink.assign(L + 1, 0);
+        G.last_text.assign(L, -1);
+        G.next_text.assign(L + 1, L);
+        G.next_free_sink.assign(L + 1, L);
+        for (int32_t t = 0; t < L; ++t) {
+            const bool text = tm->code[t] & bs::kCodeText;
+            const bool fs = text || (tm->code[t] & bs::kCodeSink);
+            G.n_text[t + 1] = G.n_text[t] + text;
+            G.n_free_sink[t + 1] = G.n_free_sink[t] + fs;
+            G.last_text[t] = text ? t : (t ? G.last_text[t - 1] : -1);
+        }
+        for (int32_t t = L - 1; t >= 0; --t) {
+            const bool text = tm->code[t] & bs::kCodeText;
+            const bool fs = text || (tm->code[t] & bs::kCodeSink);
+            G.next_text[t] = text ? t : G.next_text[t + 1];
+            G.next_free_sink[t] = fs ? t : G.next_free_sink[t + 1];
+        }
+
+        for (int c = 0; c < 4; ++c) build_class(G, c, tm->cls[c]);
+        count_pairs(G, tm->code, tm->cls);
+
+        // work list: heaviest (head, query tile) first so the tail of the launch is short;
+        // ties keep one KV group's heads of a query tile next to each other.
+        tm->work.resize((size_t)n_q_heads * tm->M);
+        size_t w = 0;
+        for (int32_t h = 0; h < n_q_heads; ++h)
+            for (int32_t m = 0; m < tm->M; ++m) tm->work[w++] = {h, m};
+        const bs_tilemap *t = tm;
+        std::stable_sort(tm->work.begin(), tm->work.end(), [t](const bs::WorkItem &a, const bs::WorkItem &b) {
+            int32_t ca = t->cls[t->head_class[a.head]].row_tiles[a.q_tile];
+            int32_t cb = t->cls[t->head_class[b.head]].row_tiles[b.q_tile];
+            if (ca != cb) return ca > cb;
+            if (a.q_tile != b.q_tile) return a.q_tile > b.q_tile;
+            return a.head < b.head;
+        });
+    } catch (const std::bad_alloc &) {
+        delete tm;
+        return BS_ENOMEM;
+    }
+    *out = tm;
+    return BS_OK;
+}
+
+extern "C" void bs_tilemap_destroy(bs_tilemap *tm)
+{
+    if (!tm) return;
+    if (tm->dev && tm->dev_free) tm->dev_free(tm->dev);
+    delete tm;
+}
+
+extern "C" int bs_tilemap_dims(const bs_tilemap *tm, int32_t *seq_len, int32_t *n_q_tiles,
+                               int32_t *n_k_tiles, int32_t *n_q_heads)
+{
+    if (!tm) return BS_EINVAL;
+    if (seq_len) *seq_len = tm->L;
+    if (n_q_tiles) *n_q_tiles = tm->M;
+    if (n_k_tiles) *n_k_tiles = tm->N;
+    if (n_q_heads) *n_q_heads = tm->n_q_heads;
+    return BS_OK;
+}
+
+extern "C" int bs_tilemap_tile_states(const bs_tilemap *tm, int32_t cls, int32_t q_tile_begin,
+                                      int32_t q_tile_count, uint8_t *states)
+{
+    if (!tm || !states || cls < 0 || cls > 3 || q_tile_begin < 0 || q_tile_count < 0 ||
+        (int64_t)q_tile_begin + q_tile_count > tm->M)
+        return BS_EINVAL;
+    const ClassLists &cl = tm->cls[cls];
+    std::memset(states, 0, (size_t)q_tile_count * tm->N);
+    for (int32_t r = 0; r < q_tile_count; ++r) {
+        uint8_t *row = states + (size_t)r * tm->N;
+        for (int64_t p = cl.row_ptr[q_tile_begin + r]; p < cl.row_ptr[q_tile_begin + r + 1]; ++p) {
+            const TileRange &rg = cl.ranges[p];
+            for (int32_t n = rg.begin; n < rg.end(); ++n) row[n] = rg.full() ? 2 : 1;
+        }
+    }
+    return BS_OK;
+}
+
+extern "C" int bs_tilemap_stats(const bs_tilemap *tm, int32_t cls, int64_t *visited, int64_t *full,
+                                int64_t *partial, int64_t *allowed_pairs, int64_t *empty_rows,
+                                int64_t *n_ranges)
+{
+    if (!tm || cls < 0 || cls > 3) return BS_EINVAL;
+    const ClassLists &cl = tm->cls[cls];
+    if (visited) *visited = cl.visited;
+    if (full) *full = cl.full;
+    if (partial) *partial = cl.partial;
+    if (allowed_pairs) *allowed_pairs = cl.allowed_pairs;
+    if (empty_rows) *empty_rows = cl.empty_rows;
+    if (n_ranges) *n_ranges = (int64_t)cl.ranges.size();
+    return BS_OK;
+}
+
+extern "C" const char *bs_strerror(int code)
+{
+    switch (code) {
+        case BS_OK: return "ok";
+        case BS_EINVAL: return "invalid argument";
+        case BS_EUNSUPPORTED: return "unsupported tile size, head_dim or dtype";
+        case BS_ENOMEM: return "out of memory";
+        case BS_EHIP: return "HIP runtime error";
+        default: return "unknown error";
+    }
+}

@@ -1,0 +1,150 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle, element by element.
+Tolerances: bf16 inputs max-abs 2e-2 and relative-L2 5e-3; fp32 configuration 1e-5."""
+import numpy as np
+import pytest
+import torch
+
+import workloads as W
+from gpu_util import assert_close, errors, oracle_rows, rows_of_tiles, run_prefill
+from test_oracle_pins import uniform_attention_closed_form
+
+pytestmark = pytest.mark.gpu
+D, S, I, IS = 0, 1, 2, 3
+DEV = "cuda:0"
+
+
+def full_parity(p, seed=0, what=None):
+    q, k, v = W.make_qkv(p, seed, DEV)
+    out, tm = run_prefill(p, q, k, v)
+    want = oracle_rows(p, q, k, v)
+    print(what or p.name, "L", p.seq_len, flush=True)
+    res = []
+    for h in range(p.n_q_heads):
+        res.append(assert_close(out[h].float().cpu().numpy(), want[h], p.dtype, f"{p.name} head {h} class {p.head_class[h]}"))
+    return res
+
+
+@pytest.mark.parametrize("mode,span_sink", [("prefix", None), ("paper10", None), ("prefix", 32)])
+def test_config1_tiny_fp32(mode, span_sink):
+    p = W.tiny_config(mode, span_sink)
+    full_parity(p)
+    full_parity(p.with_classes([S, I]), seed=1)
+
+
+RUNS_A = [("T", 37), ("I", 300), ("T", 5), ("I", 451), ("T", 9), ("I", 130), ("I", 77), ("T", 61)]
+
+
+@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("bf16", 64), ("f32", 128), ("f32", 64)])
+def test_small_prompt_all_classes_sharp_values(dtype, d):
+    # q, k ~ N(0,1): logits of order 1..4 sigma, so the running max really moves
+    p = W.custom_prompt(RUNS_A, [D, S, I, IS, IS, I, S, D], 4, d, dtype=dtype, sink_len=5,
+                        name=f"small-{dtype}-d{d}", value_recipe={"std": 1.0, "first_key_scale": 4.0})
+    full_parity(p, seed=3)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+def test_small_prompt_config_like_values(dtype):
+    p = W.custom_prompt(RUNS_A, [IS, D, S, I], 2, 128, dtype=dtype, sink_len=37, sink_mode="paper10",
+                        value_recipe={"std": 1.0 / np.sqrt(128), "outlier_frac": 0.02, "outlier_scale": 6.0})
+    full_parity(p, seed=4)
+
+
+@pytest.mark.parametrize("L", [1, 31, 64, 127, 128, 129, 192, 256, 1000])
+def test_ragged_lengths(L):
+    n_img = max(1, L // 3)
+    runs = [("T", (L - n_img) // 2), ("I", n_img), ("T", L - n_img - (L - n_img) // 2)]
+    p = W.custom_prompt(runs, [D, S, I, IS], 2, 128, dtype="bf16", sink_len=0, name=f"ragged{L}")
+    assert p.seq_len == L
+    full_parity(p, seed=L)
+    p32 = W.custom_prompt(runs, [IS, D], 1, 64, dtype="f32", sink_len=1, name=f"ragged{L}-f32")
+    full_parity(p32, seed=L)
+
+
+def test_text_only_and_image_only():
+    full_parity(W.custom_prompt([("T", 333)], [D, S, I, IS], 4, 128, name="text-only"))
+    full_parity(W.custom_prompt([("I", 333)], [D, S, I, IS], 1, 128, name="image-only"))
+    full_parity(W.custom_prompt([("I", 333)], [D, S, I, IS], 1, 128, sink_mode="prefix", sink_len=0,
+                                name="image-only-nosink"))
+
+
+def test_empty_rows_give_zeros():
+    # image first, no sink anywhere: Sink-head image rows of the first image have no allowed key
+    p = W.custom_prompt([("I", 200), ("T", 10), ("I", 150)], [S, IS], 1, 128, sink_mode="prefix",
+                        name="empty-rows")
+    q, k, v = W.make_qkv(p, 0, DEV)
+    out, tm = run_prefill(p, q, k, v)
+    assert tm.stats(S)["empty_rows"] == 200
+    assert torch.all(out[0, :200] == 0)
+    want = oracle_rows(p, q, k, v)
+    for h in range(2):
+        assert_close(out[h].float().cpu().numpy(), want[h], "bf16", f"head {h}")
+
+
+def test_many_small_images():
+    rng = np.random.default_rng(5)
+    runs = [("T", 3)]
+    for _ in range(40):
+        runs += [("I", int(rng.integers(1, 90))), ("T", int(rng.integers(0, 6)))]
+    p = W.custom_prompt(runs, [S, I, IS, D, I, IS], 3, 128, sink_len=2, name="many-small")
+    full_parity(p, seed=6)
+
+
+def test_rows_sum_to_one_and_uniform_closed_form_config2():
+    """Properties that hold at any size, on every row of the 36K configuration."""
+    p = W.config(2)
+    q, k, v = W.make_qkv(p, 0, DEV)
+    out, tm = run_prefill(p, q, k, torch.ones_like(v), None)
+    assert torch.all((out.float() - 1.0).abs() <= 2 ** -8), "rows do not sum to one"
+    out0, _ = run_prefill(p, torch.zeros_like(q), k, v, tm)
+    want = uniform_attention_closed_form(p, v.float().cpu().numpy())
+    for h in range(p.n_q_heads):
+        assert_close(out0[h].float().cpu().numpy(), want[h], "bf16", f"uniform head {h}")
+
+
+def sampled_parity(p, seed, n_random, max_tiles, row_step):
+    q, k, v = W.make_qkv(p, seed, DEV)
+    out, tm = run_prefill(p, q, k, v)
+    tiles = W.sample_q_tiles(p, 128, n_random=n_random, seed=seed, max_tiles=max_tiles)
+    rows = rows_of_tiles(p, tiles, row_step)
+    print(p.name, "L", p.seq_len, "rows checked", len(rows), flush=True)
+    want = oracle_rows(p, q.float().cpu().numpy(), k.float().cpu().numpy(), v.float().cpu().numpy(), rows)
+    got = out[:, torch.from_numpy(rows).long().to(out.device)].float().cpu().numpy()
+    worst = (0.0, 0.0)
+    for h in range(p.n_q_heads):
+        e = assert_close(got[h], want[h], p.dtype, f"{p.name} head {h} class {p.head_class[h]}")
+        worst = (max(worst[0], e[0]), max(worst[1], e[1]))
+    print("worst max_abs %.3e rel_l2 %.3e" % worst, flush=True)
+    return out, tm
+
+
+@pytest.mark.parametrize("sink_mode", ["paper10", "prefix"])
+def test_config2_sampled_rows(sink_mode):
+    sampled_parity(W.config(2, 0, sink_mode), 0, n_random=4, max_tiles=12, row_step=4)
+
+
+def test_config2_all_dense_sampled_rows():
+    sampled_parity(W.config(2).all_dense(), 1, n_random=2, max_tiles=6, row_step=8)
+
+
+def test_config3_sampled_rows():
+    sampled_parity(W.config(3), 0, n_random=2, max_tiles=8, row_step=16)
+
+
+def test_config4_sampled_rows():
+    sampled_parity(W.config(4), 0, n_random=2, max_tiles=8, row_step=32)
+
+
+def test_config5_stress_72k_sampled_rows():
+    sampled_parity(W.config(5, target_len=W.STRESS_LENGTHS[1]), 0, n_random=2, max_tiles=8, row_step=16)
+
+
+def test_determinism_and_tilemap_reuse():
+    p = W.config(2)
+    q, k, v = W.make_qkv(p, 2, DEV)
+    a, tm = run_prefill(p, q, k, v)
+    b, _ = run_prefill(p, q, k, v, tm)
+    assert torch.equal(a, b)
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        c, _ = run_prefill(p, q, k, v, tm, s.cuda_stream)
+    assert torch.equal(a, c)

@@ -1,0 +1,185 @@
+"""Host logic of the library: the tile map must equal the oracle's element-wise mask reduced to
+tiles, bit for bit (SKIP / PARTIAL / FULL), and its pair counts must equal the oracle's
+enumeration.  Mask definition: paper Sec. 3.2; per-tile metadata: App. kernel, Notation."""
+import ctypes
+import re
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+import workloads as W
+import paper_2507_09071_amd as bs
+from paper_2507_09071_amd import binding
+from golden_masks import all_fixtures, load
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def check_against_oracle(spans, L, sink_len, bm, bn, q_tiles=None, pairs=True):
+    tm = bs.bs_build_tilemap(spans, L, np.zeros(1, np.uint8), sink_len, bm, bn)
+    imgid, issink = oracle.token_arrays(spans, L, sink_len)
+    for c in range(4):
+        if q_tiles is None:
+            want = oracle.tile_states(c, imgid, issink, bm, bn)
+            got = tm.tile_states(c)
+        else:
+            want = oracle.tile_states(c, imgid, issink, bm, bn, q_tiles)
+            got = np.stack([tm.tile_states(c, int(m), 1)[0] for m in q_tiles])
+        assert np.array_equal(got, want), (c, np.argwhere(got != want)[:5])
+        st = tm.stats(c)
+        if q_tiles is None:
+            assert st["visited"] == int((want > 0).sum())
+            assert st["full"] == int((want == 2).sum())
+            assert st["partial"] == int((want == 1).sum())
+        if pairs:
+            assert st["allowed_pairs"] == oracle.pair_count(c, imgid, issink)
+            m = None
+            if L <= 2048:
+                m = oracle.mask(c, imgid, issink)
+                assert st["empty_rows"] == int((~m.any(axis=1)).sum())
+    return tm
+
+
+@pytest.mark.parametrize("path", all_fixtures())
+@pytest.mark.parametrize("bm,bn", [(1, 1), (2, 2), (4, 2), (3, 5)])
+def test_golden_prompts_small_tiles(path, bm, bn):
+    L, spans, sink_len, _ = load(path)
+    check_against_oracle(spans, L, sink_len, bm, bn)
+
+
+@pytest.mark.parametrize("seed", range(40))
+def test_random_prompts_small_tiles(seed):
+    rng = np.random.default_rng(seed)
+    runs = []
+    for _ in range(int(rng.integers(1, 8))):
+        runs.append(("T", int(rng.integers(0, 14))))
+        runs.append(("I", int(rng.integers(1, 40))))
+        if rng.random() < 0.3:   # adjacent images, no text between
+            runs.append(("I", int(rng.integers(1, 20))))
+    runs.append(("T", int(rng.integers(0, 10))))
+    mode = ["prefix", "paper10"][seed % 2]
+    span_sink = [None, None, 3, 1000][seed % 4]
+    L, spans = W.layout_from_runs(runs, mode, span_sink)
+    if L == 0:
+        return
+    sink_len = int(rng.integers(0, min(L, 12) + 1))
+    bm, bn = [(8, 4), (16, 8), (4, 4), (8, 16), (32, 16)][seed % 5]
+    check_against_oracle(spans, L, sink_len, bm, bn)
+
+
+@pytest.mark.parametrize("mode,span_sink", [("prefix", None), ("paper10", None), ("prefix", 32), ("prefix", 256)])
+def test_tiny_config_full(mode, span_sink):
+    p = W.tiny_config(mode, span_sink)
+    check_against_oracle(p.spans, p.seq_len, p.sink_len, 128, 64)
+
+
+def test_text_only_and_image_only_prompts():
+    check_against_oracle(np.zeros((0, 3), np.int32), 300, 0, 128, 64)
+    check_against_oracle(np.array([[0, 300, 0]], np.int32), 300, 0, 128, 64)
+    check_against_oracle(np.array([[0, 300, 30]], np.int32), 300, 0, 128, 64)
+    check_against_oracle(np.array([[0, 300, 300]], np.int32), 300, 300, 128, 64)
+    check_against_oracle(np.array([[0, 1, 0], [1, 2, 1], [2, 3, 0]], np.int32), 3, 0, 128, 64)
+
+
+@pytest.mark.parametrize("cfg", [2, 3, 4, 5])
+def test_large_configs_sampled_query_tiles(cfg):
+    p = W.config(cfg, seed=0, sink_mode="paper10", target_len=W.STRESS_LENGTHS[1])
+    q_tiles = W.sample_q_tiles(p, 128, n_random=4, seed=cfg, max_tiles=14)
+    tm = check_against_oracle(p.spans, p.seq_len, p.sink_len, 128, 64, q_tiles, pairs=(cfg in (2, 5)))
+    assert tm.n_q_tiles == -(-p.seq_len // 128) and tm.n_k_tiles == -(-p.seq_len // 64)
+
+
+def test_config2_prefix_mode_full_map():
+    p = W.config(2, seed=1, sink_mode="prefix")
+    check_against_oracle(p.spans, p.seq_len, p.sink_len, 128, 64)
+
+
+def test_states_do_not_depend_on_head_classes():
+    p = W.config(2)
+    a = bs.bs_build_tilemap(p.spans, p.seq_len, p.head_class, p.sink_len)
+    b = bs.bs_build_tilemap(p.spans, p.seq_len, np.zeros_like(p.head_class), p.sink_len)
+    for c in range(4):
+        assert np.array_equal(a.tile_states(c, 100, 20), b.tile_states(c, 100, 20))
+        assert a.stats(c) == b.stats(c)
+
+
+# ------------------------------------------------------------------------- error behaviour
+
+def _raw_build(spans, n_spans, L, hc, nh, sink_len, bm, bn, out):
+    return binding.load_library().bs_build_tilemap(spans, n_spans, L, hc, nh, sink_len, bm, bn, out)
+
+
+def test_build_rejects_bad_arguments():
+    lib = binding.load_library()
+    hc = (ctypes.c_uint8 * 2)(0, 3)
+    sp = (binding._Span * 2)(binding._Span(0, 4, 1), binding._Span(6, 9, 0))
+    out = ctypes.c_void_p()
+    ok = lambda: _raw_build(sp, 2, 16, hc, 2, 0, 128, 64, ctypes.byref(out))
+    assert ok() == 0
+    lib.bs_tilemap_destroy(out)
+    out = ctypes.c_void_p()
+    EINVAL = -1
+    assert _raw_build(sp, 2, 16, hc, 2, 0, 128, 64, None) == EINVAL
+    assert _raw_build(None, 2, 16, hc, 2, 0, 128, 64, ctypes.byref(out)) == EINVAL
+    assert _raw_build(sp, 2, 16, None, 2, 0, 128, 64, ctypes.byref(out)) == EINVAL
+    assert _raw_build(sp, 2, 0, hc, 2, 0, 128, 64, ctypes.byref(out)) == EINVAL
+    assert _raw_build(sp, 2, 8, hc, 2, 0, 128, 64, ctypes.byref(out)) == EINVAL      # span beyond L
+    assert _raw_build(sp, 2, 16, hc, 2, 17, 128, 64, ctypes.byref(out)) == EINVAL    # sink_len > L
+    assert _raw_build(sp, 2, 16, hc, 2, -1, 128, 64, ctypes.byref(out)) == EINVAL
+    assert _raw_build(sp, 2, 16, hc, 2, 0, 0, 64, ctypes.byref(out)) == EINVAL
+    assert _raw_build(sp, 2, 16, hc, 0, 0, 128, 64, ctypes.byref(out)) == EINVAL
+    bad_cls = (ctypes.c_uint8 * 2)(0, 4)
+    assert _raw_build(sp, 2, 16, bad_cls, 2, 0, 128, 64, ctypes.byref(out)) == EINVAL
+    for a, b in [((4, 4, 0), (6, 9, 0)), ((0, 7, 0), (6, 9, 0)), ((6, 9, 0), (0, 4, 0)),
+                 ((0, 4, 5), (6, 9, 0)), ((0, 4, -1), (6, 9, 0))]:
+        bad = (binding._Span * 2)(binding._Span(*a), binding._Span(*b))
+        assert _raw_build(bad, 2, 16, hc, 2, 0, 128, 64, ctypes.byref(out)) == EINVAL
+    assert out.value is None     # untouched on failure
+    with pytest.raises(bs.BlindsightError):
+        bs.bs_build_tilemap([(0, 99, 0)], 16, [0])
+
+
+def test_introspection_rejects_bad_arguments():
+    lib = binding.load_library()
+    tm = bs.bs_build_tilemap([(2, 9, 1)], 300, [0, 1])
+    buf = (ctypes.c_uint8 * (tm.n_q_tiles * tm.n_k_tiles))()
+    assert lib.bs_tilemap_tile_states(tm.handle, 4, 0, 1, buf) == -1
+    assert lib.bs_tilemap_tile_states(tm.handle, 0, 0, tm.n_q_tiles + 1, buf) == -1
+    assert lib.bs_tilemap_tile_states(tm.handle, 0, -1, 1, buf) == -1
+    assert lib.bs_tilemap_tile_states(tm.handle, 0, 0, 1, None) == -1
+    assert lib.bs_tilemap_stats(None, 0, None, None, None, None, None, None) == -1
+    assert lib.bs_tilemap_stats(tm.handle, 7, None, None, None, None, None, None) == -1
+    assert lib.bs_tilemap_stats(tm.handle, 0, None, None, None, None, None, None) == 0
+    assert lib.bs_tilemap_dims(None, None, None, None, None) == -1
+    lib.bs_tilemap_destroy(None)
+    for code in (0, -1, -2, -3, -4, -99):
+        assert isinstance(lib.bs_strerror(code), bytes) and lib.bs_strerror(code)
+
+
+def test_attn_prefill_argument_checks_need_no_gpu():
+    """Argument validation happens before any HIP call."""
+    lib = binding.load_library()
+    tm = bs.bs_build_tilemap([(2, 9, 1)], 300, [0, 1])
+    small = bs.bs_build_tilemap([(2, 9, 1)], 300, [0, 1], 0, 64, 64)
+    one = ctypes.c_void_p(256)
+    f = lambda *a: lib.bs_attn_prefill(*a)
+    assert f(None, one, one, one, tm.handle, 0, 2, 2, 128, 0.1, None) == -1
+    assert f(one, one, one, one, None, 0, 2, 2, 128, 0.1, None) == -1
+    assert f(one, one, one, one, tm.handle, 0, 3, 2, 128, 0.1, None) == -1      # heads % group
+    assert f(one, one, one, one, tm.handle, 0, 4, 2, 128, 0.1, None) == -1      # map built for 2 heads
+    assert f(one, one, one, one, tm.handle, 0, 2, 2, 128, 0.0, None) == -1      # scale must be > 0
+    assert f(one, one, one, one, tm.handle, 0, 2, 2, 96, 0.1, None) == -2
+    assert f(one, one, one, one, tm.handle, 5, 2, 2, 128, 0.1, None) == -2
+    assert f(one, one, one, one, small.handle, 0, 2, 2, 128, 0.1, None) == -2   # 64x64 map
+    assert f(ctypes.c_void_p(260), one, one, one, tm.handle, 0, 2, 2, 128, 0.1, None) == -1  # alignment
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "blindsight.h")).read()
+    declared = set(re.findall(r"\b(bs_[a-z_]+)\s*\(", header))
+    assert declared == set(binding.EXPORTS)
+    lib = ctypes.CDLL(bs.library_path())
+    for name in declared:
+        assert getattr(lib, name) is not None
