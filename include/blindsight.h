@@ -125,6 +125,10 @@ int bs_attn_prefill(const void *q, const void *k, const void *v, void *out, bs_t
 /* Static description of an error code. */
 const char *bs_strerror(int code);
 
+/* Detail of the most recent BS_EHIP / BS_ENOMEM failure on the calling thread (the HIP call
+ * that failed and its error string); "" if none.  The pointer stays valid for the thread's life. */
+const char *bs_last_error(void);
+
 #ifdef __cplusplus
 }
 #endif

@@ -18,13 +18,14 @@ BS_BF16, BS_F32 = 0, 1
 DENSE, SINK, INTRA, INTRA_SINK = 0, 1, 2, 3
 
 EXPORTS = ("bs_build_tilemap", "bs_tilemap_destroy", "bs_tilemap_dims", "bs_tilemap_tile_states",
-           "bs_tilemap_stats", "bs_tilemap_upload", "bs_attn_prefill", "bs_strerror")
+           "bs_tilemap_stats", "bs_tilemap_upload", "bs_attn_prefill", "bs_strerror", "bs_last_error")
 
 
 class BlindsightError(RuntimeError):
     def __init__(self, code: int, where: str):
         self.code = code
-        super().__init__(f"{where}: {_strerror(code)} ({code})")
+        detail = load_library().bs_last_error().decode() if code in (-3, -4) else ""
+        super().__init__(f"{where}: {_strerror(code)} ({code})" + (f" [{detail}]" if detail else ""))
 
 
 class _Span(ctypes.Structure):
@@ -32,6 +33,20 @@ class _Span(ctypes.Structure):
 
 
 _lib = None
+
+
+def _preload_process_hip_runtime():
+    """One process must use ONE HIP runtime.  PyTorch ships its own libamdhip64; callers hand us
+    device pointers and streams that belong to it, so load that copy first (by path) and let the
+    dynamic linker resolve our library's libamdhip64 dependency to it by soname.  Without PyTorch
+    the system runtime under /opt/rocm is used."""
+    import importlib.util
+    spec = importlib.util.find_spec("torch")
+    if spec is None or not spec.origin:
+        return
+    cand = os.path.join(os.path.dirname(spec.origin), "lib", "libamdhip64.so")
+    if os.path.exists(cand):
+        ctypes.CDLL(cand, mode=ctypes.RTLD_GLOBAL)
 
 
 def library_path() -> str:
@@ -44,6 +59,7 @@ def load_library():
         return _lib
     if not os.path.exists(_build.LIB):
         _build.build(verbose=False)
+    _preload_process_hip_runtime()
     lib = ctypes.CDLL(_build.LIB)
     i32, i64p = ctypes.c_int32, ctypes.POINTER(ctypes.c_int64)
     i32p, u8p, vp = ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_uint8), ctypes.c_void_p
@@ -64,6 +80,8 @@ def load_library():
     lib.bs_attn_prefill.restype = ctypes.c_int
     lib.bs_strerror.argtypes = [ctypes.c_int]
     lib.bs_strerror.restype = ctypes.c_char_p
+    lib.bs_last_error.argtypes = []
+    lib.bs_last_error.restype = ctypes.c_char_p
     _lib = lib
     return lib
 

@@ -17,6 +17,7 @@
 #include <stdint.h>
 
 #include <algorithm>
+#include <cstdio>
 #include <cstring>
 #include <new>
 #include <vector>
@@ -24,6 +25,16 @@
 #include "tilemap_internal.h"
 
 namespace bs {
+
+// Detail of the last failure on this thread, for bs_last_error().
+thread_local char g_last_error[256] = "";
+
+static int fail_hip(hipError_t e, const char *what)
+{
+    snprintf(g_last_error, sizeof g_last_error, "%s: %s (%d)", what, hipGetErrorString(e), (int)e);
+    (void)hipGetLastError();
+    return e == hipErrorOutOfMemory ? BS_ENOMEM : BS_EHIP;
+}
 
 struct DeviceMap {
     int device = -1;
@@ -441,7 +452,8 @@ extern "C" int bs_tilemap_upload(bs_tilemap *tm)
     if (!tm) return BS_EINVAL;
     if (tm->dev) return BS_OK;
     int dev = -1;
-    if (hipGetDevice(&dev) != hipSuccess) return BS_EHIP;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return bs::fail_hip(e, "hipGetDevice");
 
     const int64_t M1 = (int64_t)tm->M + 1;
     int64_t total_ranges = 0;
@@ -479,17 +491,16 @@ extern "C" int bs_tilemap_upload(bs_tilemap *tm)
     std::memcpy(host.data() + off_class, tm->head_class.data(), tm->head_class.size());
 
     void *blob = nullptr;
-    hipError_t e = hipMalloc(&blob, bytes);
+    e = hipMalloc(&blob, bytes);
     if (e != hipSuccess) {
         delete d;
-        (void)hipGetLastError();
-        return e == hipErrorOutOfMemory ? BS_ENOMEM : BS_EHIP;
+        return bs::fail_hip(e, "hipMalloc(tile map)");
     }
-    if (hipMemcpy(blob, host.data(), bytes, hipMemcpyHostToDevice) != hipSuccess) {
+    e = hipMemcpy(blob, host.data(), bytes, hipMemcpyHostToDevice);
+    if (e != hipSuccess) {
         (void)hipFree(blob);
         delete d;
-        (void)hipGetLastError();
-        return BS_EHIP;
+        return bs::fail_hip(e, "hipMemcpy(tile map)");
     }
     unsigned char *b = static_cast<unsigned char *>(blob);
     d->device = dev;
@@ -522,7 +533,8 @@ extern "C" int bs_attn_prefill(const void *q, const void *k, const void *v, void
     if (rc != BS_OK) return rc;
     const DeviceMap *d = tm->dev;
     int dev = -1;
-    if (hipGetDevice(&dev) != hipSuccess) return BS_EHIP;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return bs::fail_hip(e, "hipGetDevice");
     if (dev != d->device) return BS_EINVAL;  // the map lives on another device
 
     bs::KernelArgs a;
@@ -540,17 +552,18 @@ extern "C" int bs_attn_prefill(const void *q, const void *k, const void *v, void
     } else {
         if (head_dim == 128) {
             constexpr size_t lds = bs::f32_lds_bytes<128>();
-            if (hipFuncSetAttribute(reinterpret_cast<const void *>(bs::attn_prefill_f32<128>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
-                (void)hipGetLastError();
-                return BS_EHIP;
-            }
+            e = hipFuncSetAttribute(reinterpret_cast<const void *>(bs::attn_prefill_f32<128>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+            if (e != hipSuccess) return bs::fail_hip(e, "hipFuncSetAttribute");
             hipLaunchKernelGGL(bs::attn_prefill_f32<128>, grid, block, lds, st, a);
         } else {
             constexpr size_t lds = bs::f32_lds_bytes<64>();
             hipLaunchKernelGGL(bs::attn_prefill_f32<64>, grid, block, lds, st, a);
         }
     }
-    if (hipGetLastError() != hipSuccess) return BS_EHIP;
+    e = hipGetLastError();
+    if (e != hipSuccess) return bs::fail_hip(e, "kernel launch");
     return BS_OK;
 }
+
+extern "C" const char *bs_last_error(void) { return bs::g_last_error; }
