@@ -8,11 +8,19 @@
 // element predicate (PARTIAL) or not (FULL).  One softmax runs per row over the union of all
 // visited keys, and the output is divided by the running sum at the end.
 //
-// Mapping to CDNA4: a workgroup of four 64-lane waves owns one 128-row query tile of one head;
-// wave w owns rows 32w..32w+31.  Scores are produced transposed, S^T = K Q^T, with 32x32 MFMA
-// tiles so that every lane holds 16 keys of ONE query per 32-key block: row max / row sum are
-// in-lane reductions plus a single exchange with the lane 32 apart.  O^T = V^T P^T reuses the
-// score registers as the B operand after rounding to bf16; V is transposed on its way into LDS.
+// Mapping to CDNA4:
+//  * a workgroup of four 64-lane waves owns one 128-row query tile of one head; wave w owns
+//    rows 32w..32w+31 and keeps its Q rows in registers for the whole pass;
+//  * scores are produced transposed, S^T = K Q^T, with 32x32x16 bf16 MFMA tiles, so every lane
+//    holds 16 keys of ONE query per 32-key block: row max / row sum are in-lane reductions plus
+//    one exchange with the lane 32 apart (v_permlane32_swap);
+//  * O^T = V^T P^T reuses the score registers, rounded to bf16, as the B operand;
+//  * K and V tiles travel global -> LDS with 16-byte LDS-direct loads (no VGPR staging) into a
+//    two-stage ring, one barrier per tile; rows are unpadded and XOR-swizzled so both the
+//    128-bit K fragment reads and the 64-bit transposing V reads (ds_read_b64_tr_b16) are free
+//    of bank conflicts;
+//  * PARTIAL tiles build one 64-bit allowed-key word per lane from per-tile text/sink bit
+//    masks, the query's own image range and the causal bound, then test one bit per score.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -38,28 +46,37 @@ static int fail_hip(hipError_t e, const char *what)
 
 struct DeviceMap {
     int device = -1;
-    void *blob = nullptr;            // one allocation holding everything below
-    const uint32_t *code = nullptr;  // [L]
-    const int32_t *row_ptr = nullptr;  // [4][M+1] offsets into ranges
-    const int2 *ranges = nullptr;    // concatenated over classes
-    const int2 *work = nullptr;      // [n_work] (head, q_tile)
+    void *blob = nullptr;                 // one allocation holding everything below
+    const uint32_t *code = nullptr;       // [L] per-token code
+    const uint64_t *text_bits = nullptr;  // [N] text keys of each key tile
+    const uint64_t *sink_bits = nullptr;  // [N] sink keys of each key tile
+    const int2 *span_range = nullptr;     // [G+1] (start, end) by imgid; entry 0 unused
+    const int32_t *row_ptr = nullptr;     // [4][M+1] offsets into ranges
+    const int2 *ranges = nullptr;         // concatenated over classes
+    const int2 *work = nullptr;           // [n_work] (head, q_tile)
     const uint8_t *head_class = nullptr;  // [Hq]
     int32_t n_work = 0;
 };
 
+// Read-only tile-map arrays; passed as separate __restrict__ kernel parameters so that loads
+// with wave-uniform addresses go through the scalar cache (they then never wait on the vector
+// memory counter that tracks the in-flight LDS-direct loads).
 struct KernelArgs {
     const void *q, *k, *v;
     void *out;
-    const uint32_t *code;
-    const int32_t *row_ptr;
-    const int2 *ranges;
-    const int2 *work;
-    const uint8_t *head_class;
     int32_t L, M, G;
     float scale_log2e;  // scale * log2(e): softmax runs in the exp2 domain
 };
+#define BS_MAP_PARAMS                                                                              \
+    const uint32_t *__restrict__ map_code, const uint64_t *__restrict__ map_text_bits,             \
+        const uint64_t *__restrict__ map_sink_bits, const int2 *__restrict__ map_span_range,       \
+        const int32_t *__restrict__ map_row_ptr, const int2 *__restrict__ map_ranges,              \
+        const int2 *__restrict__ map_work, const uint8_t *__restrict__ map_head_class
+#define BS_MAP_ARGS(d) (d)->code, (d)->text_bits, (d)->sink_bits, (d)->span_range, (d)->row_ptr, (d)->ranges, (d)->work, (d)->head_class
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef short shortx4 __attribute__((ext_vector_type(4)));
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 
@@ -67,17 +84,26 @@ constexpr int kBlockM = 128, kBlockN = 64, kThreads = 256;
 
 // Walks the key tiles of one (class, query tile): ranges of [begin, end) with a FULL flag.
 struct TileWalker {
-    const int2 *rg;
+    const int2 *__restrict__ rg;
     int p, p_end, n, n_end;
     bool full;
     __device__ void load()
     {
         if (p < p_end) {
-            int2 r = rg[p];
-            n = r.x; n_end = r.y >> 1; full = r.y & 1;
+            // wave-uniform by construction; say so, so the loads go through the scalar cache
+            const int2 r = rg[__builtin_amdgcn_readfirstlane(p)];
+            n = __builtin_amdgcn_readfirstlane(r.x);
+            n_end = __builtin_amdgcn_readfirstlane(r.y) >> 1;
+            full = __builtin_amdgcn_readfirstlane(r.y) & 1;
         }
     }
-    __device__ void init(const int2 *ranges, int begin, int end) { rg = ranges; p = begin; p_end = end; load(); }
+    __device__ void init(const int2 *__restrict__ ranges, int begin, int end)
+    {
+        rg = ranges;
+        p = __builtin_amdgcn_readfirstlane(begin);
+        p_end = __builtin_amdgcn_readfirstlane(end);
+        load();
+    }
     __device__ bool valid() const { return p < p_end; }
     __device__ void next()
     {
@@ -85,85 +111,141 @@ struct TileWalker {
     }
 };
 
-// Per-lane view of the query this lane's score column belongs to.
-struct QueryPred {
-    uint32_t kmask;  // key code bits that make a key visible regardless of image
-    uint32_t img;    // image id that own-image keys must match (never matches when disabled)
-    int32_t row;     // query position i
-    __device__ void init(uint32_t qcode, int cls, int32_t i)
+// What the lane's query may see (paper Sec. 3.2), in a form that is cheap to apply per tile.
+struct QueryView {
+    int32_t row;       // query position i
+    int32_t own_lo;    // own image [own_lo, own_hi) if the class attends inside images, else empty
+    int32_t own_hi;
+    bool sees_all;     // text query or Dense head: every earlier key
+    __device__ void init(const uint32_t *__restrict__ code, const int2 *__restrict__ span_range, int L, int cls, int32_t i)
     {
         row = i;
-        const bool sees_all = (qcode & kCodeText) || cls == BS_DENSE;
-        kmask = sees_all ? 0xffffffffu : (kCodeText | ((cls & 1) ? kCodeSink : 0u));
-        img = (!sees_all && (cls & 2)) ? (qcode & kCodeImgMask) : 0x7fffffffu;
-    }
-    __device__ bool allowed(uint32_t kcode, int32_t j) const
-    {
-        return j <= row && (((kcode & kmask) != 0u) || ((kcode & kCodeImgMask) == img));
+        const uint32_t qcode = i < L ? code[i] : kCodeText;
+        sees_all = (qcode & kCodeText) || cls == BS_DENSE;
+        own_lo = own_hi = 0;
+        if (!sees_all && (cls & 2)) {
+            const int2 sp = span_range[qcode & kCodeImgMask];
+            own_lo = sp.x; own_hi = sp.y;
+        }
     }
 };
 
-// Online-softmax update for one 32-query x 64-key score block held as two 32x32 C tiles.
-// Lane (hl = lane/32, col = lane%32) holds, for query col, keys 32*kb + 8*(v/4) + 4*hl + v%4.
-// On return s[][] holds p = exp2(s*c - m*c); m is the running max (raw score units), l the
-// lane's partial running sum; alpha is the factor the output accumulators must be scaled by.
-__device__ inline void softmax_block(floatx16 (&s)[2], float &m_run, float &l_run, float &alpha, float c)
+__device__ inline uint64_t bits_below(int x)  // bits [0, x), x in [0, 64]
 {
-    float mx = s[0][0];
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) mx = fmaxf(mx, s[kb][v]);
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
-    const float m_new = fmaxf(m_run, mx);
-    const float m_use = (m_new == -INFINITY) ? 0.f : m_new;  // row fully masked so far: p = 0
-    const float mc = m_use * c;
-    alpha = exp2f(m_run * c - mc);  // m_run = -inf -> 0
-    float sum = 0.f;
+    return x >= 64 ? ~0ull : ((1ull << x) - 1ull);
+}
+
+// Bit b set <=> key n0 + b is allowed for this lane's query.  tbits / sbits: text keys and
+// (class-enabled) sink keys of the tile.
+__device__ inline uint64_t allowed_keys(const QueryView &qv, uint64_t tbits, uint64_t sbits, int n0)
+{
+    const uint64_t base = qv.sees_all ? ~0ull : (tbits | sbits);
+    const int lo = min(max(qv.own_lo - n0, 0), 64), hi = min(max(qv.own_hi - n0, 0), 64);
+    const uint64_t own = bits_below(hi) & ~bits_below(lo);
+    const int cz = min(max(qv.row - n0 + 1, 0), 64);  // causal: keys n0 .. row
+    return (base | own) & bits_below(cz);
+}
+
+// Score block layout (two 32x32 MFMA C tiles): lane (hl = lane/32, col = lane%32) holds, for
+// query col, keys 32*kb + 8*(v/4) + 4*hl + v%4, v = 0..15.
+__device__ inline void apply_mask(floatx16 (&s)[2], uint64_t allowed, int hl)
+{
+    const uint32_t w[2] = {(uint32_t)allowed >> (4 * hl), (uint32_t)(allowed >> 32) >> (4 * hl)};
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
-            float p = exp2f(fmaf(s[kb][v], c, -mc));
-            s[kb][v] = p;
-            sum += p;
+            const uint32_t bit = 1u << (8 * (v / 4) + (v % 4));
+            s[kb][v] = (w[kb] & bit) ? s[kb][v] : -INFINITY;
         }
-    l_run = l_run * alpha + sum;
+}
+
+__device__ inline float max_across_halves(float x)
+{
+    // r[0] = (x.lo, x.lo), r[1] = (x.hi, x.hi): both halves see both values
+    auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+
+__device__ inline float sum_across_halves(float x)
+{
+    auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(x), __float_as_uint(x), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+// Online-softmax update (running max m, running sum l, rescale factor alpha; App. kernel
+// Alg. 4) in the exp2 domain: p = exp2(s*c - m*c).  l is the lane's partial sum (its 32 keys);
+// the halves are added once, in the epilogue.  MAY_BE_EMPTY guards rows with no allowed key
+// so far (m = -inf), which only PARTIAL tiles can produce.
+template <bool MAY_BE_EMPTY>
+__device__ inline void softmax_block(floatx16 (&s)[2], float &m_run, float &l_run, float &alpha, float c)
+{
+    float mx = fmaxf(s[0][0], s[0][1]);
+#pragma unroll
+    for (int v = 2; v < 16; v += 2) mx = fmaxf(fmaxf(mx, s[0][v]), s[0][v + 1]);
+#pragma unroll
+    for (int v = 0; v < 16; v += 2) mx = fmaxf(fmaxf(mx, s[1][v]), s[1][v + 1]);
+    mx = max_across_halves(mx);
+    const float m_new = fmaxf(m_run, mx);
+    const float m_use = (MAY_BE_EMPTY && m_new == -INFINITY) ? 0.f : m_new;
+    const float mc = m_use * c;
+    alpha = __builtin_amdgcn_exp2f(fmaf(m_run, c, -mc));  // m_run = -inf -> 0
+    float sum0 = 0.f, sum1 = 0.f;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+        const float p0 = __builtin_amdgcn_exp2f(fmaf(s[0][v], c, -mc));
+        const float p1 = __builtin_amdgcn_exp2f(fmaf(s[1][v], c, -mc));
+        s[0][v] = p0; s[1][v] = p1;
+        sum0 += p0; sum1 += p1;
+    }
+    l_run = fmaf(l_run, alpha, sum0 + sum1);
     m_run = m_new;
 }
 
-// Apply the element predicate to a PARTIAL tile.  lds_code holds the 64 key codes of the tile.
-__device__ inline void mask_block(floatx16 (&s)[2], const QueryPred &qp, const uint32_t *lds_code, int n0, int hl)
+typedef __attribute__((address_space(3))) void *lds_void_ptr;
+
+// 64-bit transposing LDS read: within each group of 16 lanes, lane i receives element i%4 of
+// the 8-byte words addressed by lanes i/4, 4 + i/4, 8 + i/4, 12 + i/4.  Issued through inline
+// asm so the compiler does not tie it to the in-flight LDS-direct loads of the other ring
+// stage; the caller waits on lgkmcnt with lds_wait<N>() before using the result.
+template <int OFFSET>
+__device__ inline shortx4 lds_read_tr16(uint32_t addr)
 {
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            const int key = 32 * kb + 8 * g + 4 * hl;
-            const uint4 kc = *reinterpret_cast<const uint4 *>(lds_code + key);
-            const uint32_t kcs[4] = {kc.x, kc.y, kc.z, kc.w};
-#pragma unroll
-            for (int r = 0; r < 4; ++r)
-                if (!qp.allowed(kcs[r], n0 + key + r)) s[kb][4 * g + r] = -INFINITY;
-        }
+    shortx4 r;
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(OFFSET));
+    return r;
 }
+
+// Wait until at most N LDS operations are outstanding; the operands tie the wait to the
+// registers it protects so their consumers cannot be scheduled above it.
+template <int N>
+__device__ inline void lds_wait(shortx4 (&a)[8])
+{
+    asm volatile("s_waitcnt lgkmcnt(%8)"
+                 : "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]), "+v"(a[4]), "+v"(a[5]), "+v"(a[6]), "+v"(a[7])
+                 : "n"(N));
+}
+typedef const __attribute__((address_space(1))) void *global_void_ptr;
 
 // ------------------------------------------------------------------------------------ bf16
 
-template <int D>
-__global__ __launch_bounds__(kThreads, 2) void attn_prefill_bf16(KernelArgs a)
-{
-    constexpr int KS = D * 2 + 16;       // K row stride in LDS (bytes): 16 B pad kills bank conflicts
-    constexpr int VS = kBlockN * 2 + 16; // V^T row stride in LDS (bytes)
-    constexpr int KCH = D / 8;           // 16-byte chunks per K row
-    constexpr int K_PER_THREAD = kBlockN * KCH / kThreads;
-    __shared__ __align__(16) unsigned char lds_k[kBlockN * KS];
-    __shared__ __align__(16) unsigned char lds_v[D * VS];
-    __shared__ __align__(16) uint32_t lds_code[kBlockN];
+// LDS swizzles: row r of a tile stores its logical 16-byte chunk c at chunk c ^ f(r).
+template <int D> __device__ inline int k_swizzle(int row) { return D == 128 ? (row & 15) : ((row >> 1) & 7); }
+template <int D> __device__ inline int v_swizzle(int row) { return D == 128 ? ((row & 3) << 2) : (((row >> 1) & 1) << 2); }
 
-    const int2 item = a.work[blockIdx.x];
+template <int D>
+__global__ __launch_bounds__(kThreads, 2) void attn_prefill_bf16(KernelArgs a, BS_MAP_PARAMS)
+{
+    constexpr int ROW = D * 2;            // bytes per K / V row in LDS
+    constexpr int TILE = kBlockN * ROW;   // bytes per K or V tile
+    constexpr int STAGE = 2 * TILE;       // K tile then V tile
+    constexpr int CPR = D / 8;            // 16-byte chunks per row
+    constexpr int DMA_PER_THREAD = D / 32;  // LDS-direct loads per thread per matrix per tile
+    __shared__ __align__(1024) unsigned char lds[2 * STAGE];
+
+    const int2 item = map_work[blockIdx.x];
     const int head = item.x, m = item.y;
-    const int cls = a.head_class[head];
+    const int cls = map_head_class[head];
     const int kvh = head / a.G;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hl = lane >> 5, col = lane & 31;
     const int L = a.L;
@@ -175,14 +257,29 @@ __global__ __launch_bounds__(kThreads, 2) void attn_prefill_bf16(KernelArgs a)
 
     // Q^T operand: lane holds Q[row][16t + 8hl .. +8] for every 16-wide slice t of the head dim.
     bf16x8 qreg[D / 16];
+    {
+        const int qrow = min(row, L - 1);  // rows past the end compute on a copy and are not stored
 #pragma unroll
-    for (int t = 0; t < D / 16; ++t) {
-        uint4 raw = make_uint4(0, 0, 0, 0);
-        if (row < L) raw = *reinterpret_cast<const uint4 *>(qh + (size_t)row * D + 16 * t + 8 * hl);
-        qreg[t] = __builtin_bit_cast(bf16x8, raw);
+        for (int t = 0; t < D / 16; ++t)
+            qreg[t] = *reinterpret_cast<const bf16x8 *>(qh + (size_t)qrow * D + 16 * t + 8 * hl);
     }
-    QueryPred qp;
-    qp.init(row < L ? a.code[row] : kCodeText, cls, row);
+    QueryView qv;
+    qv.init(map_code, map_span_range, a.L, cls, row);
+
+    // LDS byte offsets of this lane's MFMA operand fragments (loop invariant).
+    //   K fragment t: row col (+32 kb), logical chunk 2t + hl.
+    //   V fragment (transposing read, per 16-lane group: 4 keys x 16 channels): lane j of the
+    //   group addresses key j/4 of the group's 4 keys and channels 4(j%4)..+3 of its 16.
+    int koff[D / 16];
+#pragma unroll
+    for (int t = 0; t < D / 16; ++t) koff[t] = col * ROW + (((2 * t + hl) ^ k_swizzle<D>(col)) << 4);
+    int voff[D / 32];
+    {
+        const int j = lane & 15, g16 = (lane >> 4) & 1, key = 4 * hl + (j >> 2);
+#pragma unroll
+        for (int db = 0; db < D / 32; ++db)
+            voff[db] = key * ROW + (((4 * db + 2 * g16 + ((j & 3) >> 1)) ^ v_swizzle<D>(key)) << 4) + 8 * (j & 1);
+    }
 
     floatx16 o[D / 32];
 #pragma unroll
@@ -192,89 +289,52 @@ __global__ __launch_bounds__(kThreads, 2) void attn_prefill_bf16(KernelArgs a)
     float m_run = -INFINITY, l_run = 0.f;
 
     TileWalker tw;
-    tw.init(a.ranges, a.row_ptr[cls * (a.M + 1) + m], a.row_ptr[cls * (a.M + 1) + m + 1]);
+    tw.init(map_ranges, map_row_ptr[cls * (a.M + 1) + m], map_row_ptr[cls * (a.M + 1) + m + 1]);
 
-    // register staging of the next tile's K / V / codes (global -> regs -> LDS)
-    uint4 kst[K_PER_THREAD];
-    uint4 vst[4];
-    uint32_t cst = 0;
-    // V task of this thread: 4 consecutive keys (quad x) x 8 consecutive channels (group y)
-    const int vx = (tid >> 2) & 15, vy = (tid & 3) + 4 * (tid >> 6);
-    const bool v_task = vy < D / 8;
-
-    auto fetch = [&](int n) {
+    // Start the LDS-direct loads of key tile n into ring stage `stage`.  Each wave instruction
+    // fills 1 KB of contiguous LDS (lane l -> bytes 16l..16l+15); the swizzle is applied on the
+    // global side by choosing which chunk of the row each lane fetches.
+    auto issue = [&](int n, int stage) {
         const int n0 = n * kBlockN;
 #pragma unroll
-        for (int r = 0; r < K_PER_THREAD; ++r) {
-            const int idx = tid + kThreads * r, key = idx / KCH, ch = idx % KCH;
-            kst[r] = make_uint4(0, 0, 0, 0);
-            if (n0 + key < L) kst[r] = *reinterpret_cast<const uint4 *>(kh + (size_t)(n0 + key) * D + ch * 8);
+        for (int r = 0; r < DMA_PER_THREAD; ++r) {
+            const int blk = r * 4 + wave;
+            const int qd = blk * 64 + lane;
+            const int trow = qd / CPR, cp = qd % CPR;
+            const int grow = min(n0 + trow, L - 1);  // keys past the end are masked by causality
+            const __bf16 *ksrc = kh + (size_t)grow * D + ((cp ^ k_swizzle<D>(trow)) << 3);
+            const __bf16 *vsrc = vh + (size_t)grow * D + ((cp ^ v_swizzle<D>(trow)) << 3);
+            unsigned char *kdst = lds + stage * STAGE + blk * 1024;
+            __builtin_amdgcn_global_load_lds((global_void_ptr)ksrc, (lds_void_ptr)kdst, 16, 0, 0);
+            __builtin_amdgcn_global_load_lds((global_void_ptr)vsrc, (lds_void_ptr)(kdst + TILE), 16, 0, 0);
         }
-        if (v_task) {
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int key = 4 * vx + r;
-                vst[r] = make_uint4(0, 0, 0, 0);
-                if (n0 + key < L) vst[r] = *reinterpret_cast<const uint4 *>(vh + (size_t)(n0 + key) * D + vy * 8);
-            }
-        }
-        if (tid < kBlockN) cst = (n0 + tid < L) ? a.code[n0 + tid] : 0u;
-    };
-    auto stage = [&]() {
-#pragma unroll
-        for (int r = 0; r < K_PER_THREAD; ++r) {
-            const int idx = tid + kThreads * r, key = idx / KCH, ch = idx % KCH;
-            *reinterpret_cast<uint4 *>(lds_k + key * KS + ch * 16) = kst[r];
-        }
-        if (v_task) {
-            // 4 keys x 8 channels -> 8 channels x 4 keys; keys of a 16-group are laid out
-            // [0..3, 8..11 | 4..7, 12..15] so each lane half reads its 8 MFMA slots as one 16 B word.
-            const int colb = 32 * (vx >> 2) + 16 * (vx & 1) + 8 * ((vx & 3) >> 1);
-            const uint32_t w[4][4] = {{vst[0].x, vst[0].y, vst[0].z, vst[0].w},
-                                      {vst[1].x, vst[1].y, vst[1].z, vst[1].w},
-                                      {vst[2].x, vst[2].y, vst[2].z, vst[2].w},
-                                      {vst[3].x, vst[3].y, vst[3].z, vst[3].w}};
-#pragma unroll
-            for (int pr = 0; pr < 4; ++pr) {
-                // channel 2pr (low halves) and 2pr+1 (high halves)
-                uint2 lo, hi;
-                lo.x = __builtin_amdgcn_perm(w[1][pr], w[0][pr], 0x05040100u);
-                lo.y = __builtin_amdgcn_perm(w[3][pr], w[2][pr], 0x05040100u);
-                hi.x = __builtin_amdgcn_perm(w[1][pr], w[0][pr], 0x07060302u);
-                hi.y = __builtin_amdgcn_perm(w[3][pr], w[2][pr], 0x07060302u);
-                *reinterpret_cast<uint2 *>(lds_v + (8 * vy + 2 * pr) * VS + colb) = lo;
-                *reinterpret_cast<uint2 *>(lds_v + (8 * vy + 2 * pr + 1) * VS + colb) = hi;
-            }
-        }
-        if (tid < kBlockN) lds_code[tid] = cst;
     };
 
-    if (tw.valid()) fetch(tw.n);
-    while (tw.valid()) {
-        const int n = tw.n;
-        const bool full = tw.full;
-        __syncthreads();  // previous tile's LDS reads are done
-        stage();
-        __syncthreads();
-        tw.next();
-        if (tw.valid()) fetch(tw.n);  // in flight while this tile is computed
-
+    auto compute = [&](int n, bool full, const unsigned char *kt, const uint32_t vt_addr) {
         // S^T = K Q^T
         floatx16 s[2];
 #pragma unroll
-        for (int kb = 0; kb < 2; ++kb) {
+        for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
             for (int v = 0; v < 16; ++v) s[kb][v] = 0.f;
 #pragma unroll
-            for (int t = 0; t < D / 16; ++t) {
-                const bf16x8 ka = *reinterpret_cast<const bf16x8 *>(lds_k + (32 * kb + col) * KS + (16 * t + 8 * hl) * 2);
+        for (int t = 0; t < D / 16; ++t)
+#pragma unroll
+            for (int kb = 0; kb < 2; ++kb) {
+                const bf16x8 ka = *reinterpret_cast<const bf16x8 *>(kt + koff[t] + kb * 32 * ROW);
                 s[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qreg[t], s[kb], 0, 0, 0);
             }
-        }
-        if (!full) mask_block(s, qp, lds_code, n * kBlockN, hl);
 
         float alpha;
-        softmax_block(s, m_run, l_run, alpha, a.scale_log2e);
+        if (full) {
+            softmax_block<false>(s, m_run, l_run, alpha, a.scale_log2e);
+        } else {
+            const int nu = __builtin_amdgcn_readfirstlane(n);
+            const uint64_t tb = map_text_bits[nu];
+            const uint64_t sb = (cls & 1) ? map_sink_bits[nu] : 0ull;
+            apply_mask(s, allowed_keys(qv, tb, sb, n * kBlockN), hl);
+            softmax_block<true>(s, m_run, l_run, alpha, a.scale_log2e);
+        }
         if (__any(alpha != 1.f)) {
 #pragma unroll
             for (int db = 0; db < D / 32; ++db)
@@ -282,7 +342,8 @@ __global__ __launch_bounds__(kThreads, 2) void attn_prefill_bf16(KernelArgs a)
                 for (int v = 0; v < 16; ++v) o[db][v] *= alpha;
         }
 
-        // P^T as bf16 B operands: slots e of MFMA (kb, t) are C values v = 8t + e
+        // P^T as bf16 B operands: contraction slots e = 0..7 of MFMA (kb, t) are C values
+        // v = 8t + e, i.e. keys 32kb + 16t + {4hl..4hl+3, 8+4hl..8+4hl+3}
         bf16x8 pf[2][2];
 #pragma unroll
         for (int kb = 0; kb < 2; ++kb)
@@ -291,20 +352,65 @@ __global__ __launch_bounds__(kThreads, 2) void attn_prefill_bf16(KernelArgs a)
 #pragma unroll
                 for (int e = 0; e < 8; ++e) pf[kb][t][e] = (__bf16)s[kb][8 * t + e];
 
-        // O^T += V^T P^T
+        // O^T += V^T P^T.  The A operand of MFMA (kb, t, db) is gathered by two transposing
+        // 64-bit LDS reads; reads of group g+1 = (kb, t) are in flight while group g multiplies.
+        shortx4 vf[2][8];
+        auto read_group = [&](int g, shortx4 (&dst)[8]) {
 #pragma unroll
-        for (int db = 0; db < D / 32; ++db)
+            for (int db = 0; db < D / 32; ++db) {
+                const uint32_t addr = vt_addr + voff[db];
+                if (g == 0) { dst[2 * db] = lds_read_tr16<0 * 16 * ROW>(addr); dst[2 * db + 1] = lds_read_tr16<0 * 16 * ROW + 8 * ROW>(addr); }
+                if (g == 1) { dst[2 * db] = lds_read_tr16<1 * 16 * ROW>(addr); dst[2 * db + 1] = lds_read_tr16<1 * 16 * ROW + 8 * ROW>(addr); }
+                if (g == 2) { dst[2 * db] = lds_read_tr16<2 * 16 * ROW>(addr); dst[2 * db + 1] = lds_read_tr16<2 * 16 * ROW + 8 * ROW>(addr); }
+                if (g == 3) { dst[2 * db] = lds_read_tr16<3 * 16 * ROW>(addr); dst[2 * db + 1] = lds_read_tr16<3 * 16 * ROW + 8 * ROW>(addr); }
+            }
+        };
+        read_group(0, vf[0]);
 #pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
+        for (int g = 0; g < 4; ++g) {
+            if (g < 3) {
+                read_group(g + 1, vf[(g + 1) & 1]);
+                lds_wait<2 * (D / 32)>(vf[g & 1]);
+            } else {
+                lds_wait<0>(vf[g & 1]);
+            }
 #pragma unroll
-                for (int t = 0; t < 2; ++t) {
-                    const bf16x8 va = *reinterpret_cast<const bf16x8 *>(lds_v + (32 * db + col) * VS + 32 * (2 * kb + t) + 16 * hl);
-                    o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pf[kb][t], o[db], 0, 0, 0);
-                }
+            for (int db = 0; db < D / 32; ++db) {
+                const bf16x8 va = __builtin_bit_cast(
+                    bf16x8, __builtin_shufflevector(vf[g & 1][2 * db], vf[g & 1][2 * db + 1], 0, 1, 2, 3, 4, 5, 6, 7));
+                o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pf[g >> 1][g & 1], o[db], 0, 0, 0);
+            }
+        }
+    };
+
+    const uint32_t lds_base = (uint32_t)(uintptr_t)(lds_void_ptr)lds;  // LDS byte address of the ring
+    // Two-stage ring, one barrier per tile: after the barrier of step i every wave has finished
+    // computing tile i-1, so its stage can be refilled with tile i+1 while tile i is computed.
+    if (tw.valid()) issue(tw.n, 0);
+    while (tw.valid()) {
+        {
+            const int n = tw.n;
+            const bool full = tw.full;
+            __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): this wave's LDS-direct loads landed
+            __syncthreads();
+            tw.next();
+            if (tw.valid()) issue(tw.n, 1);
+            compute(n, full, lds, lds_base + TILE);
+        }
+        if (!tw.valid()) break;
+        {
+            const int n = tw.n;
+            const bool full = tw.full;
+            __builtin_amdgcn_s_waitcnt(0x0f70);
+            __syncthreads();
+            tw.next();
+            if (tw.valid()) issue(tw.n, 0);
+            compute(n, full, lds + STAGE, lds_base + STAGE + TILE);
+        }
     }
 
     // epilogue: divide by the running sum, round, store.  Empty rows (l = 0) give zeros.
-    const float l_tot = l_run + __shfl_xor(l_run, 32);
+    const float l_tot = sum_across_halves(l_run);
     const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
     if (row < L) {
         __bf16 *orow = reinterpret_cast<__bf16 *>(a.out) + ((size_t)head * L + row) * D;
@@ -312,7 +418,6 @@ __global__ __launch_bounds__(kThreads, 2) void attn_prefill_bf16(KernelArgs a)
         for (int db = 0; db < D / 32; ++db)
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
-                typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
                 bf16x4 w;
 #pragma unroll
                 for (int r = 0; r < 4; ++r) w[r] = (__bf16)(o[db][4 * g + r] * inv);
@@ -323,20 +428,19 @@ __global__ __launch_bounds__(kThreads, 2) void attn_prefill_bf16(KernelArgs a)
 
 // ------------------------------------------------------------------------------------ fp32
 // Same structure with fp32 MFMA (32x32x2) end to end; P stays fp32.  Parity path for fp32
-// inputs, not tuned.  Dynamic LDS: K[64][D+1] floats, V[64][D+8] floats, 64 codes.
+// inputs, not tuned.  Dynamic LDS: K[64][D+1] floats, V[64][D+8] floats.
 
 template <int D>
-__global__ __launch_bounds__(kThreads, 1) void attn_prefill_f32(KernelArgs a)
+__global__ __launch_bounds__(kThreads, 1) void attn_prefill_f32(KernelArgs a, BS_MAP_PARAMS)
 {
     constexpr int KS = D + 1, VS = D + 8;
     extern __shared__ __align__(16) unsigned char smem[];
     float *lds_k = reinterpret_cast<float *>(smem);
     float *lds_v = lds_k + kBlockN * KS;
-    uint32_t *lds_code = reinterpret_cast<uint32_t *>(lds_v + kBlockN * VS);
 
-    const int2 item = a.work[blockIdx.x];
+    const int2 item = map_work[blockIdx.x];
     const int head = item.x, m = item.y;
-    const int cls = a.head_class[head];
+    const int cls = map_head_class[head];
     const int kvh = head / a.G;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hl = lane >> 5, col = lane & 31;
     const int L = a.L;
@@ -347,10 +451,13 @@ __global__ __launch_bounds__(kThreads, 1) void attn_prefill_f32(KernelArgs a)
     const float *vh = reinterpret_cast<const float *>(a.v) + (size_t)kvh * L * D;
 
     float qreg[D / 2];  // Q[row][2t + hl]
+    {
+        const int qrow = min(row, L - 1);
 #pragma unroll
-    for (int t = 0; t < D / 2; ++t) qreg[t] = row < L ? qh[(size_t)row * D + 2 * t + hl] : 0.f;
-    QueryPred qp;
-    qp.init(row < L ? a.code[row] : kCodeText, cls, row);
+        for (int t = 0; t < D / 2; ++t) qreg[t] = qh[(size_t)qrow * D + 2 * t + hl];
+    }
+    QueryView qv;
+    qv.init(map_code, map_span_range, a.L, cls, row);
 
     floatx16 o[D / 32];
 #pragma unroll
@@ -360,25 +467,22 @@ __global__ __launch_bounds__(kThreads, 1) void attn_prefill_f32(KernelArgs a)
     float m_run = -INFINITY, l_run = 0.f;
 
     TileWalker tw;
-    tw.init(a.ranges, a.row_ptr[cls * (a.M + 1) + m], a.row_ptr[cls * (a.M + 1) + m + 1]);
+    tw.init(map_ranges, map_row_ptr[cls * (a.M + 1) + m], map_row_ptr[cls * (a.M + 1) + m + 1]);
 
     for (; tw.valid(); tw.next()) {
         const int n0 = tw.n * kBlockN;
         __syncthreads();
         for (int idx = tid; idx < kBlockN * (D / 4); idx += kThreads) {
             const int key = idx / (D / 4), ch = idx % (D / 4);
-            floatx4 kk = {0.f, 0.f, 0.f, 0.f}, vv = {0.f, 0.f, 0.f, 0.f};
-            if (n0 + key < L) {
-                kk = *reinterpret_cast<const floatx4 *>(kh + (size_t)(n0 + key) * D + ch * 4);
-                vv = *reinterpret_cast<const floatx4 *>(vh + (size_t)(n0 + key) * D + ch * 4);
-            }
+            const int grow = min(n0 + key, L - 1);
+            const floatx4 kk = *reinterpret_cast<const floatx4 *>(kh + (size_t)grow * D + ch * 4);
+            const floatx4 vv = *reinterpret_cast<const floatx4 *>(vh + (size_t)grow * D + ch * 4);
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 lds_k[key * KS + ch * 4 + r] = kk[r];
                 lds_v[key * VS + ch * 4 + r] = vv[r];
             }
         }
-        if (tid < kBlockN) lds_code[tid] = (n0 + tid < L) ? a.code[n0 + tid] : 0u;
         __syncthreads();
 
         floatx16 s[2];
@@ -390,10 +494,15 @@ __global__ __launch_bounds__(kThreads, 1) void attn_prefill_f32(KernelArgs a)
             for (int t = 0; t < D / 2; ++t)
                 s[kb] = __builtin_amdgcn_mfma_f32_32x32x2f32(lds_k[(32 * kb + col) * KS + 2 * t + hl], qreg[t], s[kb], 0, 0, 0);
         }
-        if (!tw.full) mask_block(s, qp, lds_code, n0, hl);
-
         float alpha;
-        softmax_block(s, m_run, l_run, alpha, a.scale_log2e);
+        if (tw.full) {
+            softmax_block<false>(s, m_run, l_run, alpha, a.scale_log2e);
+        } else {
+            const uint64_t tb = map_text_bits[tw.n];
+            const uint64_t sb = (cls & 1) ? map_sink_bits[tw.n] : 0ull;
+            apply_mask(s, allowed_keys(qv, tb, sb, n0), hl);
+            softmax_block<true>(s, m_run, l_run, alpha, a.scale_log2e);
+        }
 #pragma unroll
         for (int db = 0; db < D / 32; ++db)
 #pragma unroll
@@ -411,7 +520,7 @@ __global__ __launch_bounds__(kThreads, 1) void attn_prefill_f32(KernelArgs a)
                 }
     }
 
-    const float l_tot = l_run + __shfl_xor(l_run, 32);
+    const float l_tot = sum_across_halves(l_run);
     const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
     if (row < L) {
         float *orow = reinterpret_cast<float *>(a.out) + ((size_t)head * L + row) * D;
@@ -428,7 +537,7 @@ __global__ __launch_bounds__(kThreads, 1) void attn_prefill_f32(KernelArgs a)
 }
 
 template <int D>
-constexpr size_t f32_lds_bytes() { return (size_t)kBlockN * (D + 1) * 4 + (size_t)kBlockN * (D + 8) * 4 + kBlockN * 4; }
+constexpr size_t f32_lds_bytes() { return (size_t)kBlockN * (D + 1) * 4 + (size_t)kBlockN * (D + 8) * 4; }
 
 void free_device_map(DeviceMap *d)
 {
@@ -451,6 +560,7 @@ extern "C" int bs_tilemap_upload(bs_tilemap *tm)
 {
     if (!tm) return BS_EINVAL;
     if (tm->dev) return BS_OK;
+    if (tm->bn > 64) return BS_EUNSUPPORTED;  // the per-tile key bit masks are 64 wide
     int dev = -1;
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return bs::fail_hip(e, "hipGetDevice");
@@ -459,10 +569,14 @@ extern "C" int bs_tilemap_upload(bs_tilemap *tm)
     int64_t total_ranges = 0;
     for (int c = 0; c < 4; ++c) total_ranges += (int64_t)tm->cls[c].ranges.size();
     if (total_ranges >= INT32_MAX) return BS_EUNSUPPORTED;
+    const size_t G1 = tm->spans.size() + 1;
 
     auto align = [](size_t x) { return (x + 255) & ~(size_t)255; };
     const size_t off_code = 0;
-    const size_t off_rowptr = align(off_code + (size_t)tm->L * 4);
+    const size_t off_tbits = align(off_code + (size_t)tm->L * 4);
+    const size_t off_sbits = align(off_tbits + (size_t)tm->N * 8);
+    const size_t off_spans = align(off_sbits + (size_t)tm->N * 8);
+    const size_t off_rowptr = align(off_spans + G1 * 8);
     const size_t off_ranges = align(off_rowptr + (size_t)(4 * M1) * 4);
     const size_t off_work = align(off_ranges + (size_t)std::max<int64_t>(total_ranges, 1) * 8);
     const size_t off_class = align(off_work + tm->work.size() * 8);
@@ -477,6 +591,11 @@ extern "C" int bs_tilemap_upload(bs_tilemap *tm)
         return BS_ENOMEM;
     }
     std::memcpy(host.data() + off_code, tm->code.data(), (size_t)tm->L * 4);
+    std::memcpy(host.data() + off_tbits, tm->text_bits.data(), (size_t)tm->N * 8);
+    std::memcpy(host.data() + off_sbits, tm->sink_bits.data(), (size_t)tm->N * 8);
+    int2 *sp = reinterpret_cast<int2 *>(host.data() + off_spans);
+    sp[0] = make_int2(0, 0);
+    for (size_t g = 0; g < tm->spans.size(); ++g) sp[g + 1] = make_int2(tm->spans[g].start, tm->spans[g].end);
     int32_t *rp = reinterpret_cast<int32_t *>(host.data() + off_rowptr);
     int2 *rg = reinterpret_cast<int2 *>(host.data() + off_ranges);
     int64_t base = 0;
@@ -506,6 +625,9 @@ extern "C" int bs_tilemap_upload(bs_tilemap *tm)
     d->device = dev;
     d->blob = blob;
     d->code = reinterpret_cast<const uint32_t *>(b + off_code);
+    d->text_bits = reinterpret_cast<const uint64_t *>(b + off_tbits);
+    d->sink_bits = reinterpret_cast<const uint64_t *>(b + off_sbits);
+    d->span_range = reinterpret_cast<const int2 *>(b + off_spans);
     d->row_ptr = reinterpret_cast<const int32_t *>(b + off_rowptr);
     d->ranges = reinterpret_cast<const int2 *>(b + off_ranges);
     d->work = reinterpret_cast<const int2 *>(b + off_work);
@@ -539,26 +661,24 @@ extern "C" int bs_attn_prefill(const void *q, const void *k, const void *v, void
 
     bs::KernelArgs a;
     a.q = q; a.k = k; a.v = v; a.out = out;
-    a.code = d->code; a.row_ptr = d->row_ptr; a.ranges = d->ranges; a.work = d->work;
-    a.head_class = d->head_class;
     a.L = tm->L; a.M = tm->M; a.G = gqa_group;
     a.scale_log2e = scale * 1.4426950408889634f;
 
     hipStream_t st = static_cast<hipStream_t>(stream);
     const dim3 grid((unsigned)d->n_work), block(bs::kThreads);
     if (dtype == BS_BF16) {
-        if (head_dim == 128) hipLaunchKernelGGL(bs::attn_prefill_bf16<128>, grid, block, 0, st, a);
-        else hipLaunchKernelGGL(bs::attn_prefill_bf16<64>, grid, block, 0, st, a);
+        if (head_dim == 128) hipLaunchKernelGGL(bs::attn_prefill_bf16<128>, grid, block, 0, st, a, BS_MAP_ARGS(d));
+        else hipLaunchKernelGGL(bs::attn_prefill_bf16<64>, grid, block, 0, st, a, BS_MAP_ARGS(d));
     } else {
         if (head_dim == 128) {
             constexpr size_t lds = bs::f32_lds_bytes<128>();
             e = hipFuncSetAttribute(reinterpret_cast<const void *>(bs::attn_prefill_f32<128>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
             if (e != hipSuccess) return bs::fail_hip(e, "hipFuncSetAttribute");
-            hipLaunchKernelGGL(bs::attn_prefill_f32<128>, grid, block, lds, st, a);
+            hipLaunchKernelGGL(bs::attn_prefill_f32<128>, grid, block, lds, st, a, BS_MAP_ARGS(d));
         } else {
             constexpr size_t lds = bs::f32_lds_bytes<64>();
-            hipLaunchKernelGGL(bs::attn_prefill_f32<64>, grid, block, lds, st, a);
+            hipLaunchKernelGGL(bs::attn_prefill_f32<64>, grid, block, lds, st, a, BS_MAP_ARGS(d));
         }
     }
     e = hipGetLastError();

@@ -237,6 +237,17 @@ extern "C" int bs_build_tilemap(const bs_span *spans, int32_t n_spans, int32_t s
                 tm->code[t] = c;
             }
 
+        // per-key-tile bit masks for the kernel's 64-wide element predicate
+        if (block_n <= 64) {
+            tm->text_bits.assign(tm->N, 0);
+            tm->sink_bits.assign(tm->N, 0);
+            for (int32_t t = 0; t < L; ++t) {
+                const uint64_t bit = 1ull << (t % block_n);
+                if (tm->code[t] & bs::kCodeText) tm->text_bits[t / block_n] |= bit;
+                if (tm->code[t] & bs::kCodeSink) tm->sink_bits[t / block_n] |= bit;
+            }
+        }
+
         Geometry G;
         G.L = L; G.bm = block_m; G.bn = block_n; G.M = tm->M; G.N = tm->N; G.spans = &tm->spans;
         G.n_text.assign(L + 1, 0);

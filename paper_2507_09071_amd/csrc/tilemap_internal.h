@@ -39,6 +39,8 @@ struct bs_tilemap {
     std::vector<bs_span> spans;
     std::vector<uint8_t> head_class;
     std::vector<uint32_t> code;            // L
+    std::vector<uint64_t> text_bits;       // N: bit b of entry n = key n*bn + b is a text key (bn <= 64 only)
+    std::vector<uint64_t> sink_bits;       // N: same for sink keys
     bs::ClassLists cls[4];
     std::vector<bs::WorkItem> work;        // n_q_heads * M items, heaviest first
     bs::DeviceMap *dev = nullptr;          // created lazily by bs_tilemap_upload
