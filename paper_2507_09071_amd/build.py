@@ -23,7 +23,7 @@ def command(out: str = LIB, extra=()):
     return [hipcc(), "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
             "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
             "-Wall", "-Wno-unused-command-line-argument",
-            "-I", os.path.join(ROOT, "include"), "-I", CSRC, *extra,
+            "-I", os.path.join(ROOT, "include"), "-I", CSRC, *extra, *os.environ.get("BS_EXTRA_HIPCC_FLAGS", "").split(),
             "-o", out, *[os.path.join(CSRC, s) for s in SOURCES]]
 
 
