@@ -58,6 +58,8 @@ struct DeviceMap {
     const int2 *work = nullptr;           // [n_work] (head, q_tile)
     const uint8_t *head_class = nullptr;  // [Hq]
     int32_t n_work = 0;
+    void *vt_buf = nullptr;               // workspace: packed K and V^T tiles of the last bf16 call
+    size_t vt_bytes = 0;
 };
 
 // Read-only tile-map arrays; passed as separate __restrict__ kernel parameters so that loads
@@ -102,6 +104,7 @@ struct TileWalker {
     __device__ void init(const int2 *__restrict__ ranges, int begin, int end)
     {
         rg = ranges;
+        n = 0; n_end = 0; full = false;
         p = __builtin_amdgcn_readfirstlane(begin);
         p_end = __builtin_amdgcn_readfirstlane(end);
         load();
@@ -204,6 +207,48 @@ __device__ inline void softmax_block(floatx16 (&s)[2], float &m_run, float &l_ru
     m_run = m_new;
 }
 
+// Same update as softmax_block, but the scores are only read and the probabilities go straight
+// into the bf16 B operands of the P.V MFMAs: contraction slot e of MFMA group (kb, t) is score
+// v = 8t + e of block kb, i.e. key 32kb + 16t + {4hl..4hl+3, 8+4hl..8+4hl+3}[e].
+// `between(i)`, i = 0..7, is called at eight evenly spaced points of the exponential loop and
+// pinned there, so that the caller can spread its memory instructions over the vector work.
+template <bool MAY_BE_EMPTY, class Hook>
+__device__ inline void softmax_pack(const floatx16 (&s)[2], bf16x8 (&pf)[2][2], float &m_run, float &l_run,
+                                    float &alpha, float c, Hook &&between)
+{
+    // four independent max chains
+    float mx[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) mx[i] = fmaxf(s[i >> 1][8 * (i & 1)], s[i >> 1][8 * (i & 1) + 1]);
+#pragma unroll
+    for (int v = 2; v < 8; v += 2)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) mx[i] = fmaxf(fmaxf(mx[i], s[i >> 1][8 * (i & 1) + v]), s[i >> 1][8 * (i & 1) + v + 1]);
+    const float mxl = max_across_halves(fmaxf(fmaxf(mx[0], mx[1]), fmaxf(mx[2], mx[3])));
+    const float m_new = fmaxf(m_run, mxl);
+    const float m_use = (MAY_BE_EMPTY && m_new == -INFINITY) ? 0.f : m_new;
+    const float mc = m_use * c;
+    alpha = __builtin_amdgcn_exp2f(fmaf(m_run, c, -mc));  // m_run = -inf -> 0
+    float sum[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const float pv = __builtin_amdgcn_exp2f(fmaf(s[kb][8 * t + e], c, -mc));
+                sum[e & 3] += pv;
+                pf[kb][t][e] = (__bf16)pv;
+                if ((e & 3) == 3) {
+                    __builtin_amdgcn_sched_barrier(0);
+                    between(4 * kb + 2 * t + (e >> 2));
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+    l_run = fmaf(l_run, alpha, (sum[0] + sum[1]) + (sum[2] + sum[3]));
+    m_run = m_new;
+}
+
 typedef __attribute__((address_space(3))) void *lds_void_ptr;
 typedef const __attribute__((address_space(1))) void *global_void_ptr;
 
@@ -212,14 +257,6 @@ typedef const __attribute__((address_space(1))) void *global_void_ptr;
 // LDS operand reads of the MFMA phase are issued through inline asm and waited for by hand
 // (lds_wait<N>): the compiler would otherwise tie every LDS read to the LDS-direct loads that
 // are in flight into the other ring slot and drain the vector-memory counter before it.
-
-// 64-bit transposing LDS read: within each group of 16 lanes, lane i receives element i%4 of
-// the 8-byte words addressed by lanes i/4, 4 + i/4, 8 + i/4, 12 + i/4.
-template <int OFFSET>
-__device__ inline void lds_read_tr16(shortx4 &dst, uint32_t addr)
-{
-    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(OFFSET));
-}
 
 template <int OFFSET>
 __device__ inline void lds_read_b128(bf16x8 &dst, uint32_t addr)
@@ -230,26 +267,81 @@ __device__ inline void lds_read_b128(bf16x8 &dst, uint32_t addr)
 // Wait until at most N LDS operations are outstanding.  The operands tie the wait to the
 // registers it protects, so their consumers cannot be scheduled above it.
 template <int N>
-__device__ inline void lds_wait(shortx4 (&a)[8])
-{
-    asm volatile("s_waitcnt lgkmcnt(%8)"
-                 : "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]), "+v"(a[4]), "+v"(a[5]), "+v"(a[6]), "+v"(a[7])
-                 : "n"(N));
-}
-template <int N>
 __device__ inline void lds_wait(bf16x8 (&a)[4])
 {
     asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]) : "n"(N));
 }
 
-// LDS swizzles: row r of a tile stores its logical 16-byte chunk c at chunk c ^ f(r).
+
+// K tile swizzle: row r stores its logical 16-byte chunk c at chunk c ^ k_swizzle(r).
 template <int D> __device__ inline int k_swizzle(int row) { return D == 128 ? (row & 15) : ((row >> 1) & 7); }
-template <int D> __device__ inline int v_swizzle(int row) { return D == 128 ? ((row & 3) << 2) : (((row >> 1) & 1) << 2); }
+
+// V^T tile pack (pre-pass, HBM-bound): V[kvh][L][D] -> VT[kvh][n][D rows][64 keys], one
+// contiguous 128*D-byte block per key tile, laid out exactly as the attention kernel wants it
+// in LDS so that its LDS-direct loads are plain copies and every MFMA A operand of P.V is ONE
+// 128-bit read (a 64-bit transposing read moves half the bytes per LDS cycle):
+//   row d holds the tile's 64 keys as 8 chunks of 8 keys; logical chunk c = 2g + h holds keys
+//   16g + {4h..4h+3, 8+4h..8+4h+3} (the contraction slots of lane half h in MFMA group g);
+//   it is stored at chunk c ^ ((d >> 1) & 7), which spreads 16 consecutive rows over all banks.
+// Keys past the end of the prompt are zero-filled.
+template <int D>
+__global__ __launch_bounds__(256) void pack_vt_tiles(const __bf16 *__restrict__ v, __bf16 *__restrict__ vt, int L, int N)
+{
+    constexpr int PAD = D + 2;  // odd word stride: the column gathers below spread over banks
+    __shared__ __bf16 tile[kBlockN * PAD];
+    const int n = blockIdx.x, kvh = blockIdx.y, tid = threadIdx.x;
+    const __bf16 *src = v + ((size_t)kvh * L + (size_t)n * kBlockN) * D;
+    for (int idx = tid; idx < kBlockN * (D / 8); idx += 256) {
+        const int key = idx / (D / 8), ch = idx % (D / 8);
+        bf16x8 val;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) val[e] = (__bf16)0.f;
+        if (n * kBlockN + key < L) val = *reinterpret_cast<const bf16x8 *>(src + (size_t)key * D + ch * 8);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) tile[key * PAD + ch * 8 + e] = val[e];
+    }
+    __syncthreads();
+    __bf16 *dst = vt + ((size_t)kvh * N + n) * (size_t)(D * kBlockN);
+    for (int idx = tid; idx < D * 8; idx += 256) {
+        const int d = idx >> 3, cp = idx & 7;
+        const int c = cp ^ ((d >> 1) & 7);
+        const int g = c >> 1, h = c & 1;
+        bf16x8 val;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) val[e] = tile[(16 * g + 8 * (e >> 2) + 4 * h + (e & 3)) * PAD + d];
+        *reinterpret_cast<bf16x8 *>(dst + (size_t)d * kBlockN + cp * 8) = val;
+    }
+}
+
+// K tile pack (pre-pass, HBM-bound): K[kvh][L][D] -> KP[kvh][n][64 keys][D], one contiguous
+// 128*D-byte block per key tile in the attention kernel's LDS layout: row r stores its logical
+// 16-byte chunk c at chunk c ^ k_swizzle(r), so that the 128-bit K fragment reads of 16
+// consecutive rows fall on distinct banks.  Keys past the end of the prompt are zero-filled.
+template <int D>
+__global__ __launch_bounds__(256) void pack_k_tiles(const __bf16 *__restrict__ k, __bf16 *__restrict__ kp, int L, int N)
+{
+    constexpr int CPR = D / 8;
+    const int n = blockIdx.x, kvh = blockIdx.y;
+    const __bf16 *src = k + ((size_t)kvh * L + (size_t)n * kBlockN) * D;
+    __bf16 *dst = kp + ((size_t)kvh * N + n) * (size_t)(D * kBlockN);
+    for (int idx = threadIdx.x; idx < kBlockN * CPR; idx += 256) {
+        const int row = idx / CPR, cp = idx % CPR;
+        const int c = cp ^ k_swizzle<D>(row);
+        uint4 val = make_uint4(0, 0, 0, 0);
+        if (n * kBlockN + row < L) val = *reinterpret_cast<const uint4 *>(src + (size_t)row * D + c * 8);
+        *reinterpret_cast<uint4 *>(dst + (size_t)row * D + cp * 8) = val;
+    }
+}
 
 constexpr int kPingPongThreads = 512;
 
 // Optional phase timing (build with -DBS_PHASE_TIMING): wave 0 of every workgroup adds the
 // cycles it spent in phase X, the barrier after X, phase Y and the barrier after Y.
+#ifdef BS_PROBE_NO_BARRIER
+#define BS_LOOP_BARRIER() do {} while (0)
+#else
+#define BS_LOOP_BARRIER() __builtin_amdgcn_s_barrier()
+#endif
 #ifdef BS_PHASE_TIMING
 __device__ unsigned long long g_phase_cycles[8];
 __device__ inline unsigned long long bs_now(floatx16 &a, floatx16 &b, floatx16 &c)
@@ -291,11 +383,11 @@ constexpr int bf16_lds_bytes() { return 2 /*groups*/ * 4 /*2 K + 2 V slots*/ * k
 template <int D>
 __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(KernelArgs a, BS_MAP_PARAMS,
                                                                          const int32_t *__restrict__ map_row_tiles,
-                                                                         int32_t n_work)
+                                                                         int32_t n_work, const __bf16 *__restrict__ kp,
+                                                                         const __bf16 *__restrict__ vt, int32_t n_k_tiles)
 {
     constexpr int ROW = D * 2;            // bytes per K / V row in LDS
     constexpr int TILE = kBlockN * ROW;   // bytes per K or V tile
-    constexpr int CPR = D / 8;            // 16-byte chunks per row
     constexpr int DMA_PER_THREAD = D / 32;  // LDS-direct loads per thread per matrix per tile
     constexpr int NDB = D / 32;           // 32-channel blocks of the output
     constexpr int NT = D / 16;            // 16-wide slices of the head dim
@@ -331,8 +423,9 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(KernelA
     const int row = m * kBlockM + wave * 32 + col;
 
     const __bf16 *qh = reinterpret_cast<const __bf16 *>(a.q) + (size_t)head * L * D;
-    const __bf16 *kh = reinterpret_cast<const __bf16 *>(a.k) + (size_t)kvh * L * D;
-    const __bf16 *vh = reinterpret_cast<const __bf16 *>(a.v) + (size_t)kvh * L * D;
+    // packed K and V^T tiles of this KV head (one TILE-byte block per key tile)
+    const char *kph = reinterpret_cast<const char *>(kp + (size_t)kvh * n_k_tiles * (size_t)(D * kBlockN));
+    const char *vth = reinterpret_cast<const char *>(vt + (size_t)kvh * n_k_tiles * (size_t)(D * kBlockN));
 
     // Q^T operand: lane holds Q[row][16t + 8hl .. +8] for every 16-wide slice t of the head dim.
     bf16x8 qreg[NT];
@@ -346,19 +439,14 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(KernelA
     qv.init(map_code, map_span_range, L, cls, row);
 
     // LDS byte addresses of this lane's MFMA operand fragments inside the group's ring.
-    //   ring layout: K slot 0, K slot 1, V slot 0, V slot 1 (TILE bytes each)
-    //   K fragment t: row col (+32 kb), logical chunk 2t + hl
-    //   V fragment (transposing read, per 16-lane group: 4 keys x 16 channels): lane j of the
-    //   group addresses key j/4 of the group's 4 keys and channels 4(j%4)..+3 of its 16
+    //   ring layout: K slot 0, K slot 1, V^T slot 0, V^T slot 1 (TILE bytes each)
+    //   K fragment t: tile row col (+32 kb), logical chunk 2t + hl of the row's D/8 chunks
+    //   V^T fragment of MFMA group g: tile row 32db + col, logical chunk 2g + hl of 8
+    //   both swizzles only touch address bits that t / g also select, so the fragment sits at
+    //   the base address XOR (t << 5) resp. (g << 5); kb and db are immediate offsets
     const uint32_t ring = (uint32_t)(uintptr_t)(lds_void_ptr)lds + grp * 4 * TILE;
-    //   the swizzles only touch address bits that t (bits 5-7) and db (bits 6-7) also select,
-    //   so fragment t / block db sits at the base address XOR (t << 5) / (db << 6)
     const uint32_t kaddr0 = ring + col * ROW + ((hl ^ k_swizzle<D>(col)) << 4);
-    uint32_t vaddr0;
-    {
-        const int j = lane & 15, g16 = (lane >> 4) & 1, key = 4 * hl + (j >> 2);
-        vaddr0 = ring + 2 * TILE + key * ROW + (((2 * g16 + ((j & 3) >> 1)) ^ v_swizzle<D>(key)) << 4) + 8 * (j & 1);
-    }
+    const uint32_t vaddr0 = ring + 2 * TILE + col * 128 + ((hl ^ ((col >> 1) & 7)) << 4);
 
     floatx16 o[NDB];
 #pragma unroll
@@ -377,70 +465,62 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(KernelA
         for (int e = 0; e < 8; ++e) pf[i >> 1][i & 1][e] = (__bf16)0.f;
     float m_run = -INFINITY, l_run = 0.f;
 
-    // tile walkers: wk runs one tile ahead (K loads), wv names the tile of the current step
-    TileWalker wk, wv;
+    // three walkers over the item's tile list: w0 names the tile of the current step (mask and
+    // FULL flag), w1 the next tile (V^T refill), w2 the one after (K refill)
+    TileWalker w0, w1, w2;
     {
         const int rb = map_row_ptr[cls * (a.M + 1) + m], re = have_item ? map_row_ptr[cls * (a.M + 1) + m + 1] : rb;
-        wk.init(map_ranges, rb, re);
-        wv.init(map_ranges, rb, re);
+        w0.init(map_ranges, rb, re);
+        w1 = w0; if (w1.valid()) w1.next();
+        w2 = w1; if (w2.valid()) w2.next();
     }
 
-    // Start the LDS-direct loads of one K or V tile into a ring slot.  Each wave instruction
-    // fills 1 KB of contiguous LDS (lane l -> bytes 16l..16l+15), i.e. 1024/ROW tile rows; the
-    // swizzle is applied on the global side by choosing which chunk of the row a lane fetches.
-    // Instruction r of wave w covers tile rows (4r + w) * RPI + lane / CPR; neither swizzle
-    // depends on r, so one per-lane byte offset serves all r (the rest is scalar arithmetic).
-    constexpr int RPI = 1024 / ROW;  // tile rows per wave instruction
-    const int dma_row0 = wave * RPI + lane / CPR;
-    const int dma_cp = lane % CPR;
-    const uint32_t dma_off_k = dma_row0 * ROW + ((dma_cp ^ k_swizzle<D>(dma_row0)) << 4);
-    const uint32_t dma_off_v = dma_row0 * ROW + ((dma_cp ^ v_swizzle<D>(dma_row0)) << 4);
-    auto issue_tile = [&](const __bf16 *src, int n, int slot_byte, bool is_v) {
+    // LDS-direct loads of one packed tile into a ring slot: a straight TILE-byte copy.  Each
+    // wave instruction moves 1 KB (lane l -> bytes 16l..16l+15); instruction r of wave w covers
+    // bytes (4r + w) KB .. +1 KB of the tile.
+    const uint32_t dma_lane_off = wave * 1024 + lane * 16;
+    auto dma = [&](int r, const char *tile, int slot_byte) {
+        unsigned char *dst = lds + grp * 4 * TILE + slot_byte + wave * 1024 + r * 4 * 1024;
+        __builtin_amdgcn_global_load_lds((global_void_ptr)(tile + (dma_lane_off + r * 4 * 1024)), (lds_void_ptr)dst, 16, 0, 0);
+    };
+    auto tile_ptr = [&](const char *base, int n) {
 #ifdef BS_PROBE_SAME_TILE
         n = n & 7;
 #endif
-        const int n0 = n * kBlockN;
-        const char *tile = reinterpret_cast<const char *>(src) + (size_t)n0 * ROW;
-        unsigned char *dst0 = lds + grp * 4 * TILE + slot_byte + wave * 1024;
-        if (n0 + kBlockN <= L) {
-            const uint32_t off = is_v ? dma_off_v : dma_off_k;
-#pragma unroll
-            for (int r = 0; r < DMA_PER_THREAD; ++r)
-                __builtin_amdgcn_global_load_lds((global_void_ptr)(tile + (off + r * 4 * 1024)),
-                                                 (lds_void_ptr)(dst0 + r * 4 * 1024), 16, 0, 0);
-        } else {
-            // ragged last tile: rows past the end fetch the last row (masked by causality)
-            const int last = L - 1 - n0;
-#pragma unroll
-            for (int r = 0; r < DMA_PER_THREAD; ++r) {
-                const int trow = r * 4 * RPI + dma_row0;
-                const int sw = is_v ? v_swizzle<D>(trow) : k_swizzle<D>(trow);
-                const uint32_t off = min(trow, last) * ROW + ((dma_cp ^ sw) << 4);
-                __builtin_amdgcn_global_load_lds((global_void_ptr)(tile + off),
-                                                 (lds_void_ptr)(dst0 + r * 4 * 1024), 16, 0, 0);
-            }
-        }
+        return base + (size_t)min(n, n_k_tiles - 1) * TILE;  // a walker past its end names no tile
     };
 
-    // ---- phase X building blocks (PAR = parity of the step: K slot PAR, V slot PAR ^ 1) ----
-    auto read_pv = [&](auto par, auto g, shortx4 (&dst)[8]) {
-        constexpr int base = (decltype(par)::value ^ 1) * TILE + decltype(g)::value * 16 * ROW;
+    // ---- phase X building blocks (PAR = parity of the step: K slot PAR, V^T slot PAR ^ 1) ----
+    // A batch is four 128-bit operand reads feeding four MFMAs:
+    //   PV batch g (D = 128): O^T block db += V^T(db, group g) . P^T(group g), db = 0..3
+    //   S  batch b          : head-dim slices 2b, 2b+1 for both 32-key blocks
+    auto read_pv = [&](auto par, auto g, bf16x8 (&dst)[4]) {
+#ifdef BS_PROBE_NO_LDSREAD
+        return;
+#endif
+        constexpr int base = (decltype(par)::value ^ 1) * TILE;
+        const uint32_t addr = vaddr0 ^ (decltype(g)::value << 5);
 #pragma unroll
         for (int db = 0; db < NDB; ++db) {
-            lds_read_tr16<base>(dst[2 * db], vaddr0 ^ (db << 6));
-            lds_read_tr16<base + 8 * ROW>(dst[2 * db + 1], vaddr0 ^ (db << 6));
+            if (db == 0) lds_read_b128<base + 0 * 4096>(dst[0], addr);
+            if (db == 1) lds_read_b128<base + 1 * 4096>(dst[1], addr);
+            if (db == 2) lds_read_b128<base + 2 * 4096>(dst[2], addr);
+            if (db == 3) lds_read_b128<base + 3 * 4096>(dst[3], addr);
         }
     };
-    auto mul_pv = [&](auto g, shortx4 (&f)[8]) {
+    auto mul_pv = [&](auto g, bf16x8 (&f)[4]) {
+#ifdef BS_PROBE_NO_MFMA
+        return;
+#endif
         constexpr int G = decltype(g)::value;
 #pragma unroll
-        for (int db = 0; db < NDB; ++db) {
-            const bf16x8 va = __builtin_bit_cast(bf16x8, __builtin_shufflevector(f[2 * db], f[2 * db + 1], 0, 1, 2, 3, 4, 5, 6, 7));
-            o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pf[G >> 1][G & 1], o[db], 0, 0, 0);
-        }
+        for (int db = 0; db < NDB; ++db)
+            o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[db], pf[G >> 1][G & 1], o[db], 0, 0, 0);
     };
-    // S batch b covers head-dim slices 2b, 2b+1 for both 32-key blocks
     auto read_s = [&](auto par, auto b, bf16x8 (&dst)[4]) {
+#ifdef BS_PROBE_NO_LDSREAD
+        return;
+#endif
         constexpr int base = decltype(par)::value * TILE;
         constexpr int B = decltype(b)::value;
         lds_read_b128<base>(dst[0], kaddr0 ^ ((2 * B) << 5));
@@ -449,6 +529,9 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(KernelA
         lds_read_b128<base + 32 * ROW>(dst[3], kaddr0 ^ ((2 * B + 1) << 5));
     };
     auto mul_s = [&](auto b, bf16x8 (&f)[4]) {
+#ifdef BS_PROBE_NO_MFMA
+        return;
+#endif
         constexpr int B = decltype(b)::value;
         if (B == 0) {
             const floatx16 z = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
@@ -466,64 +549,85 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(KernelA
     using I2 = std::integral_constant<int, 2>;
     using I3 = std::integral_constant<int, 3>;
 
-    // Phase X of step k.  Always the same straight-line sequence, so the accumulators never
-    // move between registers: before the first tile P is zero (the V slots were zero-filled),
-    // after the last tile P is zero again and the scores it produces are ignored.  LDS reads
-    // run one batch ahead of the MFMAs that consume them; each lds_wait<N> count is the number
-    // of reads issued after the batch being waited for.  A batch's registers are refilled right
-    // after the MFMAs that read them have issued (operands are read at issue, LDS data returns
-    // later).
-    auto phase_x = [&](auto par, int k) {
-        // refill: K(k+1) -> K slot par^1 (last read in step k-1), V(k) -> V slot par (same)
-        if (k + 1 < T) issue_tile(kh, wk.n, (decltype(par)::value ^ 1) * TILE, false);
-        if (k < T) issue_tile(vh, wv.n, 2 * TILE + decltype(par)::value * TILE, true);
+    // Phase X of step k: O += P(k-1) V(k-1) and S(k) = K(k) Q^T.  Always the same straight-line sequence, so the accumulators never
+    // move between registers: before the first tile P is zero (the ring was zero-filled),
+    // after the last tile P is zero again and the scores it produces are ignored.  Operand
+    // reads run three batches ahead of the MFMAs that consume them, in three rotating register
+    // sets; each lds_wait<N> count is the number of reads issued after the batch waited for.
+    // A set is refilled right after the MFMAs that read it have issued (operands are read at
+    // issue, LDS data returns later).
+    auto phase_x = [&](auto par) {
 #ifdef BS_PROBE_NO_X
         return;
 #endif
-        shortx4 vf[8];
-        bf16x8 kf[4];
+        bf16x8 fa[4], fb[4], fc[4];
         if constexpr (NDB < 4) {
 #pragma unroll
-            for (int i = 2 * NDB; i < 8; ++i) vf[i] = shortx4{0, 0, 0, 0};
+            for (int i = NDB; i < 4; ++i)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) { fa[i][e] = (__bf16)0.f; fb[i][e] = (__bf16)0.f; fc[i][e] = (__bf16)0.f; }
         }
         if constexpr (D == 128) {
-            read_pv(par, I0{}, vf); read_s(par, I0{}, kf);
-            lds_wait<4>(vf); mul_pv(I0{}, vf); read_pv(par, I1{}, vf);
-            lds_wait<8>(kf); mul_s(I0{}, kf); read_s(par, I1{}, kf);
-            lds_wait<4>(vf); mul_pv(I1{}, vf); read_pv(par, I2{}, vf);
-            lds_wait<8>(kf); mul_s(I1{}, kf); read_s(par, I2{}, kf);
-            lds_wait<4>(vf); mul_pv(I2{}, vf); read_pv(par, I3{}, vf);
-            lds_wait<8>(kf); mul_s(I2{}, kf); read_s(par, I3{}, kf);
-            lds_wait<4>(vf); mul_pv(I3{}, vf);
-            lds_wait<0>(kf); mul_s(I3{}, kf);
-        } else {  // D == 64: PV batches hold 4 reads, S has 2 batches
-            read_pv(par, I0{}, vf); read_s(par, I0{}, kf);
-            lds_wait<4>(vf); mul_pv(I0{}, vf); read_pv(par, I1{}, vf);
-            lds_wait<4>(kf); mul_s(I0{}, kf); read_s(par, I1{}, kf);
-            lds_wait<4>(vf); mul_pv(I1{}, vf); read_pv(par, I2{}, vf);
-            lds_wait<4>(kf); mul_s(I1{}, kf);
-            lds_wait<0>(vf); mul_pv(I2{}, vf); read_pv(par, I3{}, vf);
-            lds_wait<0>(vf); mul_pv(I3{}, vf);
+            // batch order: PV0 S0 PV1 S1 PV2 S2 PV3 S3, four reads each
+            read_pv(par, I0{}, fa); read_s(par, I0{}, fb); read_pv(par, I1{}, fc);
+            lds_wait<8>(fa); mul_pv(I0{}, fa); read_s(par, I1{}, fa);
+            lds_wait<8>(fb); mul_s(I0{}, fb); read_pv(par, I2{}, fb);
+            lds_wait<8>(fc); mul_pv(I1{}, fc); read_s(par, I2{}, fc);
+            lds_wait<8>(fa); mul_s(I1{}, fa); read_pv(par, I3{}, fa);
+            lds_wait<8>(fb); mul_pv(I2{}, fb); read_s(par, I3{}, fb);
+            lds_wait<8>(fc); mul_s(I2{}, fc);
+            lds_wait<4>(fa); mul_pv(I3{}, fa);
+            lds_wait<0>(fb); mul_s(I3{}, fb);
+        } else {
+            // D == 64: PV batches hold two reads, S has two batches of four
+            read_pv(par, I0{}, fa); read_s(par, I0{}, fb); read_pv(par, I1{}, fc);   // 2 + 4 + 2
+            lds_wait<6>(fa); mul_pv(I0{}, fa); read_pv(par, I2{}, fa);    // 4 2 | 2
+            lds_wait<4>(fb); mul_s(I0{}, fb); read_s(par, I1{}, fb);      // 2 2 | 4
+            lds_wait<6>(fc); mul_pv(I1{}, fc); read_pv(par, I3{}, fc);    // 2 4 | 2
+            lds_wait<6>(fa); mul_pv(I2{}, fa);
+            lds_wait<2>(fb); mul_s(I1{}, fb);
+            lds_wait<0>(fc); mul_pv(I3{}, fc);
         }
+        // Refill the slots this phase has just finished reading: K(k+2) -> K slot par,
+        // V^T(k+1) -> V^T slot par^1.  Issued here, after the last MFMA, because LDS-direct
+        // loads issue several times slower while a wave of the same SIMD is feeding the matrix
+        // pipe; now this wave is done with it and its SIMD mate is in its vector phase.
+        // Unconditional: past the end of the list a valid tile is fetched again and never
+        // used.  The loads are waited for at the end of the NEXT step's phase Y.
+#ifndef BS_PROBE_NO_DMA
+        {
+            __builtin_amdgcn_sched_barrier(0);
+            const char *ksrc = tile_ptr(kph, w2.n), *vsrc = tile_ptr(vth, w1.n);
+#pragma unroll
+            for (int r = 0; r < DMA_PER_THREAD; ++r) dma(r, ksrc, decltype(par)::value * TILE);
+#pragma unroll
+            for (int r = 0; r < DMA_PER_THREAD; ++r) dma(r, vsrc, 2 * TILE + (decltype(par)::value ^ 1) * TILE);
+        }
+#endif
+        w1.next();
+        w2.next();
     };
 
     // Phase Y of step k: mask (PARTIAL tiles), online softmax, rescale O, round P to bf16.
-    auto phase_y = [&](int k) {
+    auto phase_y = [&](auto par, int k) {
 #ifdef BS_PROBE_NO_Y
-        if (k < T) wv.next();
-        __builtin_amdgcn_s_waitcnt(0x0f70);
+        if (k < T) w0.next();
+#ifndef BS_PROBE_NO_WAIT
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * DMA_PER_THREAD));
+#endif
         return;
 #endif
         if (k < T) {
             float alpha;
-            if (wv.full) {
-                softmax_block<false>(s, m_run, l_run, alpha, a.scale_log2e);
+            if (w0.full) {
+                softmax_pack<false>(s, pf, m_run, l_run, alpha, a.scale_log2e, [](int) {});
             } else {
-                const int nu = __builtin_amdgcn_readfirstlane(wv.n);
+                const int nu = __builtin_amdgcn_readfirstlane(w0.n);
                 const uint64_t tb = map_text_bits[nu];
                 const uint64_t sb = (cls & 1) ? map_sink_bits[nu] : 0ull;
-                apply_mask(s, allowed_keys(qv, tb, sb, wv.n * kBlockN), hl);
-                softmax_block<true>(s, m_run, l_run, alpha, a.scale_log2e);
+                floatx16 sm[2] = {s[0], s[1]};
+                apply_mask(sm, allowed_keys(qv, tb, sb, w0.n * kBlockN), hl);
+                softmax_pack<true>(sm, pf, m_run, l_run, alpha, a.scale_log2e, [](int) {});
             }
             if (__any(alpha != 1.f)) {
 #pragma unroll
@@ -531,15 +635,7 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(KernelA
 #pragma unroll
                     for (int v = 0; v < 16; ++v) o[db][v] *= alpha;
             }
-            // P^T as bf16 B operands: contraction slots e = 0..7 of MFMA (kb, t) are C values
-            // v = 8t + e, i.e. keys 32kb + 16t + {4hl..4hl+3, 8+4hl..8+4hl+3}
-#pragma unroll
-            for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-                for (int t = 0; t < 2; ++t)
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) pf[kb][t][e] = (__bf16)s[kb][8 * t + e];
-            wv.next();
+            w0.next();
         } else if (k == T) {
             // past the last tile: phase X keeps running (the other group may have more tiles)
             // but must add nothing
@@ -548,7 +644,8 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(KernelA
 #pragma unroll
                 for (int e = 0; e < 8; ++e) pf[i >> 1][i & 1][e] = (__bf16)0.f;
         }
-        __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): the tiles requested in phase X have landed
+        // the tiles requested one step ago have landed once only this step's loads are in flight
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * DMA_PER_THREAD));
     };
 
     // Zero the group's ring once: phase X reads every slot from its first step on, and stale
@@ -559,36 +656,39 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(KernelA
         for (int i = (tid & 255) * 16; i < 4 * TILE; i += 256 * 16) *reinterpret_cast<uint4 *>(mine + i) = z4;
     }
     __syncthreads();
-    // prologue: K(0) into K slot 0
-    if (T > 0) {
-        issue_tile(kh, wk.n, 0, false);
-        wk.next();
+    // prologue: K(0) -> K slot 0, K(1) -> K slot 1, V^T(0) -> V^T slot 0 (unconditional, clamped)
+    {
+        const char *k0 = tile_ptr(kph, w0.n), *k1 = tile_ptr(kph, w1.n), *v0 = tile_ptr(vth, w0.n);
+#pragma unroll
+        for (int r = 0; r < DMA_PER_THREAD; ++r) dma(r, k0, 0);
+#pragma unroll
+        for (int r = 0; r < DMA_PER_THREAD; ++r) dma(r, k1, TILE);
+#pragma unroll
+        for (int r = 0; r < DMA_PER_THREAD; ++r) dma(r, v0, 2 * TILE);
     }
     // Raw barriers: every LDS access of this kernel is an LDS-direct load (drained with vmcnt
     // at the end of phase Y) or an asm read (drained with lgkmcnt inside phase X), so no fence
-    // is wanted here -- a fence would drain the loads already at the end of phase X.
-    __builtin_amdgcn_s_waitcnt(0x0f70);
+    // is wanted here -- a fence would drain loads that are meant to stay in flight.
+    __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0)
     __builtin_amdgcn_s_barrier();
     if (grp == 1) __builtin_amdgcn_s_barrier();  // second group runs half a step behind
     BS_T0();
     for (int k = 0; k < n_steps; k += 2) {
-        phase_x(I0{}, k);
-        if (k + 1 < T) wk.next();
+        phase_x(I0{});
         BS_TICK(0);
-        __builtin_amdgcn_s_barrier();
+        BS_LOOP_BARRIER();
         BS_TICK(1);
-        phase_y(k);
+        phase_y(I0{}, k);
         BS_TICK(2);
-        __builtin_amdgcn_s_barrier();
+        BS_LOOP_BARRIER();
         BS_TICK(3);
-        phase_x(I1{}, k + 1);
-        if (k + 2 < T) wk.next();
+        phase_x(I1{});
         BS_TICK(0);
-        __builtin_amdgcn_s_barrier();
+        BS_LOOP_BARRIER();
         BS_TICK(1);
-        phase_y(k + 1);
+        phase_y(I1{}, k + 1);
         BS_TICK(2);
-        __builtin_amdgcn_s_barrier();
+        BS_LOOP_BARRIER();
         BS_TICK(3);
     }
     if (grp == 0) __builtin_amdgcn_s_barrier();  // same barrier count for every wave of the workgroup
@@ -732,6 +832,7 @@ void free_device_map(DeviceMap *d)
         (void)hipGetDevice(&cur);
         if (cur != d->device) (void)hipSetDevice(d->device);
         (void)hipFree(d->blob);
+        if (d->vt_buf) (void)hipFree(d->vt_buf);
         if (cur >= 0 && cur != d->device) (void)hipSetDevice(cur);
     }
     delete d;
@@ -842,7 +943,7 @@ extern "C" int bs_attn_prefill(const void *q, const void *k, const void *v, void
 
     int rc = bs_tilemap_upload(tm);
     if (rc != BS_OK) return rc;
-    const DeviceMap *d = tm->dev;
+    DeviceMap *d = tm->dev;
     int dev = -1;
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return bs::fail_hip(e, "hipGetDevice");
@@ -856,6 +957,23 @@ extern "C" int bs_attn_prefill(const void *q, const void *k, const void *v, void
     hipStream_t st = static_cast<hipStream_t>(stream);
     const dim3 grid((unsigned)d->n_work), block(bs::kThreads);
     if (dtype == BS_BF16) {
+        // pre-pass: pack V into transposed, swizzled key tiles (workspace owned by the map)
+        const int n_kv_heads = n_q_heads / gqa_group;
+        const size_t pack_bytes = (size_t)n_kv_heads * tm->N * (size_t)head_dim * bs::kBlockN * 2;
+        const size_t vt_need = 2 * pack_bytes;  // packed K tiles, then packed V^T tiles
+        if (d->vt_bytes < vt_need) {
+            if (d->vt_buf) {
+                e = hipFree(d->vt_buf);  // synchronises: earlier launches that read it are done
+                d->vt_buf = nullptr; d->vt_bytes = 0;
+                if (e != hipSuccess) return bs::fail_hip(e, "hipFree(V^T workspace)");
+            }
+            e = hipMalloc(&d->vt_buf, vt_need);
+            if (e != hipSuccess) { d->vt_buf = nullptr; return bs::fail_hip(e, "hipMalloc(V^T workspace)"); }
+            d->vt_bytes = vt_need;
+        }
+        __bf16 *kp = static_cast<__bf16 *>(d->vt_buf);
+        __bf16 *vt = reinterpret_cast<__bf16 *>(static_cast<char *>(d->vt_buf) + pack_bytes);
+        const dim3 tgrid((unsigned)tm->N, (unsigned)n_kv_heads);
         // two work items per workgroup (one per wave group)
         const dim3 pgrid((unsigned)((d->n_work + 1) / 2)), pblock(bs::kPingPongThreads);
         if (head_dim == 128) {
@@ -863,13 +981,17 @@ extern "C" int bs_attn_prefill(const void *q, const void *k, const void *v, void
             e = hipFuncSetAttribute(reinterpret_cast<const void *>(bs::attn_prefill_bf16<128>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, lds);
             if (e != hipSuccess) return bs::fail_hip(e, "hipFuncSetAttribute");
-            hipLaunchKernelGGL(bs::attn_prefill_bf16<128>, pgrid, pblock, lds, st, a, BS_MAP_ARGS(d), d->row_tiles, d->n_work);
+            hipLaunchKernelGGL(bs::pack_k_tiles<128>, tgrid, dim3(256), 0, st, static_cast<const __bf16 *>(k), kp, tm->L, tm->N);
+            hipLaunchKernelGGL(bs::pack_vt_tiles<128>, tgrid, dim3(256), 0, st, static_cast<const __bf16 *>(v), vt, tm->L, tm->N);
+            hipLaunchKernelGGL(bs::attn_prefill_bf16<128>, pgrid, pblock, lds, st, a, BS_MAP_ARGS(d), d->row_tiles, d->n_work, kp, vt, tm->N);
         } else {
             constexpr int lds = bs::bf16_lds_bytes<64>();
             e = hipFuncSetAttribute(reinterpret_cast<const void *>(bs::attn_prefill_bf16<64>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, lds);
             if (e != hipSuccess) return bs::fail_hip(e, "hipFuncSetAttribute");
-            hipLaunchKernelGGL(bs::attn_prefill_bf16<64>, pgrid, pblock, lds, st, a, BS_MAP_ARGS(d), d->row_tiles, d->n_work);
+            hipLaunchKernelGGL(bs::pack_k_tiles<64>, tgrid, dim3(256), 0, st, static_cast<const __bf16 *>(k), kp, tm->L, tm->N);
+            hipLaunchKernelGGL(bs::pack_vt_tiles<64>, tgrid, dim3(256), 0, st, static_cast<const __bf16 *>(v), vt, tm->L, tm->N);
+            hipLaunchKernelGGL(bs::attn_prefill_bf16<64>, pgrid, pblock, lds, st, a, BS_MAP_ARGS(d), d->row_tiles, d->n_work, kp, vt, tm->N);
         }
     } else {
         if (head_dim == 128) {
