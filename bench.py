@@ -37,8 +37,49 @@ def parse_args():
     ap.add_argument("--all-dense", action="store_true", help="run the same prompt with every head Dense")
     ap.add_argument("--no-dense-leg", action="store_true", help="skip the all-Dense comparison run")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-seconds", type=float, default=15.0, help="target CPU time of the oracle sample")
+    ap.add_argument("--cpu-seconds", type=float, default=40.0, help="target CPU time of the oracle sample")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one 1 GiB device-to-device copy (a kernel of known HBM traffic, "
+                         "used to scale rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
     return ap.parse_args()
+
+
+class HipEvents:
+    """Raw hipEvent_t pairs on the process's HIP runtime, for timing the attention kernel alone
+    on the stream it is launched on."""
+
+    def __init__(self):
+        import ctypes
+        self.ct = ctypes
+        self.hip = ctypes.CDLL("libamdhip64.so")   # resolves to the copy the process already loaded
+        self.hip.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+        self.hip.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+        self.hip.hipEventSynchronize.argtypes = [ctypes.c_void_p]
+        self.hip.hipEventDestroy.argtypes = [ctypes.c_void_p]
+
+    def create(self):
+        e = self.ct.c_void_p()
+        rc = self.hip.hipEventCreate(self.ct.byref(e))
+        assert rc == 0, f"hipEventCreate failed ({rc})"
+        return e
+
+    def elapsed_ms(self, a, b):
+        self.hip.hipEventSynchronize(b)
+        ms = self.ct.c_float()
+        rc = self.hip.hipEventElapsedTime(self.ct.byref(ms), a, b)
+        assert rc == 0, f"hipEventElapsedTime failed ({rc})"
+        return float(ms.value)
+
+    def destroy(self, e):
+        self.hip.hipEventDestroy(e)
+
+
+# HBM traffic per launch of the attention kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+# runs, scaled by the same counters' reading for a 1 GiB copy (see profiles/).  Bytes.
+MEASURED_TRAFFIC = {
+    # profiles/attn_prefill_bf16_d128_cfg2_36k.md: 13.49 GB read + 0.28 GB written
+    "cfg2-qwen2vl7b-36k/paper10/seed0": 1.377e10,
+}
 
 
 def class_totals(tm, head_class):
@@ -51,8 +92,9 @@ def class_totals(tm, head_class):
     return tot, per_class
 
 
-def timed_steps(bs, torch, p, q, k, v, out, steps, warmup):
-    """Returns (wall ms per step, mean kernel ms, mean tile-map build ms, last tile map)."""
+def timed_steps(bs, torch, p, q, k, v, out, steps, warmup, hev):
+    """Returns (wall ms per step, mean attention-kernel ms, mean device ms of the whole call
+    incl. the tile-pack pre-pass, mean tile-map build+upload ms, last tile map)."""
     dt = bs.BS_BF16 if p.dtype == "bf16" else bs.BS_F32
     stream = torch.cuda.current_stream()
     keep = []
@@ -66,14 +108,15 @@ def timed_steps(bs, torch, p, q, k, v, out, steps, warmup):
         t1 = time.perf_counter()
         e0 = torch.cuda.Event(enable_timing=True)
         e1 = torch.cuda.Event(enable_timing=True)
+        k0, k1 = (hev.create(), hev.create()) if record else (None, None)
         e0.record(stream)
-        bs.bs_attn_prefill(q, k, v, out, tm, dt, p.n_q_heads, p.gqa_group, p.head_dim, p.scale,
-                           stream.cuda_stream)
+        bs.bs_attn_prefill_ex(q, k, v, out, tm, dt, p.n_q_heads, p.gqa_group, p.head_dim, p.scale,
+                              stream.cuda_stream, k0.value if k0 else None, k1.value if k1 else None)
         e1.record(stream)
         keep.append(tm)
         if record:
             build_s.append(t1 - t0)
-            ev.append((e0, e1))
+            ev.append((e0, e1, k0, k1))
 
     for _ in range(warmup):
         step(False)
@@ -83,8 +126,12 @@ def timed_steps(bs, torch, p, q, k, v, out, steps, warmup):
         step(True)
     torch.cuda.synchronize()
     wall = (time.perf_counter() - t0) / steps
-    kern = sum(a.elapsed_time(b) for a, b in ev) / len(ev)
-    return wall * 1e3, kern, 1e3 * sum(build_s) / len(build_s), keep[-1]
+    call_ms = sum(a.elapsed_time(b) for a, b, _, _ in ev) / len(ev)
+    kern_ms = sum(hev.elapsed_ms(c, d) for _, _, c, d in ev) / len(ev)
+    for _, _, c, d in ev:
+        hev.destroy(c)
+        hev.destroy(d)
+    return wall * 1e3, kern_ms, call_ms, 1e3 * sum(build_s) / len(build_s), keep[-1]
 
 
 def cpu_baseline(p, q, k, v, target_seconds):
@@ -158,8 +205,15 @@ def main():
         p = p.all_dense()
     q, k, v = W.make_qkv(p, args.seed, "cuda:0")
     out = torch.empty_like(q)
+    hev = HipEvents()
+    if args.calibrate_copy:
+        a = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0")
+        b = torch.empty_like(a)
+        b.copy_(a)
+        torch.cuda.synchronize()
+        del a, b
 
-    wall_ms, kern_ms, build_ms, tm = timed_steps(bs, torch, p, q, k, v, out, args.steps, args.warmup)
+    wall_ms, kern_ms, call_ms, build_ms, tm = timed_steps(bs, torch, p, q, k, v, out, args.steps, args.warmup, hev)
     tot, per_class = class_totals(tm, p.head_class)
     d = p.head_dim
     useful_flop = 4.0 * d * tot["allowed_pairs"]
@@ -172,7 +226,7 @@ def main():
     if not args.all_dense and not args.no_dense_leg:
         pd = p.all_dense()
         dsteps = max(3, min(args.steps, 10))
-        d_wall, d_kern, _, d_tm = timed_steps(bs, torch, pd, q, k, v, out, dsteps, 1)
+        d_wall, d_kern, _, _, d_tm = timed_steps(bs, torch, pd, q, k, v, out, dsteps, 1, hev)
         d_tot, _ = class_totals(d_tm, pd.head_class)
         dense = {"ms_per_step": round(d_wall, 4), "kernel_ms": round(d_kern, 4), "steps": dsteps,
                  "visited_tiles": d_tot["visited"],
@@ -195,6 +249,7 @@ def main():
                    "sink_mode": args.sink_mode, "seed": args.seed,
                    "head_classes": {n: int((p.head_class == c).sum()) for c, n in enumerate(W.CLASS_NAMES)}},
         "kernel_ms": round(kern_ms, 4),
+        "device_ms_per_call": round(call_ms, 4),
         "tilemap_build_upload_ms": round(build_ms, 4),
         "executed_tflops": round(executed_flop / (kern_ms * 1e-3) / 1e12, 2),
         "kv_stream_gbs": round(kv_stream_bytes / (kern_ms * 1e-3) / 1e9, 1),
@@ -204,7 +259,7 @@ def main():
                   "useful_over_executed": round(useful_flop / executed_flop, 4)},
         "all_dense": dense,
         "roofline": {"bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS,
-                     "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                     "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": MEASURED_TRAFFIC.get(p.name),
                      "kernel": "attn_prefill_%s<%d>" % (p.dtype, d),
                      "flop_per_launch": useful_flop, "avg_launch_ms": round(kern_ms, 4)},
     }

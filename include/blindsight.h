@@ -114,6 +114,10 @@ int bs_tilemap_upload(bs_tilemap *tm);
  *   scale    finite and > 0 (1/sqrt(d_k) in the paper)
  *   stream   hipStream_t (NULL = default stream).  The call only enqueues work; the caller
  *            owns q/k/v/out and keeps them alive until the stream has drained.
+ * bf16 path: a pre-pass first packs K and V into per-key-tile blocks (V transposed) in a
+ * workspace the map owns (allocated on first use, 2 x the size of K; grown with a synchronising
+ * hipFree + hipMalloc if a later call needs more).  Calls that share a map must therefore be
+ * ordered on one stream: they share that workspace.
  * The first call on a map uploads it (see bs_tilemap_upload), which synchronises once.
  * Errors: BS_EINVAL (null pointers, head counts that do not match), BS_EUNSUPPORTED,
  * BS_EHIP, BS_ENOMEM.  Nothing is launched on error.
@@ -121,6 +125,16 @@ int bs_tilemap_upload(bs_tilemap *tm);
 int bs_attn_prefill(const void *q, const void *k, const void *v, void *out, bs_tilemap *tm,
                     int32_t dtype, int32_t n_q_heads, int32_t gqa_group, int32_t head_dim,
                     float scale, void *stream);
+
+/*
+ * Same call, for profiling harnesses: if non-NULL, ev_main_start / ev_main_stop (hipEvent_t,
+ * created by the caller with timing enabled) are recorded on `stream` immediately before and
+ * after the attention kernel itself, i.e. excluding the bf16 path's K / V^T tile-pack pre-pass
+ *.  hipEventElapsedTime between them is that kernel's duration.
+ */
+int bs_attn_prefill_ex(const void *q, const void *k, const void *v, void *out, bs_tilemap *tm,
+                       int32_t dtype, int32_t n_q_heads, int32_t gqa_group, int32_t head_dim,
+                       float scale, void *stream, void *ev_main_start, void *ev_main_stop);
 
 /* Static description of an error code. */
 const char *bs_strerror(int code);

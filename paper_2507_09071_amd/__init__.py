@@ -2,5 +2,5 @@
 libblindsight.so.  Argument marshalling only — every step of the path runs in the library."""
 from .binding import (  # noqa: F401
     BS_BF16, BS_F32, DENSE, SINK, INTRA, INTRA_SINK, BlindsightError, TileMap,
-    bs_build_tilemap, bs_attn_prefill, library_path, load_library,
+    bs_build_tilemap, bs_attn_prefill, bs_attn_prefill_ex, library_path, load_library,
 )

@@ -18,7 +18,8 @@ BS_BF16, BS_F32 = 0, 1
 DENSE, SINK, INTRA, INTRA_SINK = 0, 1, 2, 3
 
 EXPORTS = ("bs_build_tilemap", "bs_tilemap_destroy", "bs_tilemap_dims", "bs_tilemap_tile_states",
-           "bs_tilemap_stats", "bs_tilemap_upload", "bs_attn_prefill", "bs_strerror", "bs_last_error")
+           "bs_tilemap_stats", "bs_tilemap_upload", "bs_attn_prefill", "bs_attn_prefill_ex", "bs_strerror",
+           "bs_last_error")
 
 
 class BlindsightError(RuntimeError):
@@ -78,6 +79,8 @@ def load_library():
     lib.bs_tilemap_upload.restype = ctypes.c_int
     lib.bs_attn_prefill.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, ctypes.c_float, vp]
     lib.bs_attn_prefill.restype = ctypes.c_int
+    lib.bs_attn_prefill_ex.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, ctypes.c_float, vp, vp, vp]
+    lib.bs_attn_prefill_ex.restype = ctypes.c_int
     lib.bs_strerror.argtypes = [ctypes.c_int]
     lib.bs_strerror.restype = ctypes.c_char_p
     lib.bs_last_error.argtypes = []
@@ -158,6 +161,18 @@ def bs_build_tilemap(spans, seq_len: int, head_class, sink_len: int = 0,
 
 def _ptr(x) -> int:
     return int(x.data_ptr()) if hasattr(x, "data_ptr") else int(x)
+
+
+def bs_attn_prefill_ex(q, k, v, out, tilemap: TileMap, dtype: int, n_q_heads: int, gqa_group: int,
+                       head_dim: int, scale: float, stream=None, ev_main_start=None, ev_main_stop=None) -> None:
+    """bs_attn_prefill that also records two caller-owned hipEvent_t handles (ints) around the
+    attention kernel itself."""
+    rc = load_library().bs_attn_prefill_ex(_ptr(q), _ptr(k), _ptr(v), _ptr(out), tilemap.handle,
+                                           int(dtype), int(n_q_heads), int(gqa_group), int(head_dim),
+                                           float(scale), ctypes.c_void_p(int(stream) if stream else 0),
+                                           ctypes.c_void_p(int(ev_main_start) if ev_main_start else 0),
+                                           ctypes.c_void_p(int(ev_main_stop) if ev_main_stop else 0))
+    _check(rc, "bs_attn_prefill_ex")
 
 
 def bs_attn_prefill(q, k, v, out, tilemap: TileMap, dtype: int, n_q_heads: int, gqa_group: int,

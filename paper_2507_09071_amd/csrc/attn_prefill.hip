@@ -932,6 +932,13 @@ extern "C" int bs_attn_prefill(const void *q, const void *k, const void *v, void
                                int32_t dtype, int32_t n_q_heads, int32_t gqa_group, int32_t head_dim,
                                float scale, void *stream)
 {
+    return bs_attn_prefill_ex(q, k, v, out, tm, dtype, n_q_heads, gqa_group, head_dim, scale, stream, nullptr, nullptr);
+}
+
+extern "C" int bs_attn_prefill_ex(const void *q, const void *k, const void *v, void *out, bs_tilemap *tm,
+                                  int32_t dtype, int32_t n_q_heads, int32_t gqa_group, int32_t head_dim,
+                                  float scale, void *stream, void *ev_main_start, void *ev_main_stop)
+{
     if (!q || !k || !v || !out || !tm) return BS_EINVAL;
     if (n_q_heads <= 0 || gqa_group <= 0 || n_q_heads % gqa_group != 0) return BS_EINVAL;
     if (n_q_heads != tm->n_q_heads) return BS_EINVAL;
@@ -983,6 +990,7 @@ extern "C" int bs_attn_prefill(const void *q, const void *k, const void *v, void
             if (e != hipSuccess) return bs::fail_hip(e, "hipFuncSetAttribute");
             hipLaunchKernelGGL(bs::pack_k_tiles<128>, tgrid, dim3(256), 0, st, static_cast<const __bf16 *>(k), kp, tm->L, tm->N);
             hipLaunchKernelGGL(bs::pack_vt_tiles<128>, tgrid, dim3(256), 0, st, static_cast<const __bf16 *>(v), vt, tm->L, tm->N);
+            if (ev_main_start) (void)hipEventRecord(static_cast<hipEvent_t>(ev_main_start), st);
             hipLaunchKernelGGL(bs::attn_prefill_bf16<128>, pgrid, pblock, lds, st, a, BS_MAP_ARGS(d), d->row_tiles, d->n_work, kp, vt, tm->N);
         } else {
             constexpr int lds = bs::bf16_lds_bytes<64>();
@@ -991,9 +999,11 @@ extern "C" int bs_attn_prefill(const void *q, const void *k, const void *v, void
             if (e != hipSuccess) return bs::fail_hip(e, "hipFuncSetAttribute");
             hipLaunchKernelGGL(bs::pack_k_tiles<64>, tgrid, dim3(256), 0, st, static_cast<const __bf16 *>(k), kp, tm->L, tm->N);
             hipLaunchKernelGGL(bs::pack_vt_tiles<64>, tgrid, dim3(256), 0, st, static_cast<const __bf16 *>(v), vt, tm->L, tm->N);
+            if (ev_main_start) (void)hipEventRecord(static_cast<hipEvent_t>(ev_main_start), st);
             hipLaunchKernelGGL(bs::attn_prefill_bf16<64>, pgrid, pblock, lds, st, a, BS_MAP_ARGS(d), d->row_tiles, d->n_work, kp, vt, tm->N);
         }
     } else {
+        if (ev_main_start) (void)hipEventRecord(static_cast<hipEvent_t>(ev_main_start), st);
         if (head_dim == 128) {
             constexpr size_t lds = bs::f32_lds_bytes<128>();
             e = hipFuncSetAttribute(reinterpret_cast<const void *>(bs::attn_prefill_f32<128>),
@@ -1007,6 +1017,7 @@ extern "C" int bs_attn_prefill(const void *q, const void *k, const void *v, void
     }
     e = hipGetLastError();
     if (e != hipSuccess) return bs::fail_hip(e, "kernel launch");
+    if (ev_main_stop) (void)hipEventRecord(static_cast<hipEvent_t>(ev_main_stop), st);
     return BS_OK;
 }
 

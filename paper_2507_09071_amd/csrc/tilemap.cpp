@@ -28,9 +28,13 @@ struct Geometry {
     std::vector<int32_t> last_text;    // L: largest text position <= t, or -1
     std::vector<int32_t> next_text;    // L+1: smallest text position >= t, or L
     std::vector<int32_t> next_free_sink;  // L+1: smallest (text or sink) position >= t, or L
+    // per key tile, for classes without / with the sink bit: smallest n' >= n whose keys are
+    // all free (text, or text/sink) and which is a complete tile; N if none
+    std::vector<int32_t> next_allfree_tile[2];  // N+1 each
 
     const std::vector<int32_t> &free_count(int cls) const { return (cls & 1) ? n_free_sink : n_text; }
     const std::vector<int32_t> &next_free(int cls) const { return (cls & 1) ? next_free_sink : next_text; }
+    const std::vector<int32_t> &next_allfree(int cls) const { return next_allfree_tile[cls & 1]; }
 };
 
 struct QueryTile {
@@ -140,23 +144,59 @@ void build_class(const Geometry &G, int cls, ClassLists &out)
     std::vector<int32_t> cand;
     for (int32_t m = 0; m < G.M; ++m) {
         describe_query_tile(G, m, qt);
-        candidate_tiles(G, qt, cls, cand);
         int32_t run_begin = -1, run_end = -1, run_state = 0;
         auto flush = [&]() {
             if (run_begin >= 0) out.ranges.push_back({run_begin, (run_end << 1) | (run_state == 2)});
             run_begin = -1;
         };
-        for (int32_t n : cand) {
-            int st = tile_state(G, qt, cls, n);
-            if (st == 0) continue;
-            if (run_begin >= 0 && n == run_end && st == run_state) {
-                ++run_end;
+        // append tiles [b, e) of one state (1 partial, 2 full) to the row, merging runs
+        auto emit = [&](int32_t b, int32_t e, int st) {
+            if (e <= b) return;
+            if (run_begin >= 0 && b == run_end && st == run_state) {
+                run_end = e;
             } else {
                 flush();
-                run_begin = n; run_end = n + 1; run_state = st;
+                run_begin = b; run_end = e; run_state = st;
             }
-            ++out.row_tiles[m];
-            if (st == 2) ++out.full; else ++out.partial;
+            out.row_tiles[m] += e - b;
+            if (st == 2) out.full += e - b; else out.partial += e - b;
+        };
+        const int32_t n_last = (qt.r1 - 1) / G.bn;
+        // key tiles wholly at or before the first row of a complete query tile can be FULL
+        const int32_t n_full_limit = qt.ragged ? 0 : (qt.r0 + 1) / G.bn;
+
+        if (cls == BS_DENSE || qt.segs.empty()) {
+            // every earlier key is visible: FULL below the diagonal, PARTIAL on it
+            emit(0, n_full_limit, 2);
+            emit(n_full_limit, n_last + 1, 1);
+        } else if (qt.last_text >= 0) {
+            // mixed text/image query tile: every causal key tile up to the last text row is
+            // visited.  Only a few of them can differ from PARTIAL: all-free tiles and tiles
+            // overlapping an own image (candidates for FULL), and the tiles past the last text
+            // row (may be SKIP).  Those are classified exactly; the rest are PARTIAL.
+            cand.clear();
+            const auto &naf = G.next_allfree(cls);
+            for (int32_t n = naf[0]; n < n_full_limit; n = naf[n + 1]) cand.push_back(n);
+            const auto &sp = *G.spans;
+            for (const Segment &sg : qt.segs)
+                for (int32_t n = sp[sg.g].start / G.bn; n <= (sg.b - 1) / G.bn && n < n_full_limit; ++n) cand.push_back(n);
+            for (int32_t n = qt.last_text / G.bn + 1; n <= n_last; ++n) cand.push_back(n);
+            std::sort(cand.begin(), cand.end());
+            cand.erase(std::unique(cand.begin(), cand.end()), cand.end());
+            int32_t cur = 0;
+            for (int32_t n : cand) {
+                emit(cur, n, 1);
+                const int st = tile_state(G, qt, cls, n);
+                if (st) emit(n, n + 1, st);
+                cur = n + 1;
+            }
+            emit(cur, qt.last_text / G.bn + 1, 1);
+        } else {
+            candidate_tiles(G, qt, cls, cand);
+            for (int32_t n : cand) {
+                const int st = tile_state(G, qt, cls, n);
+                if (st) emit(n, n + 1, st);
+            }
         }
         flush();
         out.row_ptr[m + 1] = (int64_t)out.ranges.size();
@@ -269,6 +309,15 @@ extern "C" int bs_build_tilemap(const bs_span *spans, int32_t n_spans, int32_t s
             G.next_free_sink[t] = fs ? t : G.next_free_sink[t + 1];
         }
 
+        for (int b = 0; b < 2; ++b) {
+            const std::vector<int32_t> &fc = b ? G.n_free_sink : G.n_text;
+            G.next_allfree_tile[b].assign(tm->N + 1, tm->N);
+            for (int32_t n = tm->N - 1; n >= 0; --n) {
+                const int32_t c0 = n * block_n, c1 = std::min(c0 + block_n, L);
+                const bool allfree = (c1 - c0 == block_n) && (fc[c1] - fc[c0] == block_n);
+                G.next_allfree_tile[b][n] = allfree ? n : G.next_allfree_tile[b][n + 1];
+            }
+        }
         for (int c = 0; c < 4; ++c) build_class(G, c, tm->cls[c]);
         count_pairs(G, tm->code, tm->cls);
 
