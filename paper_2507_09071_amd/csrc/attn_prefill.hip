@@ -210,11 +210,13 @@ __device__ inline void softmax_block(floatx16 (&s)[2], float &m_run, float &l_ru
 // Same update as softmax_block, but the scores are only read and the probabilities go straight
 // into the bf16 B operands of the P.V MFMAs: contraction slot e of MFMA group (kb, t) is score
 // v = 8t + e of block kb, i.e. key 32kb + 16t + {4hl..4hl+3, 8+4hl..8+4hl+3}[e].
-// `between(i)`, i = 0..7, is called at eight evenly spaced points of the exponential loop and
-// pinned there, so that the caller can spread its memory instructions over the vector work.
-template <bool MAY_BE_EMPTY, class Hook>
+//   MODE 0  FULL tile: every score counts.
+//   MODE 1  row-uniform PARTIAL tile: a lane's query sees either all 64 keys or none (`drop`).
+//           A dropped row keeps its running max and gets p = 0 through an infinite offset.
+//   MODE 2  general PARTIAL tile: `s` already holds -inf at the masked positions.
+template <int MODE>
 __device__ inline void softmax_pack(const floatx16 (&s)[2], bf16x8 (&pf)[2][2], float &m_run, float &l_run,
-                                    float &alpha, float c, Hook &&between)
+                                    float &alpha, float c, bool drop)
 {
     // four independent max chains
     float mx[4];
@@ -224,27 +226,39 @@ __device__ inline void softmax_pack(const floatx16 (&s)[2], bf16x8 (&pf)[2][2], 
     for (int v = 2; v < 8; v += 2)
 #pragma unroll
         for (int i = 0; i < 4; ++i) mx[i] = fmaxf(fmaxf(mx[i], s[i >> 1][8 * (i & 1) + v]), s[i >> 1][8 * (i & 1) + v + 1]);
-    const float mxl = max_across_halves(fmaxf(fmaxf(mx[0], mx[1]), fmaxf(mx[2], mx[3])));
+    float mxl = max_across_halves(fmaxf(fmaxf(mx[0], mx[1]), fmaxf(mx[2], mx[3])));
+    if (MODE == 1) mxl = drop ? -INFINITY : mxl;
     const float m_new = fmaxf(m_run, mxl);
-    const float m_use = (MAY_BE_EMPTY && m_new == -INFINITY) ? 0.f : m_new;
+    const float m_use = (MODE != 0 && m_new == -INFINITY) ? 0.f : m_new;  // no key seen so far: p = 0
     const float mc = m_use * c;
     alpha = __builtin_amdgcn_exp2f(fmaf(m_run, c, -mc));  // m_run = -inf -> 0
-    float sum[4] = {0.f, 0.f, 0.f, 0.f};
+    const float off = (MODE == 1 && drop) ? -INFINITY : -mc;
+    // all 32 exponentials as independent work (the wave has no SIMD mate doing vector work, so
+    // instruction-level parallelism is what hides the transcendental latency), then eight sum
+    // chains, then the bf16 packing
+    float pr[32];
+#pragma unroll
+    for (int i = 0; i < 32; ++i) pr[i] = fmaf(s[i >> 4][i & 15], c, off);
+#pragma unroll
+    for (int i = 0; i < 32; ++i) pr[i] = __builtin_amdgcn_exp2f(pr[i]);
+    float sum[4];
+    {
+        float part[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) part[i] = pr[i] + pr[i + 8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) part[i] += pr[i + 16];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) part[i] += pr[i + 24];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) sum[i] = part[i] + part[i + 4];
+    }
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
         for (int t = 0; t < 2; ++t)
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const float pv = __builtin_amdgcn_exp2f(fmaf(s[kb][8 * t + e], c, -mc));
-                sum[e & 3] += pv;
-                pf[kb][t][e] = (__bf16)pv;
-                if ((e & 3) == 3) {
-                    __builtin_amdgcn_sched_barrier(0);
-                    between(4 * kb + 2 * t + (e >> 2));
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-            }
+            for (int e = 0; e < 8; ++e) pf[kb][t][e] = (__bf16)pr[16 * kb + 8 * t + e];
     l_run = fmaf(l_run, alpha, (sum[0] + sum[1]) + (sum[2] + sum[3]));
     m_run = m_new;
 }
@@ -608,6 +622,13 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(KernelA
         w2.next();
     };
 
+    // text / sink key bits of the tile w0 names (scalar registers, fetched one step ahead)
+    uint64_t tb_cur, sb_cur;
+    {
+        const int nn = min(__builtin_amdgcn_readfirstlane(w0.n), n_k_tiles - 1);
+        tb_cur = map_text_bits[nn];
+        sb_cur = map_sink_bits[nn];
+    }
     // Phase Y of step k: mask (PARTIAL tiles), online softmax, rescale O, round P to bf16.
     auto phase_y = [&](auto par, int k) {
 #ifdef BS_PROBE_NO_Y
@@ -620,14 +641,18 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(KernelA
         if (k < T) {
             float alpha;
             if (w0.full) {
-                softmax_pack<false>(s, pf, m_run, l_run, alpha, a.scale_log2e, [](int) {});
+                softmax_pack<0>(s, pf, m_run, l_run, alpha, a.scale_log2e, false);
             } else {
                 const int nu = __builtin_amdgcn_readfirstlane(w0.n);
-                const uint64_t tb = map_text_bits[nu];
-                const uint64_t sb = (cls & 1) ? map_sink_bits[nu] : 0ull;
-                floatx16 sm[2] = {s[0], s[1]};
-                apply_mask(sm, allowed_keys(qv, tb, sb, w0.n * kBlockN), hl);
-                softmax_pack<true>(sm, pf, m_run, l_run, alpha, a.scale_log2e, [](int) {});
+                const uint64_t allowed = allowed_keys(qv, tb_cur, (cls & 1) ? sb_cur : 0ull, nu * kBlockN);
+                if (__all(allowed == 0ull || allowed == ~0ull)) {
+                    // every query of the wave sees all 64 keys or none (e.g. a text row and an
+                    // image row over keys of another image): no per-score work
+                    softmax_pack<1>(s, pf, m_run, l_run, alpha, a.scale_log2e, allowed == 0ull);
+                } else {
+                    apply_mask(s, allowed, hl);
+                    softmax_pack<2>(s, pf, m_run, l_run, alpha, a.scale_log2e, false);
+                }
             }
             if (__any(alpha != 1.f)) {
 #pragma unroll
@@ -636,6 +661,12 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(KernelA
                     for (int v = 0; v < 16; ++v) o[db][v] *= alpha;
             }
             w0.next();
+            // key bit masks of the next tile: requested now, used one step later
+            {
+                const int nn = min(__builtin_amdgcn_readfirstlane(w0.n), n_k_tiles - 1);
+                tb_cur = map_text_bits[nn];
+                sb_cur = map_sink_bits[nn];
+            }
         } else if (k == T) {
             // past the last tile: phase X keeps running (the other group may have more tiles)
             // but must add nothing
