@@ -95,6 +95,18 @@ int bs_tilemap_stats(const bs_tilemap *tm, int32_t cls, int64_t *visited, int64_
                      int64_t *partial, int64_t *allowed_pairs, int64_t *empty_rows,
                      int64_t *n_ranges);
 
+/*
+ * Plan (and check) the work units the bf16 kernel uses for `gqa_group` query heads per KV head:
+ * pairs of (head, query tile) items that read the same KV head and walk one merged key-tile
+ * list, so a workgroup streams every K / V tile once for two items.  Returns BS_OK only if
+ * every (head, query tile) appears in exactly one unit and each unit's merged list reproduces
+ * both items' tile states.  Outputs (may be NULL): number of units, key tiles summed over the
+ * units' merged lists, and steps on which one of a unit's items has nothing to do.
+ * Host only.  bs_attn_prefill plans by itself; this entry point is for tests and accounting.
+ */
+int bs_tilemap_pair_plan(bs_tilemap *tm, int32_t gqa_group, int64_t *n_units, int64_t *unit_tiles,
+                         int64_t *skip_steps);
+
 /* Copy the map to the current HIP device (hipMalloc + synchronous hipMemcpy).  Optional:
  * bs_attn_prefill does it on first use.  Not thread-safe against concurrent calls on the
  * same map.  Errors: BS_EHIP, BS_ENOMEM. */

@@ -18,7 +18,7 @@ BS_BF16, BS_F32 = 0, 1
 DENSE, SINK, INTRA, INTRA_SINK = 0, 1, 2, 3
 
 EXPORTS = ("bs_build_tilemap", "bs_tilemap_destroy", "bs_tilemap_dims", "bs_tilemap_tile_states",
-           "bs_tilemap_stats", "bs_tilemap_upload", "bs_attn_prefill", "bs_attn_prefill_ex", "bs_strerror",
+           "bs_tilemap_stats", "bs_tilemap_pair_plan", "bs_tilemap_upload", "bs_attn_prefill", "bs_attn_prefill_ex", "bs_strerror",
            "bs_last_error")
 
 
@@ -75,6 +75,8 @@ def load_library():
     lib.bs_tilemap_tile_states.restype = ctypes.c_int
     lib.bs_tilemap_stats.argtypes = [vp, i32, i64p, i64p, i64p, i64p, i64p, i64p]
     lib.bs_tilemap_stats.restype = ctypes.c_int
+    lib.bs_tilemap_pair_plan.argtypes = [vp, i32, i64p, i64p, i64p]
+    lib.bs_tilemap_pair_plan.restype = ctypes.c_int
     lib.bs_tilemap_upload.argtypes = [vp]
     lib.bs_tilemap_upload.restype = ctypes.c_int
     lib.bs_attn_prefill.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, ctypes.c_float, vp]
@@ -128,6 +130,12 @@ class TileMap:
                "bs_tilemap_stats")
         names = ("visited", "full", "partial", "allowed_pairs", "empty_rows", "n_ranges")
         return {n: int(x.value) for n, x in zip(names, v)}
+
+    def pair_plan(self, gqa_group: int) -> dict:
+        v = [ctypes.c_int64() for _ in range(3)]
+        _check(load_library().bs_tilemap_pair_plan(self._h, int(gqa_group), *[ctypes.byref(x) for x in v]),
+               "bs_tilemap_pair_plan")
+        return {n: int(x.value) for n, x in zip(("n_units", "unit_tiles", "skip_steps"), v)}
 
     def upload(self):
         _check(load_library().bs_tilemap_upload(self._h), "bs_tilemap_upload")

@@ -60,6 +60,10 @@ struct DeviceMap {
     int32_t n_work = 0;
     void *vt_buf = nullptr;               // workspace: packed K and V^T tiles of the last bf16 call
     size_t vt_bytes = 0;
+    void *pair_blob = nullptr;            // bf16 work units for pair_G: items, then ranges
+    const int4 *pair_items = nullptr;
+    const int2 *pair_ranges = nullptr;
+    int32_t n_pairs = 0, pair_G = 0;
 };
 
 // Read-only tile-map arrays; passed as separate __restrict__ kernel parameters so that loads
@@ -165,6 +169,27 @@ __device__ inline void apply_mask(floatx16 (&s)[2], uint64_t allowed, int hl)
         }
 }
 
+// The same masking with the three instructions of one score kept together, so that the
+// scheduler cannot hoist the 32 bit tests in front of the 32 selects (32 registers of pressure
+// in a kernel that has none to spare).
+__device__ inline void apply_mask_tight(floatx16 (&s)[2], uint64_t allowed, int hl)
+{
+    const uint32_t w[2] = {(uint32_t)allowed >> (4 * hl), (uint32_t)(allowed >> 32) >> (4 * hl)};
+    const float ninf = -INFINITY;
+#pragma unroll
+    for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+            uint32_t t;
+            asm("v_and_b32 %1, %3, %2\n\t"
+                "v_cmp_ne_u32 vcc, 0, %1\n\t"
+                "v_cndmask_b32 %0, %4, %0, vcc"
+                : "+v"(s[kb][v]), "=&v"(t)
+                : "v"(w[kb]), "n"(1u << (8 * (v / 4) + (v % 4))), "v"(ninf)
+                : "vcc");
+        }
+}
+
 __device__ inline float max_across_halves(float x)
 {
     // r[0] = (x.lo, x.lo), r[1] = (x.hi, x.hi): both halves see both values
@@ -233,32 +258,17 @@ __device__ inline void softmax_pack(const floatx16 (&s)[2], bf16x8 (&pf)[2][2], 
     const float mc = m_use * c;
     alpha = __builtin_amdgcn_exp2f(fmaf(m_run, c, -mc));  // m_run = -inf -> 0
     const float off = (MODE == 1 && drop) ? -INFINITY : -mc;
-    // all 32 exponentials as independent work (the wave has no SIMD mate doing vector work, so
-    // instruction-level parallelism is what hides the transcendental latency), then eight sum
-    // chains, then the bf16 packing
-    float pr[32];
-#pragma unroll
-    for (int i = 0; i < 32; ++i) pr[i] = fmaf(s[i >> 4][i & 15], c, off);
-#pragma unroll
-    for (int i = 0; i < 32; ++i) pr[i] = __builtin_amdgcn_exp2f(pr[i]);
-    float sum[4];
-    {
-        float part[8];
-#pragma unroll
-        for (int i = 0; i < 8; ++i) part[i] = pr[i] + pr[i + 8];
-#pragma unroll
-        for (int i = 0; i < 8; ++i) part[i] += pr[i + 16];
-#pragma unroll
-        for (int i = 0; i < 8; ++i) part[i] += pr[i + 24];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) sum[i] = part[i] + part[i + 4];
-    }
+    float sum[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
         for (int t = 0; t < 2; ++t)
 #pragma unroll
-            for (int e = 0; e < 8; ++e) pf[kb][t][e] = (__bf16)pr[16 * kb + 8 * t + e];
+            for (int e = 0; e < 8; ++e) {
+                const float pv = __builtin_amdgcn_exp2f(fmaf(s[kb][8 * t + e], c, off));
+                sum[e & 3] += pv;
+                pf[kb][t][e] = (__bf16)pv;
+            }
     l_run = fmaf(l_run, alpha, (sum[0] + sum[1]) + (sum[2] + sum[3]));
     m_run = m_new;
 }
@@ -286,17 +296,68 @@ __device__ inline void lds_wait(bf16x8 (&a)[4])
     asm volatile("s_waitcnt lgkmcnt(%4)" : "+v"(a[0]), "+v"(a[1]), "+v"(a[2]), "+v"(a[3]) : "n"(N));
 }
 
+// The MFMAs of the matrix phase are asm as well: together with the asm reads and waits they
+// form one chain of volatile statements, which the compiler keeps in program order, and the
+// accumulator is an in/out operand, so it is updated in place (no copies of the 64 output
+// registers).  The compiler does not see a matrix instruction here, so the wait states between
+// the last MFMA writing an accumulator and the first vector instruction reading it are
+// inserted by hand (mfma_drain) at the end of the chain.
+__device__ inline void mfma_acc(floatx16 &c, const bf16x8 &a, const bf16x8 &b)
+{
+    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(c) : "v"(a), "v"(b));
+}
+__device__ inline void mfma_set(floatx16 &c, const bf16x8 &a, const bf16x8 &b)   // c = a b
+{
+    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(c) : "v"(a), "v"(b));
+}
+// The output accumulators O^T live in v64..v127 for the whole main loop: every statement that
+// touches them there is asm with the register named in the constraint, so the allocator has no
+// choice to make (left alone it moves the 64 registers around once or twice per step).
+template <int DB>
+__device__ inline void mfma_o(floatx16 &c, const bf16x8 &a, const bf16x8 &b)
+{
+    if constexpr (DB == 0) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(c) : "v"(a), "v"(b));
+    if constexpr (DB == 1) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(c) : "v"(a), "v"(b));
+    if constexpr (DB == 2) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(c) : "v"(a), "v"(b));
+    if constexpr (DB == 3) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(c) : "v"(a), "v"(b));
+}
+#define BS_MUL4(r0, r1, r2, r3) \
+    "v_mul_f32 v" #r0 ", v" #r0 ", %1\n\tv_mul_f32 v" #r1 ", v" #r1 ", %1\n\t" \
+    "v_mul_f32 v" #r2 ", v" #r2 ", %1\n\tv_mul_f32 v" #r3 ", v" #r3 ", %1\n\t"
+template <int DB>
+__device__ inline void scale_o(floatx16 &c, float alpha)
+{
+    if constexpr (DB == 0)
+        asm(BS_MUL4(64, 65, 66, 67) BS_MUL4(68, 69, 70, 71) BS_MUL4(72, 73, 74, 75) BS_MUL4(76, 77, 78, 79)
+            : "+{v[64:79]}"(c) : "v"(alpha));
+    if constexpr (DB == 1)
+        asm(BS_MUL4(80, 81, 82, 83) BS_MUL4(84, 85, 86, 87) BS_MUL4(88, 89, 90, 91) BS_MUL4(92, 93, 94, 95)
+            : "+{v[80:95]}"(c) : "v"(alpha));
+    if constexpr (DB == 2)
+        asm(BS_MUL4(96, 97, 98, 99) BS_MUL4(100, 101, 102, 103) BS_MUL4(104, 105, 106, 107) BS_MUL4(108, 109, 110, 111)
+            : "+{v[96:111]}"(c) : "v"(alpha));
+    if constexpr (DB == 3)
+        asm(BS_MUL4(112, 113, 114, 115) BS_MUL4(116, 117, 118, 119) BS_MUL4(120, 121, 122, 123) BS_MUL4(124, 125, 126, 127)
+            : "+{v[112:127]}"(c) : "v"(alpha));
+}
+#undef BS_MUL4
+// 16 wait states: more than the 8 passes of a 32x32x16 MFMA plus the result write-back.
+__device__ inline void mfma_drain(floatx16 &c0, floatx16 &c1)
+{
+    asm volatile("s_nop 15" : "+v"(c0), "+v"(c1));
+}
 
-// K tile swizzle: row r stores its logical 16-byte chunk c at chunk c ^ k_swizzle(r).
-template <int D> __device__ inline int k_swizzle(int row) { return D == 128 ? (row & 15) : ((row >> 1) & 7); }
 
-// V^T tile pack (pre-pass, HBM-bound): V[kvh][L][D] -> VT[kvh][n][D rows][64 keys], one
-// contiguous 128*D-byte block per key tile, laid out exactly as the attention kernel wants it
-// in LDS so that its LDS-direct loads are plain copies and every MFMA A operand of P.V is ONE
-// 128-bit read (a 64-bit transposing read moves half the bytes per LDS cycle):
-//   row d holds the tile's 64 keys as 8 chunks of 8 keys; logical chunk c = 2g + h holds keys
-//   16g + {4h..4h+3, 8+4h..8+4h+3} (the contraction slots of lane half h in MFMA group g);
-//   it is stored at chunk c ^ ((d >> 1) & 7), which spreads 16 consecutive rows over all banks.
+// LDS tile layouts of the bf16 kernel (written by the pre-pass below, copied verbatim by the
+// kernel's LDS-direct loads).  Both are "slice-major": everything an MFMA operand read selects
+// at compile time (head-dim slice, key block, key group, channel block) is an immediate offset,
+// and one per-lane base address serves all reads of a tile.
+//   K tile   [D/16 slices t][64 keys][32 B]   32 B = channels 16t..16t+15 of one key, as two
+//            16-byte halves h (channels 16t+8h..+7) stored at half h ^ ((key >> 3) & 1)
+//   V^T tile [4 key groups g][D channels][32 B]   32 B = the 16 keys of group g of one channel,
+//            as two halves h holding keys 16g + {4h..4h+3, 8+4h..8+4h+3} (the contraction slots
+//            of lane half h), stored at half h ^ ((channel >> 3) & 1)
+// A 128-bit read of 16 consecutive keys (channels) then touches every bank exactly once.
 // Keys past the end of the prompt are zero-filled.
 template <int D>
 __global__ __launch_bounds__(256) void pack_vt_tiles(const __bf16 *__restrict__ v, __bf16 *__restrict__ vt, int L, int N)
@@ -316,34 +377,28 @@ __global__ __launch_bounds__(256) void pack_vt_tiles(const __bf16 *__restrict__ 
     }
     __syncthreads();
     __bf16 *dst = vt + ((size_t)kvh * N + n) * (size_t)(D * kBlockN);
-    for (int idx = tid; idx < D * 8; idx += 256) {
-        const int d = idx >> 3, cp = idx & 7;
-        const int c = cp ^ ((d >> 1) & 7);
-        const int g = c >> 1, h = c & 1;
+    for (int idx = tid; idx < D * 8; idx += 256) {   // one 16-byte half per iteration
+        const int hp = idx & 1, d = (idx >> 1) % D, g = idx / (2 * D);
+        const int h = hp ^ ((d >> 3) & 1);
         bf16x8 val;
 #pragma unroll
         for (int e = 0; e < 8; ++e) val[e] = tile[(16 * g + 8 * (e >> 2) + 4 * h + (e & 3)) * PAD + d];
-        *reinterpret_cast<bf16x8 *>(dst + (size_t)d * kBlockN + cp * 8) = val;
+        *reinterpret_cast<bf16x8 *>(dst + (size_t)idx * 8) = val;
     }
 }
 
-// K tile pack (pre-pass, HBM-bound): K[kvh][L][D] -> KP[kvh][n][64 keys][D], one contiguous
-// 128*D-byte block per key tile in the attention kernel's LDS layout: row r stores its logical
-// 16-byte chunk c at chunk c ^ k_swizzle(r), so that the 128-bit K fragment reads of 16
-// consecutive rows fall on distinct banks.  Keys past the end of the prompt are zero-filled.
 template <int D>
 __global__ __launch_bounds__(256) void pack_k_tiles(const __bf16 *__restrict__ k, __bf16 *__restrict__ kp, int L, int N)
 {
-    constexpr int CPR = D / 8;
     const int n = blockIdx.x, kvh = blockIdx.y;
     const __bf16 *src = k + ((size_t)kvh * L + (size_t)n * kBlockN) * D;
     __bf16 *dst = kp + ((size_t)kvh * N + n) * (size_t)(D * kBlockN);
-    for (int idx = threadIdx.x; idx < kBlockN * CPR; idx += 256) {
-        const int row = idx / CPR, cp = idx % CPR;
-        const int c = cp ^ k_swizzle<D>(row);
+    for (int idx = threadIdx.x; idx < kBlockN * (D / 8); idx += 256) {   // one 16-byte half per iteration
+        const int hp = idx & 1, key = (idx >> 1) % kBlockN, t = idx / (2 * kBlockN);
+        const int h = hp ^ ((key >> 3) & 1);
         uint4 val = make_uint4(0, 0, 0, 0);
-        if (n * kBlockN + row < L) val = *reinterpret_cast<const uint4 *>(src + (size_t)row * D + c * 8);
-        *reinterpret_cast<uint4 *>(dst + (size_t)row * D + cp * 8) = val;
+        if (n * kBlockN + key < L) val = *reinterpret_cast<const uint4 *>(src + (size_t)key * D + 16 * t + 8 * h);
+        *reinterpret_cast<uint4 *>(dst + (size_t)idx * 8) = val;
     }
 }
 
@@ -385,58 +440,81 @@ __device__ inline unsigned long long bs_now(floatx16 &a, floatx16 &b, floatx16 &
 #endif
 
 template <int D>
-constexpr int bf16_lds_bytes() { return 2 /*groups*/ * 4 /*2 K + 2 V slots*/ * kBlockN * D * 2; }
+constexpr int bf16_lds_bytes() { return 6 /*3 K + 3 V^T slots*/ * kBlockN * D * 2; }
 
-// One workgroup = two groups of four waves.  Each group owns one (head, query tile) work item
-// and a private K/V ring (2 K slots + 2 V slots).  Per key tile a group runs two phases:
+// Walks the merged key-tile list of a work unit: runs of [begin, end) with a state per item.
+struct PairWalker {
+    const int2 *__restrict__ rg;
+    int p, p_end, n, n_end, states;
+    __device__ void load()
+    {
+        if (p < p_end) {
+            const int2 r = rg[__builtin_amdgcn_readfirstlane(p)];
+            n = __builtin_amdgcn_readfirstlane(r.x);
+            n_end = __builtin_amdgcn_readfirstlane(r.y) >> 4;
+            states = __builtin_amdgcn_readfirstlane(r.y) & 15;
+        }
+    }
+    __device__ void init(const int2 *__restrict__ ranges, int begin, int end)
+    {
+        rg = ranges;
+        n = 0; n_end = 0; states = 0;
+        p = __builtin_amdgcn_readfirstlane(begin);
+        p_end = __builtin_amdgcn_readfirstlane(end);
+        load();
+    }
+    __device__ bool valid() const { return p < p_end; }
+    __device__ void next()
+    {
+        if (++n == n_end) { ++p; load(); }
+    }
+    __device__ int state(int grp) const { return grp ? (states & 3) : (states >> 2); }  // 0 skip 1 partial 2 full
+};
+
+// One workgroup = two groups of four waves = one work unit: two (head, query tile) items that
+// read the same KV head and walk one merged key-tile list (heads of a GQA group with the same
+// class, or two neighbouring query tiles of one head), so each K / V^T tile is fetched ONCE for
+// 256 query rows.  The tiles live in a shared ring of 3 K + 3 V^T slots.  Per key tile a group
+// runs two phases:
 //   X (matrix):  O += P(k-1) V(k-1)  and  S(k) = K(k) Q^T        -- MFMA + LDS reads only
 //   Y (vector):  mask, online softmax of S(k) -> P(k), rescale O  -- VALU only
-// separated by workgroup barriers.  The second group starts half a step late, so on every SIMD
+// separated by workgroup barriers.  The second group runs half a step late, so on every SIMD
 // one wave is in X while the other is in Y: the matrix pipe and the vector ALU stay busy
 // together instead of the two waves queueing for the same unit.
 template <int D>
-__global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(KernelArgs a, BS_MAP_PARAMS,
-                                                                         const int32_t *__restrict__ map_row_tiles,
-                                                                         int32_t n_work, const __bf16 *__restrict__ kp,
-                                                                         const __bf16 *__restrict__ vt, int32_t n_k_tiles)
+__global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(
+    KernelArgs a, const uint32_t *__restrict__ map_code, const uint64_t *__restrict__ map_text_bits,
+    const uint64_t *__restrict__ map_sink_bits, const int2 *__restrict__ map_span_range,
+    const uint8_t *__restrict__ map_head_class, const int4 *__restrict__ pair_items,
+    const int2 *__restrict__ pair_ranges, const __bf16 *__restrict__ kp, const __bf16 *__restrict__ vt,
+    int32_t n_k_tiles)
 {
-    constexpr int ROW = D * 2;            // bytes per K / V row in LDS
-    constexpr int TILE = kBlockN * ROW;   // bytes per K or V tile
-    constexpr int DMA_PER_THREAD = D / 32;  // LDS-direct loads per thread per matrix per tile
+    constexpr int ROW = D * 2;            // bytes per K row in LDS
+    constexpr int TILE = kBlockN * ROW;   // bytes per K or V^T tile
+    constexpr int DMA_PER_WAVE = D / 64;  // LDS-direct loads per wave per matrix per tile (8 waves)
     constexpr int NDB = D / 32;           // 32-channel blocks of the output
     constexpr int NT = D / 16;            // 16-wide slices of the head dim
-    extern __shared__ __align__(1024) unsigned char lds[];
+    extern __shared__ __align__(1024) unsigned char lds[];   // K slots 0..2, then V^T slots 0..2
 
     const int tid = threadIdx.x, lane = tid & 63, hl = lane >> 5, col = lane & 31;
     const int grp = __builtin_amdgcn_readfirstlane(tid >> 8);          // wave group 0 / 1
     const int wave = __builtin_amdgcn_readfirstlane((tid >> 6) & 3);   // wave within the group
+    const int wave8 = __builtin_amdgcn_readfirstlane(tid >> 6);        // wave within the workgroup
     const int L = a.L;
 
-    // this group's work item, and the step count both groups must agree on
-    int my_tiles = 0, other_tiles = 0, head = 0, m = 0, cls = 0;
-    {
-        const int mine = 2 * blockIdx.x + grp, other = 2 * blockIdx.x + (grp ^ 1);
-        if (mine < n_work) {
-            const int2 it = map_work[mine];
-            head = it.x; m = it.y; cls = map_head_class[head];
-            my_tiles = map_row_tiles[cls * a.M + m];
-        }
-        if (other < n_work) {
-            const int2 it = map_work[other];
-            other_tiles = map_row_tiles[map_head_class[it.x] * a.M + it.y];
-        }
-    }
-    const bool have_item = 2 * blockIdx.x + grp < n_work;
-    // wave-uniform by construction; say so, so that addresses built from them stay scalar
-    head = __builtin_amdgcn_readfirstlane(head);
-    m = __builtin_amdgcn_readfirstlane(m);
-    cls = __builtin_amdgcn_readfirstlane(cls);
-    const int T = __builtin_amdgcn_readfirstlane(my_tiles);
-    const int n_steps = (max(T, __builtin_amdgcn_readfirstlane(other_tiles)) + 2) & ~1;  // even, >= T + 1
-    const int kvh = __builtin_amdgcn_readfirstlane(head / a.G);
+    // the work unit and this group's item in it
+    const int4 it0 = pair_items[2 * blockIdx.x], it1 = pair_items[2 * blockIdx.x + 1];
+    const int head = __builtin_amdgcn_readfirstlane(grp ? it0.z : it0.x);
+    const int m = __builtin_amdgcn_readfirstlane(grp ? it0.w : it0.y);
+    const bool have_item = head >= 0;
+    const int T = __builtin_amdgcn_readfirstlane(it1.z);            // key tiles in the merged list
+    const int n_steps = T + 1;                                      // the last step only adds P(T-1) V(T-1)
+    const int hsafe = max(head, 0);
+    const int cls = __builtin_amdgcn_readfirstlane((int)map_head_class[hsafe]);
+    const int kvh = __builtin_amdgcn_readfirstlane(it0.x / a.G);    // both items share it
     const int row = m * kBlockM + wave * 32 + col;
 
-    const __bf16 *qh = reinterpret_cast<const __bf16 *>(a.q) + (size_t)head * L * D;
+    const __bf16 *qh = reinterpret_cast<const __bf16 *>(a.q) + (size_t)hsafe * L * D;
     // packed K and V^T tiles of this KV head (one TILE-byte block per key tile)
     const char *kph = reinterpret_cast<const char *>(kp + (size_t)kvh * n_k_tiles * (size_t)(D * kBlockN));
     const char *vth = reinterpret_cast<const char *>(vt + (size_t)kvh * n_k_tiles * (size_t)(D * kBlockN));
@@ -452,15 +530,11 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(KernelA
     QueryView qv;
     qv.init(map_code, map_span_range, L, cls, row);
 
-    // LDS byte addresses of this lane's MFMA operand fragments inside the group's ring.
-    //   ring layout: K slot 0, K slot 1, V^T slot 0, V^T slot 1 (TILE bytes each)
-    //   K fragment t: tile row col (+32 kb), logical chunk 2t + hl of the row's D/8 chunks
-    //   V^T fragment of MFMA group g: tile row 32db + col, logical chunk 2g + hl of 8
-    //   both swizzles only touch address bits that t / g also select, so the fragment sits at
-    //   the base address XOR (t << 5) resp. (g << 5); kb and db are immediate offsets
-    const uint32_t ring = (uint32_t)(uintptr_t)(lds_void_ptr)lds + grp * 4 * TILE;
-    const uint32_t kaddr0 = ring + col * ROW + ((hl ^ k_swizzle<D>(col)) << 4);
-    const uint32_t vaddr0 = ring + 2 * TILE + col * 128 + ((hl ^ ((col >> 1) & 7)) << 4);
+    // LDS byte address of this lane's MFMA operand fragments inside a K / V^T tile (see the
+    // tile layouts above): key or channel `col`, half hl; slices, blocks and groups are
+    // immediate offsets, the ring slot is added per step.
+    const uint32_t ring = (uint32_t)(uintptr_t)(lds_void_ptr)lds;
+    const uint32_t kaddr0 = ring + col * 32 + ((hl ^ ((col >> 3) & 1)) << 4);
 
     floatx16 o[NDB];
 #pragma unroll
@@ -479,23 +553,20 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(KernelA
         for (int e = 0; e < 8; ++e) pf[i >> 1][i & 1][e] = (__bf16)0.f;
     float m_run = -INFINITY, l_run = 0.f;
 
-    // three walkers over the item's tile list: w0 names the tile of the current step (mask and
-    // FULL flag), w1 the next tile (V^T refill), w2 the one after (K refill)
-    TileWalker w0, w1, w2;
-    {
-        const int rb = map_row_ptr[cls * (a.M + 1) + m], re = have_item ? map_row_ptr[cls * (a.M + 1) + m + 1] : rb;
-        w0.init(map_ranges, rb, re);
-        w1 = w0; if (w1.valid()) w1.next();
-        w2 = w1; if (w2.valid()) w2.next();
-    }
+    // three walkers over the merged tile list: w0 names the tile of the current step (state),
+    // w1 the next tile (V^T refill), w2 the one after (K refill)
+    PairWalker w0, w1, w2;
+    w0.init(pair_ranges, it1.x, it1.y);
+    w1 = w0; if (w1.valid()) w1.next();
+    w2 = w1; if (w2.valid()) w2.next();
 
-    // LDS-direct loads of one packed tile into a ring slot: a straight TILE-byte copy.  Each
-    // wave instruction moves 1 KB (lane l -> bytes 16l..16l+15); instruction r of wave w covers
-    // bytes (4r + w) KB .. +1 KB of the tile.
-    const uint32_t dma_lane_off = wave * 1024 + lane * 16;
+    // LDS-direct loads of packed tiles into ring slots: straight TILE-byte copies.  Each wave
+    // instruction moves 1 KB (lane l -> bytes 16l..16l+15); instruction r of wave w (0..7) covers
+    // bytes (8r + w) KB .. +1 KB of the tile, so the eight waves together fetch a tile.
+    const uint32_t dma_lane_off = wave8 * 1024 + lane * 16;
     auto dma = [&](int r, const char *tile, int slot_byte) {
-        unsigned char *dst = lds + grp * 4 * TILE + slot_byte + wave * 1024 + r * 4 * 1024;
-        __builtin_amdgcn_global_load_lds((global_void_ptr)(tile + (dma_lane_off + r * 4 * 1024)), (lds_void_ptr)dst, 16, 0, 0);
+        unsigned char *dst = lds + slot_byte + wave8 * 1024 + r * 8 * 1024;
+        __builtin_amdgcn_global_load_lds((global_void_ptr)((tile + r * 8 * 1024) + dma_lane_off), (lds_void_ptr)dst, 16, 0, 0);
     };
     auto tile_ptr = [&](const char *base, int n) {
 #ifdef BS_PROBE_SAME_TILE
@@ -504,22 +575,21 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(KernelA
         return base + (size_t)min(n, n_k_tiles - 1) * TILE;  // a walker past its end names no tile
     };
 
-    // ---- phase X building blocks (PAR = parity of the step: K slot PAR, V^T slot PAR ^ 1) ----
+    // ---- phase X building blocks (step k reads K slot k mod 3 and V^T slot (k + 2) mod 3) ----
     // A batch is four 128-bit operand reads feeding four MFMAs:
     //   PV batch g (D = 128): O^T block db += V^T(db, group g) . P^T(group g), db = 0..3
     //   S  batch b          : head-dim slices 2b, 2b+1 for both 32-key blocks
-    auto read_pv = [&](auto par, auto g, bf16x8 (&dst)[4]) {
+    uint32_t kbase = 0, vbase = 0;  // fragment base addresses inside the ring slots of this step
+    auto read_pv = [&](auto g, bf16x8 (&dst)[4]) {
 #ifdef BS_PROBE_NO_LDSREAD
         return;
 #endif
-        constexpr int base = (decltype(par)::value ^ 1) * TILE;
-        const uint32_t addr = vaddr0 ^ (decltype(g)::value << 5);
-#pragma unroll
-        for (int db = 0; db < NDB; ++db) {
-            if (db == 0) lds_read_b128<base + 0 * 4096>(dst[0], addr);
-            if (db == 1) lds_read_b128<base + 1 * 4096>(dst[1], addr);
-            if (db == 2) lds_read_b128<base + 2 * 4096>(dst[2], addr);
-            if (db == 3) lds_read_b128<base + 3 * 4096>(dst[3], addr);
+        constexpr int base = decltype(g)::value * (D * 32);   // key group g; channel block db = +1 KB
+        lds_read_b128<base>(dst[0], vbase);
+        lds_read_b128<base + 1024>(dst[1], vbase);
+        if constexpr (NDB == 4) {
+            lds_read_b128<base + 2048>(dst[2], vbase);
+            lds_read_b128<base + 3072>(dst[3], vbase);
         }
     };
     auto mul_pv = [&](auto g, bf16x8 (&f)[4]) {
@@ -527,20 +597,23 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(KernelA
         return;
 #endif
         constexpr int G = decltype(g)::value;
-#pragma unroll
-        for (int db = 0; db < NDB; ++db)
-            o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[db], pf[G >> 1][G & 1], o[db], 0, 0, 0);
+        const bf16x8 &pg = pf[G >> 1][G & 1];
+        mfma_o<0>(o[0], f[0], pg);
+        mfma_o<1>(o[1], f[1], pg);
+        if constexpr (NDB == 4) {
+            mfma_o<2>(o[2], f[2], pg);
+            mfma_o<3>(o[3], f[3], pg);
+        }
     };
-    auto read_s = [&](auto par, auto b, bf16x8 (&dst)[4]) {
+    auto read_s = [&](auto b, bf16x8 (&dst)[4]) {
 #ifdef BS_PROBE_NO_LDSREAD
         return;
 #endif
-        constexpr int base = decltype(par)::value * TILE;
         constexpr int B = decltype(b)::value;
-        lds_read_b128<base>(dst[0], kaddr0 ^ ((2 * B) << 5));
-        lds_read_b128<base + 32 * ROW>(dst[1], kaddr0 ^ ((2 * B) << 5));
-        lds_read_b128<base>(dst[2], kaddr0 ^ ((2 * B + 1) << 5));
-        lds_read_b128<base + 32 * ROW>(dst[3], kaddr0 ^ ((2 * B + 1) << 5));
+        lds_read_b128<(2 * B) * 2048>(dst[0], kbase);            // slice 2B, keys 0..31
+        lds_read_b128<(2 * B) * 2048 + 1024>(dst[1], kbase);     // slice 2B, keys 32..63
+        lds_read_b128<(2 * B + 1) * 2048>(dst[2], kbase);
+        lds_read_b128<(2 * B + 1) * 2048 + 1024>(dst[3], kbase);
     };
     auto mul_s = [&](auto b, bf16x8 (&f)[4]) {
 #ifdef BS_PROBE_NO_MFMA
@@ -548,32 +621,33 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(KernelA
 #endif
         constexpr int B = decltype(b)::value;
         if (B == 0) {
-            const floatx16 z = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-            s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[0], qreg[0], z, 0, 0, 0);
-            s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[1], qreg[0], z, 0, 0, 0);
+            mfma_set(s[0], f[0], qreg[0]);
+            mfma_set(s[1], f[1], qreg[0]);
         } else {
-            s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[0], qreg[2 * B], s[0], 0, 0, 0);
-            s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[1], qreg[2 * B], s[1], 0, 0, 0);
+            mfma_acc(s[0], f[0], qreg[2 * B]);
+            mfma_acc(s[1], f[1], qreg[2 * B]);
         }
-        s[0] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[2], qreg[2 * B + 1], s[0], 0, 0, 0);
-        s[1] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f[3], qreg[2 * B + 1], s[1], 0, 0, 0);
+        mfma_acc(s[0], f[2], qreg[2 * B + 1]);
+        mfma_acc(s[1], f[3], qreg[2 * B + 1]);
     };
     using I0 = std::integral_constant<int, 0>;
     using I1 = std::integral_constant<int, 1>;
     using I2 = std::integral_constant<int, 2>;
     using I3 = std::integral_constant<int, 3>;
 
-    // Phase X of step k: O += P(k-1) V(k-1) and S(k) = K(k) Q^T.  Always the same straight-line sequence, so the accumulators never
-    // move between registers: before the first tile P is zero (the ring was zero-filled),
-    // after the last tile P is zero again and the scores it produces are ignored.  Operand
-    // reads run three batches ahead of the MFMAs that consume them, in three rotating register
-    // sets; each lds_wait<N> count is the number of reads issued after the batch waited for.
-    // A set is refilled right after the MFMAs that read it have issued (operands are read at
-    // issue, LDS data returns later).
-    auto phase_x = [&](auto par) {
-#ifdef BS_PROBE_NO_X
-        return;
-#endif
+    // Phase X of step k: O += P(k-1) V(k-1) and S(k) = K(k) Q^T.  Always the same straight-line
+    // sequence, so the accumulators never move between registers: before the first tile P is
+    // zero (the ring was zero-filled), after the last tile -- and on tiles this item skips --
+    // P is zero again and the scores it produces are ignored.  Operand reads run three batches
+    // ahead of the MFMAs that consume them, in three rotating register sets; each lds_wait<N>
+    // count is the number of reads issued after the batch waited for.  A set is refilled right
+    // after the MFMAs that read it have issued (operands are read at issue, LDS data returns
+    // later).
+    auto phase_x = [&](int S) __attribute__((always_inline)) {  // S = k mod 3
+        const int S1 = S == 2 ? 0 : S + 1, S2 = S == 0 ? 2 : S - 1;  // (S+1)%3, (S+2)%3
+        kbase = kaddr0 + S * TILE;
+        vbase = kaddr0 + (3 + S2) * TILE;
+#ifndef BS_PROBE_NO_X
         bf16x8 fa[4], fb[4], fc[4];
         if constexpr (NDB < 4) {
 #pragma unroll
@@ -583,43 +657,60 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(KernelA
         }
         if constexpr (D == 128) {
             // batch order: PV0 S0 PV1 S1 PV2 S2 PV3 S3, four reads each
-            read_pv(par, I0{}, fa); read_s(par, I0{}, fb); read_pv(par, I1{}, fc);
-            lds_wait<8>(fa); mul_pv(I0{}, fa); read_s(par, I1{}, fa);
-            lds_wait<8>(fb); mul_s(I0{}, fb); read_pv(par, I2{}, fb);
-            lds_wait<8>(fc); mul_pv(I1{}, fc); read_s(par, I2{}, fc);
-            lds_wait<8>(fa); mul_s(I1{}, fa); read_pv(par, I3{}, fa);
-            lds_wait<8>(fb); mul_pv(I2{}, fb); read_s(par, I3{}, fb);
+#ifdef BS_TWO_SETS
+            read_pv(I0{}, fa); read_s(I0{}, fb);
+            lds_wait<4>(fa); mul_pv(I0{}, fa); read_pv(I1{}, fa);
+            lds_wait<4>(fb); mul_s(I0{}, fb); read_s(I1{}, fb);
+            lds_wait<4>(fa); mul_pv(I1{}, fa); read_pv(I2{}, fa);
+            lds_wait<4>(fb); mul_s(I1{}, fb); read_s(I2{}, fb);
+            lds_wait<4>(fa); mul_pv(I2{}, fa); read_pv(I3{}, fa);
+            lds_wait<4>(fb); mul_s(I2{}, fb); read_s(I3{}, fb);
+            lds_wait<4>(fa); mul_pv(I3{}, fa);
+            lds_wait<0>(fb); mul_s(I3{}, fb);
+#else
+            read_pv(I0{}, fa); read_s(I0{}, fb); read_pv(I1{}, fc);
+            lds_wait<8>(fa); mul_pv(I0{}, fa); read_s(I1{}, fa);
+            lds_wait<8>(fb); mul_s(I0{}, fb); read_pv(I2{}, fb);
+            lds_wait<8>(fc); mul_pv(I1{}, fc); read_s(I2{}, fc);
+            lds_wait<8>(fa); mul_s(I1{}, fa); read_pv(I3{}, fa);
+            lds_wait<8>(fb); mul_pv(I2{}, fb); read_s(I3{}, fb);
             lds_wait<8>(fc); mul_s(I2{}, fc);
             lds_wait<4>(fa); mul_pv(I3{}, fa);
             lds_wait<0>(fb); mul_s(I3{}, fb);
+#endif
+            mfma_drain(s[0], s[1]);   // the PV accumulators finished four MFMAs earlier
         } else {
             // D == 64: PV batches hold two reads, S has two batches of four
-            read_pv(par, I0{}, fa); read_s(par, I0{}, fb); read_pv(par, I1{}, fc);   // 2 + 4 + 2
-            lds_wait<6>(fa); mul_pv(I0{}, fa); read_pv(par, I2{}, fa);    // 4 2 | 2
-            lds_wait<4>(fb); mul_s(I0{}, fb); read_s(par, I1{}, fb);      // 2 2 | 4
-            lds_wait<6>(fc); mul_pv(I1{}, fc); read_pv(par, I3{}, fc);    // 2 4 | 2
+            read_pv(I0{}, fa); read_s(I0{}, fb); read_pv(I1{}, fc);   // 2 + 4 + 2
+            lds_wait<6>(fa); mul_pv(I0{}, fa); read_pv(I2{}, fa);                // 4 2 | 2
+            lds_wait<4>(fb); mul_s(I0{}, fb); read_s(I1{}, fb);                  // 2 2 | 4
+            lds_wait<6>(fc); mul_pv(I1{}, fc); read_pv(I3{}, fc);                // 2 4 | 2
             lds_wait<6>(fa); mul_pv(I2{}, fa);
             lds_wait<2>(fb); mul_s(I1{}, fb);
             lds_wait<0>(fc); mul_pv(I3{}, fc);
+            mfma_drain(o[0], o[1]);   // the scores finished two MFMAs earlier
         }
-        // Refill the slots this phase has just finished reading: K(k+2) -> K slot par,
-        // V^T(k+1) -> V^T slot par^1.  Issued here, after the last MFMA, because LDS-direct
-        // loads issue several times slower while a wave of the same SIMD is feeding the matrix
-        // pipe; now this wave is done with it and its SIMD mate is in its vector phase.
-        // Unconditional: past the end of the list a valid tile is fetched again and never
-        // used.  The loads are waited for at the end of the NEXT step's phase Y.
+#endif
+        // Refill: this wave's share of K(k+2) -> K slot (S+2)%3 and V^T(k+1) -> V^T slot (S+1)%3,
+        // both last read one step ago by the other group.  Issued here, after the last MFMA,
+        // because LDS-direct loads issue several times slower while a wave of the same SIMD is
+        // feeding the matrix pipe.  Unconditional: past the end of the list a valid tile is
+        // fetched again and never used.  Then wait for the loads issued one step ago (only the
+        // new ones may stay in flight): with the barriers that follow, every tile is complete
+        // two half-steps before its first reader.
 #ifndef BS_PROBE_NO_DMA
         {
             __builtin_amdgcn_sched_barrier(0);
             const char *ksrc = tile_ptr(kph, w2.n), *vsrc = tile_ptr(vth, w1.n);
 #pragma unroll
-            for (int r = 0; r < DMA_PER_THREAD; ++r) dma(r, ksrc, decltype(par)::value * TILE);
+            for (int r = 0; r < DMA_PER_WAVE; ++r) dma(r, ksrc, S2 * TILE);
 #pragma unroll
-            for (int r = 0; r < DMA_PER_THREAD; ++r) dma(r, vsrc, 2 * TILE + (decltype(par)::value ^ 1) * TILE);
+            for (int r = 0; r < DMA_PER_WAVE; ++r) dma(r, vsrc, 3 * TILE + S1 * TILE);
         }
 #endif
         w1.next();
         w2.next();
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * DMA_PER_WAVE));
     };
 
     // text / sink key bits of the tile w0 names (scalar registers, fetched one step ahead)
@@ -630,27 +721,30 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(KernelA
         sb_cur = map_sink_bits[nn];
     }
     // Phase Y of step k: mask (PARTIAL tiles), online softmax, rescale O, round P to bf16.
-    auto phase_y = [&](auto par, int k) {
+    auto phase_y = [&](int k) __attribute__((always_inline)) {
 #ifdef BS_PROBE_NO_Y
         if (k < T) w0.next();
-#ifndef BS_PROBE_NO_WAIT
-        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * DMA_PER_THREAD));
-#endif
         return;
 #endif
         if (k < T) {
+            // state of the tile for this group's item: 0 skip (only the other item wants the
+            // tile), 1 partial, 2 full.  A skipped tile goes through the row-uniform path with
+            // every row dropped (P = 0, running max and sum unchanged): rare, and one straight
+            // code path keeps the register allocation of the loop simple.
+            const int st = have_item ? w0.state(grp) : 0;
             float alpha;
-            if (w0.full) {
+            if (st == 2) {
                 softmax_pack<0>(s, pf, m_run, l_run, alpha, a.scale_log2e, false);
             } else {
                 const int nu = __builtin_amdgcn_readfirstlane(w0.n);
-                const uint64_t allowed = allowed_keys(qv, tb_cur, (cls & 1) ? sb_cur : 0ull, nu * kBlockN);
+                uint64_t allowed = allowed_keys(qv, tb_cur, (cls & 1) ? sb_cur : 0ull, nu * kBlockN);
+                if (st == 0) allowed = 0ull;
                 if (__all(allowed == 0ull || allowed == ~0ull)) {
                     // every query of the wave sees all 64 keys or none (e.g. a text row and an
                     // image row over keys of another image): no per-score work
                     softmax_pack<1>(s, pf, m_run, l_run, alpha, a.scale_log2e, allowed == 0ull);
                 } else {
-                    apply_mask(s, allowed, hl);
+                    apply_mask_tight(s, allowed, hl);
                     softmax_pack<2>(s, pf, m_run, l_run, alpha, a.scale_log2e, false);
                 }
             }
@@ -662,66 +756,69 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(KernelA
             }
             w0.next();
             // key bit masks of the next tile: requested now, used one step later
-            {
-                const int nn = min(__builtin_amdgcn_readfirstlane(w0.n), n_k_tiles - 1);
-                tb_cur = map_text_bits[nn];
-                sb_cur = map_sink_bits[nn];
-            }
-        } else if (k == T) {
-            // past the last tile: phase X keeps running (the other group may have more tiles)
-            // but must add nothing
+            const int nn = min(__builtin_amdgcn_readfirstlane(w0.n), n_k_tiles - 1);
+            tb_cur = map_text_bits[nn];
+            sb_cur = map_sink_bits[nn];
+        } else {
+            // past the last tile: the final phase X adds P(T-1) V(T-1); steps after it (none
+            // today) must add nothing
 #pragma unroll
             for (int i = 0; i < 4; ++i)
 #pragma unroll
                 for (int e = 0; e < 8; ++e) pf[i >> 1][i & 1][e] = (__bf16)0.f;
         }
-        // the tiles requested one step ago have landed once only this step's loads are in flight
-        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * DMA_PER_THREAD));
     };
 
-    // Zero the group's ring once: phase X reads every slot from its first step on, and stale
-    // LDS bits could be NaN patterns (0 * NaN would poison the accumulators).
+    // Zero the ring once: phase X reads every slot from its first step on, and stale LDS bits
+    // could be NaN patterns (0 * NaN would poison the accumulators).
     {
         const uint4 z4 = make_uint4(0, 0, 0, 0);
-        unsigned char *mine = lds + grp * 4 * TILE;
-        for (int i = (tid & 255) * 16; i < 4 * TILE; i += 256 * 16) *reinterpret_cast<uint4 *>(mine + i) = z4;
+        for (int i = tid * 16; i < 6 * TILE; i += kPingPongThreads * 16) *reinterpret_cast<uint4 *>(lds + i) = z4;
     }
     __syncthreads();
     // prologue: K(0) -> K slot 0, K(1) -> K slot 1, V^T(0) -> V^T slot 0 (unconditional, clamped)
     {
         const char *k0 = tile_ptr(kph, w0.n), *k1 = tile_ptr(kph, w1.n), *v0 = tile_ptr(vth, w0.n);
 #pragma unroll
-        for (int r = 0; r < DMA_PER_THREAD; ++r) dma(r, k0, 0);
+        for (int r = 0; r < DMA_PER_WAVE; ++r) dma(r, k0, 0);
 #pragma unroll
-        for (int r = 0; r < DMA_PER_THREAD; ++r) dma(r, k1, TILE);
+        for (int r = 0; r < DMA_PER_WAVE; ++r) dma(r, k1, TILE);
 #pragma unroll
-        for (int r = 0; r < DMA_PER_THREAD; ++r) dma(r, v0, 2 * TILE);
+        for (int r = 0; r < DMA_PER_WAVE; ++r) dma(r, v0, 3 * TILE);
     }
     // Raw barriers: every LDS access of this kernel is an LDS-direct load (drained with vmcnt
-    // at the end of phase Y) or an asm read (drained with lgkmcnt inside phase X), so no fence
+    // at the end of phase X) or an asm read (drained with lgkmcnt inside phase X), so no fence
     // is wanted here -- a fence would drain loads that are meant to stay in flight.
     __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0)
     __builtin_amdgcn_s_barrier();
     if (grp == 1) __builtin_amdgcn_s_barrier();  // second group runs half a step behind
     BS_T0();
-    for (int k = 0; k < n_steps; k += 2) {
-        phase_x(I0{});
+    auto step = [&](int slot, int k) __attribute__((always_inline)) {
+        phase_x(slot);
         BS_TICK(0);
         BS_LOOP_BARRIER();
         BS_TICK(1);
-        phase_y(I0{}, k);
+        phase_y(k);
         BS_TICK(2);
         BS_LOOP_BARRIER();
         BS_TICK(3);
-        phase_x(I1{});
-        BS_TICK(0);
-        BS_LOOP_BARRIER();
-        BS_TICK(1);
-        phase_y(I1{}, k + 1);
-        BS_TICK(2);
-        BS_LOOP_BARRIER();
-        BS_TICK(3);
+    };
+#ifdef BS_UNROLL3
+    // three copies of the step, one per ring slot; both groups share n_steps, so the exits are
+    // uniform over the workgroup and every wave passes the same number of barriers
+    for (int k = 0; k < n_steps; k += 3) {
+        step(0, k);
+        if (k + 1 >= n_steps) break;
+        step(1, k + 1);
+        if (k + 2 >= n_steps) break;
+        step(2, k + 2);
     }
+#else
+    for (int k = 0, slot = 0; k < n_steps; ++k) {
+        step(slot, k);
+        slot = slot == 2 ? 0 : slot + 1;
+    }
+#endif
     if (grp == 0) __builtin_amdgcn_s_barrier();  // same barrier count for every wave of the workgroup
     BS_TFLUSH();
 
@@ -864,6 +961,7 @@ void free_device_map(DeviceMap *d)
         if (cur != d->device) (void)hipSetDevice(d->device);
         (void)hipFree(d->blob);
         if (d->vt_buf) (void)hipFree(d->vt_buf);
+        if (d->pair_blob) (void)hipFree(d->pair_blob);
         if (cur >= 0 && cur != d->device) (void)hipSetDevice(cur);
     }
     delete d;
@@ -1011,9 +1109,36 @@ extern "C" int bs_attn_prefill_ex(const void *q, const void *k, const void *v, v
         }
         __bf16 *kp = static_cast<__bf16 *>(d->vt_buf);
         __bf16 *vt = reinterpret_cast<__bf16 *>(static_cast<char *>(d->vt_buf) + pack_bytes);
+        // work units: pairs of items that share a KV head (depends on gqa_group; cached)
+        if (d->pair_G != gqa_group) {
+            try {
+                bs_plan_pairs(tm, gqa_group);
+            } catch (const std::bad_alloc &) {
+                return BS_ENOMEM;
+            }
+            const bs::PairPlan &plan = tm->pairs;
+            if (plan.ranges.size() >= (size_t)INT32_MAX) return BS_EUNSUPPORTED;
+            if (d->pair_blob) {
+                e = hipFree(d->pair_blob);  // synchronises: earlier launches that read it are done
+                d->pair_blob = nullptr; d->pair_G = 0;
+                if (e != hipSuccess) return bs::fail_hip(e, "hipFree(work units)");
+            }
+            const size_t items_bytes = (plan.items.size() * sizeof(bs::PairItem) + 255) & ~(size_t)255;
+            const size_t ranges_bytes = std::max<size_t>(plan.ranges.size(), 1) * sizeof(bs::PairRange);
+            e = hipMalloc(&d->pair_blob, items_bytes + ranges_bytes);
+            if (e != hipSuccess) { d->pair_blob = nullptr; return bs::fail_hip(e, "hipMalloc(work units)"); }
+            e = hipMemcpy(d->pair_blob, plan.items.data(), plan.items.size() * sizeof(bs::PairItem), hipMemcpyHostToDevice);
+            if (e == hipSuccess && !plan.ranges.empty())
+                e = hipMemcpy(static_cast<char *>(d->pair_blob) + items_bytes, plan.ranges.data(),
+                              plan.ranges.size() * sizeof(bs::PairRange), hipMemcpyHostToDevice);
+            if (e != hipSuccess) return bs::fail_hip(e, "hipMemcpy(work units)");
+            d->pair_items = static_cast<const int4 *>(d->pair_blob);
+            d->pair_ranges = reinterpret_cast<const int2 *>(static_cast<char *>(d->pair_blob) + items_bytes);
+            d->n_pairs = (int32_t)plan.items.size();
+            d->pair_G = gqa_group;
+        }
         const dim3 tgrid((unsigned)tm->N, (unsigned)n_kv_heads);
-        // two work items per workgroup (one per wave group)
-        const dim3 pgrid((unsigned)((d->n_work + 1) / 2)), pblock(bs::kPingPongThreads);
+        const dim3 pgrid((unsigned)d->n_pairs), pblock(bs::kPingPongThreads);
         if (head_dim == 128) {
             constexpr int lds = bs::bf16_lds_bytes<128>();
             e = hipFuncSetAttribute(reinterpret_cast<const void *>(bs::attn_prefill_bf16<128>),
@@ -1022,7 +1147,8 @@ extern "C" int bs_attn_prefill_ex(const void *q, const void *k, const void *v, v
             hipLaunchKernelGGL(bs::pack_k_tiles<128>, tgrid, dim3(256), 0, st, static_cast<const __bf16 *>(k), kp, tm->L, tm->N);
             hipLaunchKernelGGL(bs::pack_vt_tiles<128>, tgrid, dim3(256), 0, st, static_cast<const __bf16 *>(v), vt, tm->L, tm->N);
             if (ev_main_start) (void)hipEventRecord(static_cast<hipEvent_t>(ev_main_start), st);
-            hipLaunchKernelGGL(bs::attn_prefill_bf16<128>, pgrid, pblock, lds, st, a, BS_MAP_ARGS(d), d->row_tiles, d->n_work, kp, vt, tm->N);
+            hipLaunchKernelGGL(bs::attn_prefill_bf16<128>, pgrid, pblock, lds, st, a, d->code, d->text_bits, d->sink_bits,
+                               d->span_range, d->head_class, d->pair_items, d->pair_ranges, kp, vt, tm->N);
         } else {
             constexpr int lds = bs::bf16_lds_bytes<64>();
             e = hipFuncSetAttribute(reinterpret_cast<const void *>(bs::attn_prefill_bf16<64>),
@@ -1031,7 +1157,8 @@ extern "C" int bs_attn_prefill_ex(const void *q, const void *k, const void *v, v
             hipLaunchKernelGGL(bs::pack_k_tiles<64>, tgrid, dim3(256), 0, st, static_cast<const __bf16 *>(k), kp, tm->L, tm->N);
             hipLaunchKernelGGL(bs::pack_vt_tiles<64>, tgrid, dim3(256), 0, st, static_cast<const __bf16 *>(v), vt, tm->L, tm->N);
             if (ev_main_start) (void)hipEventRecord(static_cast<hipEvent_t>(ev_main_start), st);
-            hipLaunchKernelGGL(bs::attn_prefill_bf16<64>, pgrid, pblock, lds, st, a, BS_MAP_ARGS(d), d->row_tiles, d->n_work, kp, vt, tm->N);
+            hipLaunchKernelGGL(bs::attn_prefill_bf16<64>, pgrid, pblock, lds, st, a, d->code, d->text_bits, d->sink_bits,
+                               d->span_range, d->head_class, d->pair_items, d->pair_ranges, kp, vt, tm->N);
         }
     } else {
         if (ev_main_start) (void)hipEventRecord(static_cast<hipEvent_t>(ev_main_start), st);

@@ -8,6 +8,7 @@
 // key tile, an image-only query tile walks only tiles that hold a text key, an enabled sink
 // key, or a key of its own image.
 #include <algorithm>
+#include <climits>
 #include <cstring>
 #include <new>
 
@@ -340,6 +341,194 @@ extern "C" int bs_build_tilemap(const bs_span *spans, int32_t n_spans, int32_t s
         return BS_ENOMEM;
     }
     *out = tm;
+    return BS_OK;
+}
+
+// Pairing for the KV-sharing bf16 kernel.  Three rules, all exact (no approximation, only a
+// different grouping of the same work), applied inside each KV group:
+//   1. heads that carry the same class walk identical lists at the same query tile: pair them
+//      two by two (no step is wasted);
+//   2. heads left over with different classes may be paired at the same query tile: their lists
+//      are merged and each run records the state for either item (a tile only one of them needs
+//      is a SKIP step for the other).  Good when most query tiles mix text and image rows (then
+//      both walk every causal tile anyway), bad when one class visits far more tiles;
+//   3. a left-over head pairs its own query tiles 2j and 2j+1 the same way.
+// Rule 2 is used for a pair of left-over heads only if it needs fewer steps than rule 3 for both.
+void bs_plan_pairs(bs_tilemap *tm, int32_t G)
+{
+    bs::PairPlan &plan = tm->pairs;
+    if (plan.gqa_group == G) return;
+    plan.ranges.clear();
+    plan.items.clear();
+    const int32_t M = tm->M, H = tm->n_q_heads;
+
+    // merged list of (class ca, row ma) and (class cb, row mb); cb < 0: item A alone
+    struct Span2 { int32_t begin, end, tiles; };
+    bool count_only = false;
+    auto merged = [&](int ca, int32_t ma, int cb, int32_t mb) {
+        const ClassLists &la = tm->cls[ca];
+        const ClassLists &lb = tm->cls[cb < 0 ? ca : cb];
+        int64_t pa = la.row_ptr[ma], ea = la.row_ptr[ma + 1];
+        int64_t pb = cb < 0 ? 0 : lb.row_ptr[mb], eb = cb < 0 ? 0 : lb.row_ptr[mb + 1];
+        Span2 out{(int32_t)plan.ranges.size(), 0, 0};
+        int32_t cur = 0, rb = -1, re = -1, rs = 0;
+        auto emit = [&](int32_t b, int32_t e, int sa, int sb) {
+            if (e <= b || (sa == 0 && sb == 0)) return;
+            out.tiles += e - b;
+            const int st = (sa << 2) | sb;
+            if (count_only) return;
+            if (rb >= 0 && b == re && st == rs) { re = e; return; }
+            if (rb >= 0) plan.ranges.push_back({rb, (re << 4) | rs});
+            rb = b; re = e; rs = st;
+        };
+        while (pa < ea || pb < eb) {
+            while (pa < ea && la.ranges[pa].end() <= cur) ++pa;
+            while (pb < eb && lb.ranges[pb].end() <= cur) ++pb;
+            if (pa >= ea && pb >= eb) break;
+            const bool in_a = pa < ea && la.ranges[pa].begin <= cur;
+            const bool in_b = pb < eb && lb.ranges[pb].begin <= cur;
+            int32_t nxt = INT32_MAX;  // next boundary after cur
+            if (pa < ea) nxt = std::min(nxt, in_a ? la.ranges[pa].end() : la.ranges[pa].begin);
+            if (pb < eb) nxt = std::min(nxt, in_b ? lb.ranges[pb].end() : lb.ranges[pb].begin);
+            emit(cur, nxt, in_a ? (la.ranges[pa].full() ? 2 : 1) : 0, in_b ? (lb.ranges[pb].full() ? 2 : 1) : 0);
+            cur = nxt;
+        }
+        if (rb >= 0) plan.ranges.push_back({rb, (re << 4) | rs});
+        out.end = (int32_t)plan.ranges.size();
+        return out;
+    };
+    // lists shared by many units are made once: key (ca, cb or 4 for "alone"/same row pair kind, row)
+    std::vector<Span2> cache_same[4], cache_cross[4][4], cache_rows[4], cache_alone[4];
+    auto cached = [&](std::vector<Span2> &tab, int32_t idx, int32_t size, auto make) -> const Span2 & {
+        if (tab.empty()) tab.assign(size, Span2{-1, -1, 0});
+        if (tab[idx].begin < 0) tab[idx] = make();
+        return tab[idx];
+    };
+
+    // total steps of rule 2 for a class pair / of rule 3 for a class, over all query tiles
+    int64_t cross_total[4][4], rows_total[4];
+    for (int a = 0; a < 4; ++a) { rows_total[a] = -1; for (int b = 0; b < 4; ++b) cross_total[a][b] = -1; }
+    auto cross_cost = [&](int ca, int cb) {
+        if (cross_total[ca][cb] < 0) {
+            count_only = true;
+            int64_t t = 0;
+            for (int32_t m = 0; m < M; ++m) t += merged(ca, m, cb, m).tiles;
+            count_only = false;
+            cross_total[ca][cb] = cross_total[cb][ca] = t;
+        }
+        return cross_total[ca][cb];
+    };
+    auto rows_cost = [&](int c) {
+        if (rows_total[c] < 0) {
+            count_only = true;
+            int64_t t = 0;
+            for (int32_t j = 0; 2 * j < M; ++j)
+                t += (2 * j + 1 < M) ? merged(c, 2 * j, c, 2 * j + 1).tiles : merged(c, 2 * j, -1, 0).tiles;
+            count_only = false;
+            rows_total[c] = t;
+        }
+        return rows_total[c];
+    };
+
+    std::vector<int32_t> byclass[4], rest, solo;
+    for (int32_t kv = 0; kv < H / G; ++kv) {
+        for (int c = 0; c < 4; ++c) byclass[c].clear();
+        for (int32_t h = kv * G; h < (kv + 1) * G; ++h) byclass[tm->head_class[h]].push_back(h);
+        rest.clear();
+        for (int c = 0; c < 4; ++c) {
+            size_t i = 0;
+            for (; i + 1 < byclass[c].size(); i += 2)  // rule 1
+                for (int32_t m = 0; m < M; ++m) {
+                    const Span2 &sp = cached(cache_same[c], m, M, [&] { return merged(c, m, c, m); });
+                    plan.items.push_back({byclass[c][i], m, byclass[c][i + 1], m, sp.begin, sp.end, sp.tiles, 0});
+                }
+            if (i < byclass[c].size()) rest.push_back(byclass[c][i]);
+        }
+        // rule 2 where it saves steps over rule 3: repeatedly take the pair with the best saving
+        solo.clear();
+        while (rest.size() >= 2) {
+            int64_t best = 0;
+            size_t bi = 0, bj = 0;
+            for (size_t i = 0; i < rest.size(); ++i)
+                for (size_t j = i + 1; j < rest.size(); ++j) {
+                    const int ca = tm->head_class[rest[i]], cb = tm->head_class[rest[j]];
+                    const int64_t saving = rows_cost(ca) + rows_cost(cb) - cross_cost(ca, cb);
+                    if (saving > best) { best = saving; bi = i; bj = j; }
+                }
+            if (best <= 0) break;
+            const int32_t ha = rest[bi], hb = rest[bj];
+            const int ca = tm->head_class[ha], cb = tm->head_class[hb];
+            for (int32_t m = 0; m < M; ++m) {
+                const Span2 &sp = cached(cache_cross[ca][cb], m, M, [&] { return merged(ca, m, cb, m); });
+                plan.items.push_back({ha, m, hb, m, sp.begin, sp.end, sp.tiles, 0});
+            }
+            rest.erase(rest.begin() + bj);
+            rest.erase(rest.begin() + bi);
+        }
+        for (int32_t h : rest) {  // rule 3
+            const int c = tm->head_class[h];
+            for (int32_t j = 0; 2 * j < M; ++j) {
+                if (2 * j + 1 < M) {
+                    const Span2 &sp = cached(cache_rows[c], j, (M + 1) / 2, [&] { return merged(c, 2 * j, c, 2 * j + 1); });
+                    plan.items.push_back({h, 2 * j, h, 2 * j + 1, sp.begin, sp.end, sp.tiles, 0});
+                } else {
+                    const Span2 &sp = cached(cache_alone[c], 0, 1, [&] { return merged(c, 2 * j, -1, 0); });
+                    plan.items.push_back({h, 2 * j, -1, 0, sp.begin, sp.end, sp.tiles, 0});
+                }
+            }
+        }
+    }
+    std::stable_sort(plan.items.begin(), plan.items.end(),
+                     [](const bs::PairItem &a, const bs::PairItem &b) { return a.n_tiles > b.n_tiles; });
+    plan.gqa_group = G;
+}
+
+extern "C" int bs_tilemap_pair_plan(bs_tilemap *tm, int32_t gqa_group, int64_t *n_units, int64_t *unit_tiles,
+                                    int64_t *skip_steps)
+{
+    if (!tm || gqa_group <= 0 || tm->n_q_heads % gqa_group != 0) return BS_EINVAL;
+    try {
+        bs_plan_pairs(tm, gqa_group);
+        // check the plan against the per-class lists it was derived from
+        const bs::PairPlan &plan = tm->pairs;
+        std::vector<uint8_t> want_a(tm->N), want_b(tm->N), got_a(tm->N), got_b(tm->N);
+        std::vector<int32_t> seen((size_t)tm->n_q_heads * tm->M, 0);
+        int64_t tiles = 0, skips = 0;
+        for (const bs::PairItem &it : plan.items) {
+            if (it.head_a < 0 || it.head_a >= tm->n_q_heads || it.tile_a < 0 || it.tile_a >= tm->M) return BS_EINVAL;
+            if (it.head_b >= tm->n_q_heads || (it.head_b >= 0 && (it.tile_b < 0 || it.tile_b >= tm->M))) return BS_EINVAL;
+            if (it.head_b >= 0 && it.head_b / gqa_group != it.head_a / gqa_group) return BS_EINVAL;
+            ++seen[(size_t)it.head_a * tm->M + it.tile_a];
+            if (it.head_b >= 0) ++seen[(size_t)it.head_b * tm->M + it.tile_b];
+            std::fill(got_a.begin(), got_a.end(), 0);
+            std::fill(got_b.begin(), got_b.end(), 0);
+            int32_t prev_end = 0, n_tiles = 0;
+            for (int32_t p = it.list_begin; p < it.list_end; ++p) {
+                const bs::PairRange &r = plan.ranges[p];
+                const int32_t e = r.end_states >> 4, sa = (r.end_states >> 2) & 3, sb = r.end_states & 3;
+                if (r.begin < prev_end || e <= r.begin || e > tm->N || (sa == 0 && sb == 0) || sa == 3 || sb == 3) return BS_EINVAL;
+                for (int32_t n = r.begin; n < e; ++n) { got_a[n] = (uint8_t)sa; got_b[n] = (uint8_t)sb; }
+                skips += (int64_t)(e - r.begin) * ((sa == 0) + (sb == 0 && it.head_b >= 0));
+                n_tiles += e - r.begin;
+                prev_end = e;
+            }
+            if (n_tiles != it.n_tiles) return BS_EINVAL;
+            tiles += n_tiles;
+            if (bs_tilemap_tile_states(tm, tm->head_class[it.head_a], it.tile_a, 1, want_a.data()) != BS_OK) return BS_EINVAL;
+            if (want_a != got_a) return BS_EINVAL;
+            if (it.head_b >= 0) {
+                if (bs_tilemap_tile_states(tm, tm->head_class[it.head_b], it.tile_b, 1, want_b.data()) != BS_OK) return BS_EINVAL;
+                if (want_b != got_b) return BS_EINVAL;
+            }
+        }
+        for (int32_t v : seen)
+            if (v != 1) return BS_EINVAL;  // every (head, query tile) exactly once
+        if (n_units) *n_units = (int64_t)plan.items.size();
+        if (unit_tiles) *unit_tiles = tiles;
+        if (skip_steps) *skip_steps = skips;
+    } catch (const std::bad_alloc &) {
+        return BS_ENOMEM;
+    }
     return BS_OK;
 }
 

@@ -30,9 +30,34 @@ struct ClassLists {
 
 struct WorkItem { int32_t head, q_tile; };
 
+// Work unit of the bf16 kernel: two (head, query tile) items that read the SAME KV head and walk
+// one merged key-tile list, so a workgroup streams each K / V tile once for both.
+//   item B is absent when head_b < 0.
+struct PairItem {
+    int32_t head_a, tile_a, head_b, tile_b;
+    int32_t list_begin, list_end;  // entries of PairPlan::ranges
+    int32_t n_tiles;               // key tiles in the merged list (scheduling weight)
+    int32_t pad;
+};
+
+// Run of key tiles [begin, end) with one state per item: 0 skip, 1 partial, 2 full.
+struct PairRange {
+    int32_t begin;
+    int32_t end_states;  // (end << 4) | (state_a << 2) | state_b
+};
+
+struct PairPlan {
+    int32_t gqa_group = 0;  // the plan depends on which heads share a KV head
+    std::vector<PairRange> ranges;
+    std::vector<PairItem> items;  // heaviest first
+};
+
 struct DeviceMap;  // defined by the HIP side
 
 }  // namespace bs
+
+// Pair up the work items for KV-sharing workgroups (host only; see PairItem).
+void bs_plan_pairs(bs_tilemap *tm, int32_t gqa_group);
 
 struct bs_tilemap {
     int32_t L = 0, bm = 0, bn = 0, M = 0, N = 0, n_q_heads = 0, sink_len = 0;
@@ -43,6 +68,7 @@ struct bs_tilemap {
     std::vector<uint64_t> sink_bits;       // N: same for sink keys
     bs::ClassLists cls[4];
     std::vector<bs::WorkItem> work;        // n_q_heads * M items, heaviest first
+    bs::PairPlan pairs;                    // built on first use for a given gqa_group
     bs::DeviceMap *dev = nullptr;          // created lazily by bs_tilemap_upload
     void (*dev_free)(bs::DeviceMap *) = nullptr;
 };

@@ -105,6 +105,47 @@ def test_states_do_not_depend_on_head_classes():
         assert a.stats(c) == b.stats(c)
 
 
+# ------------------------------------------------------------------------- work units (KV-sharing pairs)
+
+@pytest.mark.parametrize("seed", range(12))
+def test_pair_plan_random_prompts(seed):
+    rng = np.random.default_rng(100 + seed)
+    runs = [("T", int(rng.integers(0, 200)))]
+    for _ in range(int(rng.integers(1, 7))):
+        runs += [("I", int(rng.integers(1, 900))), ("T", int(rng.integers(0, 70)))]
+    G = [1, 2, 3, 7][seed % 4]
+    n_kv = [1, 2, 3][seed % 3]
+    hc = rng.integers(0, 4, size=G * n_kv).astype(np.uint8)
+    L, spans = W.layout_from_runs(runs, "paper10")
+    if L == 0:
+        return
+    tm = bs.bs_build_tilemap(spans, L, hc, int(rng.integers(0, min(L, 40) + 1)))
+    plan = tm.pair_plan(G)          # BS_OK only if the plan reproduces every item's tile states
+    per_class = [tm.stats(c) for c in range(4)]
+    item_tiles = sum(per_class[int(c)]["visited"] for c in hc)
+    n_items = len(hc) * tm.n_q_tiles
+    assert n_items / 2 <= plan["n_units"] <= n_items
+    # every item's tiles are covered; a unit step serves one or two items
+    assert plan["unit_tiles"] * 2 - plan["skip_steps"] - (2 * plan["n_units"] - n_items) * 0 >= item_tiles
+    assert plan["unit_tiles"] <= item_tiles
+    # planning again for another group size replaces the plan
+    if len(hc) % 2 == 0:
+        tm.pair_plan(2)
+    tm.pair_plan(G)
+
+
+@pytest.mark.parametrize("cfg", [1, 2, 5])
+def test_pair_plan_configs(cfg):
+    p = W.config(cfg)
+    tm = bs.bs_build_tilemap(p.spans, p.seq_len, p.head_class, p.sink_len)
+    plan = tm.pair_plan(p.gqa_group)
+    per_class = [tm.stats(c) for c in range(4)]
+    item_tiles = sum(per_class[int(c)]["visited"] for c in p.head_class)
+    assert item_tiles / 2 <= plan["unit_tiles"] <= item_tiles
+    with pytest.raises(bs.BlindsightError):
+        tm.pair_plan(5 if p.n_q_heads % 5 else 0)
+
+
 # ------------------------------------------------------------------------- error behaviour
 
 def _raw_build(spans, n_spans, L, hc, nh, sink_len, bm, bn, out):
