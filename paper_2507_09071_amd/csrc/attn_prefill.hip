@@ -253,10 +253,16 @@ __device__ inline void softmax_pack(const floatx16 (&s)[2], bf16x8 (&pf)[2][2], 
         for (int i = 0; i < 4; ++i) mx[i] = fmaxf(fmaxf(mx[i], s[i >> 1][8 * (i & 1) + v]), s[i >> 1][8 * (i & 1) + v + 1]);
     float mxl = max_across_halves(fmaxf(fmaxf(mx[0], mx[1]), fmaxf(mx[2], mx[3])));
     if (MODE == 1) mxl = drop ? -INFINITY : mxl;
-    const float m_new = fmaxf(m_run, mxl);
+    // Lazy reference point: the running reference m only moves when the tile maximum exceeds it
+    // by more than kLazyLog2 (in the exp2 domain), so p <= 2^kLazyLog2 instead of p <= 1.  The
+    // result is the same quotient O / l; what changes is that alpha is exactly 1 on almost every
+    // tile after the first few, and the rescaling of the 64 output accumulators is skipped.
+    constexpr float kLazyLog2 = 8.f;
+    const bool grow = fmaf(mxl, c, -(m_run * c)) > kLazyLog2;   // m_run = -inf, mxl finite: +inf > 8
+    const float m_new = grow ? mxl : m_run;                     // both -inf: NaN > 8 is false
     const float m_use = (MODE != 0 && m_new == -INFINITY) ? 0.f : m_new;  // no key seen so far: p = 0
     const float mc = m_use * c;
-    alpha = __builtin_amdgcn_exp2f(fmaf(m_run, c, -mc));  // m_run = -inf -> 0
+    alpha = grow ? __builtin_amdgcn_exp2f(fmaf(m_run, c, -mc)) : 1.f;     // m_run = -inf -> 0
     const float off = (MODE == 1 && drop) ? -INFINITY : -mc;
     float sum[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -310,37 +316,6 @@ __device__ inline void mfma_set(floatx16 &c, const bf16x8 &a, const bf16x8 &b)  
 {
     asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, 0" : "=&v"(c) : "v"(a), "v"(b));
 }
-// The output accumulators O^T live in v64..v127 for the whole main loop: every statement that
-// touches them there is asm with the register named in the constraint, so the allocator has no
-// choice to make (left alone it moves the 64 registers around once or twice per step).
-template <int DB>
-__device__ inline void mfma_o(floatx16 &c, const bf16x8 &a, const bf16x8 &b)
-{
-    if constexpr (DB == 0) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(c) : "v"(a), "v"(b));
-    if constexpr (DB == 1) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(c) : "v"(a), "v"(b));
-    if constexpr (DB == 2) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(c) : "v"(a), "v"(b));
-    if constexpr (DB == 3) asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %2, %0" : "+v"(c) : "v"(a), "v"(b));
-}
-#define BS_MUL4(r0, r1, r2, r3) \
-    "v_mul_f32 v" #r0 ", v" #r0 ", %1\n\tv_mul_f32 v" #r1 ", v" #r1 ", %1\n\t" \
-    "v_mul_f32 v" #r2 ", v" #r2 ", %1\n\tv_mul_f32 v" #r3 ", v" #r3 ", %1\n\t"
-template <int DB>
-__device__ inline void scale_o(floatx16 &c, float alpha)
-{
-    if constexpr (DB == 0)
-        asm(BS_MUL4(64, 65, 66, 67) BS_MUL4(68, 69, 70, 71) BS_MUL4(72, 73, 74, 75) BS_MUL4(76, 77, 78, 79)
-            : "+{v[64:79]}"(c) : "v"(alpha));
-    if constexpr (DB == 1)
-        asm(BS_MUL4(80, 81, 82, 83) BS_MUL4(84, 85, 86, 87) BS_MUL4(88, 89, 90, 91) BS_MUL4(92, 93, 94, 95)
-            : "+{v[80:95]}"(c) : "v"(alpha));
-    if constexpr (DB == 2)
-        asm(BS_MUL4(96, 97, 98, 99) BS_MUL4(100, 101, 102, 103) BS_MUL4(104, 105, 106, 107) BS_MUL4(108, 109, 110, 111)
-            : "+{v[96:111]}"(c) : "v"(alpha));
-    if constexpr (DB == 3)
-        asm(BS_MUL4(112, 113, 114, 115) BS_MUL4(116, 117, 118, 119) BS_MUL4(120, 121, 122, 123) BS_MUL4(124, 125, 126, 127)
-            : "+{v[112:127]}"(c) : "v"(alpha));
-}
-#undef BS_MUL4
 // 16 wait states: more than the 8 passes of a 32x32x16 MFMA plus the result write-back.
 __device__ inline void mfma_drain(floatx16 &c0, floatx16 &c1)
 {
@@ -438,6 +413,11 @@ __device__ inline unsigned long long bs_now(floatx16 &a, floatx16 &b, floatx16 &
 #define BS_TICK(slot) do {} while (0)
 #define BS_TFLUSH() do {} while (0)
 #endif
+
+// Batch tags of the matrix phase: four operand reads + four MFMAs each.
+template <int G> struct PvBatch { static constexpr int kind = 1, idx = G; static constexpr bool first = false; };            // O^T += V^T(group G) P^T(group G)
+template <int B, bool FIRST> struct ScBatch { static constexpr int kind = 2, idx = B; static constexpr bool first = FIRST; }; // S += K(slices 2B, 2B+1) Q^T
+struct NoBatch { static constexpr int kind = 0, idx = 0; static constexpr bool first = false; };
 
 template <int D>
 constexpr int bf16_lds_bytes() { return 6 /*3 K + 3 V^T slots*/ * kBlockN * D * 2; }
@@ -580,55 +560,31 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(
     //   PV batch g (D = 128): O^T block db += V^T(db, group g) . P^T(group g), db = 0..3
     //   S  batch b          : head-dim slices 2b, 2b+1 for both 32-key blocks
     uint32_t kbase = 0, vbase = 0;  // fragment base addresses inside the ring slots of this step
-    auto read_pv = [&](auto g, bf16x8 (&dst)[4]) {
+    // one operand read / one MFMA of a batch (element i = 0..3)
+    auto read_one = [&](auto tag, auto ic, bf16x8 &dst) __attribute__((always_inline)) {
 #ifdef BS_PROBE_NO_LDSREAD
         return;
 #endif
-        constexpr int base = decltype(g)::value * (D * 32);   // key group g; channel block db = +1 KB
-        lds_read_b128<base>(dst[0], vbase);
-        lds_read_b128<base + 1024>(dst[1], vbase);
-        if constexpr (NDB == 4) {
-            lds_read_b128<base + 2048>(dst[2], vbase);
-            lds_read_b128<base + 3072>(dst[3], vbase);
+        using T = decltype(tag);
+        constexpr int i = decltype(ic)::value;
+        if constexpr (T::kind == 1) {
+            if constexpr (i < NDB) lds_read_b128<T::idx * (D * 32) + i * 1024>(dst, vbase);   // channel block i
+        } else if constexpr (T::kind == 2) {
+            lds_read_b128<(2 * T::idx + (i >> 1)) * 2048 + (i & 1) * 1024>(dst, kbase);        // slice, key block
         }
     };
-    auto mul_pv = [&](auto g, bf16x8 (&f)[4]) {
+    auto mul_one = [&](auto tag, auto ic, const bf16x8 &f) __attribute__((always_inline)) {
 #ifdef BS_PROBE_NO_MFMA
         return;
 #endif
-        constexpr int G = decltype(g)::value;
-        const bf16x8 &pg = pf[G >> 1][G & 1];
-        mfma_o<0>(o[0], f[0], pg);
-        mfma_o<1>(o[1], f[1], pg);
-        if constexpr (NDB == 4) {
-            mfma_o<2>(o[2], f[2], pg);
-            mfma_o<3>(o[3], f[3], pg);
+        using T = decltype(tag);
+        constexpr int i = decltype(ic)::value;
+        if constexpr (T::kind == 1) {
+            if constexpr (i < NDB) mfma_acc(o[i], f, pf[T::idx >> 1][T::idx & 1]);
+        } else if constexpr (T::kind == 2) {
+            if constexpr (T::first && i < 2) mfma_set(s[i & 1], f, qreg[2 * T::idx + (i >> 1)]);
+            else mfma_acc(s[i & 1], f, qreg[2 * T::idx + (i >> 1)]);
         }
-    };
-    auto read_s = [&](auto b, bf16x8 (&dst)[4]) {
-#ifdef BS_PROBE_NO_LDSREAD
-        return;
-#endif
-        constexpr int B = decltype(b)::value;
-        lds_read_b128<(2 * B) * 2048>(dst[0], kbase);            // slice 2B, keys 0..31
-        lds_read_b128<(2 * B) * 2048 + 1024>(dst[1], kbase);     // slice 2B, keys 32..63
-        lds_read_b128<(2 * B + 1) * 2048>(dst[2], kbase);
-        lds_read_b128<(2 * B + 1) * 2048 + 1024>(dst[3], kbase);
-    };
-    auto mul_s = [&](auto b, bf16x8 (&f)[4]) {
-#ifdef BS_PROBE_NO_MFMA
-        return;
-#endif
-        constexpr int B = decltype(b)::value;
-        if (B == 0) {
-            mfma_set(s[0], f[0], qreg[0]);
-            mfma_set(s[1], f[1], qreg[0]);
-        } else {
-            mfma_acc(s[0], f[0], qreg[2 * B]);
-            mfma_acc(s[1], f[1], qreg[2 * B]);
-        }
-        mfma_acc(s[0], f[2], qreg[2 * B + 1]);
-        mfma_acc(s[1], f[3], qreg[2 * B + 1]);
     };
     using I0 = std::integral_constant<int, 0>;
     using I1 = std::integral_constant<int, 1>;
@@ -636,18 +592,17 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(
     using I3 = std::integral_constant<int, 3>;
 
     // Phase X of step k: O += P(k-1) V(k-1) and S(k) = K(k) Q^T.  Always the same straight-line
-    // sequence, so the accumulators never move between registers: before the first tile P is
-    // zero (the ring was zero-filled), after the last tile -- and on tiles this item skips --
-    // P is zero again and the scores it produces are ignored.  Operand reads run three batches
-    // ahead of the MFMAs that consume them, in three rotating register sets; each lds_wait<N>
-    // count is the number of reads issued after the batch waited for.  A set is refilled right
-    // after the MFMAs that read it have issued (operands are read at issue, LDS data returns
-    // later).
+    // chain of asm statements: before the first tile P is zero (the ring was zero-filled), after
+    // the last tile -- and on tiles this item skips -- P is zero again and the scores it
+    // produces are ignored.  Operand reads run three batches ahead of the MFMAs that consume
+    // them, in three rotating register sets; each lds_wait<N> count is the number of reads
+    // issued after the batch waited for.  A register is refilled right after the MFMA that
+    // read it has issued (operands are read at issue, LDS data returns later), so the reads
+    // issue in the shadow of the MFMAs.
     auto phase_x = [&](int S) __attribute__((always_inline)) {  // S = k mod 3
         const int S1 = S == 2 ? 0 : S + 1, S2 = S == 0 ? 2 : S - 1;  // (S+1)%3, (S+2)%3
         kbase = kaddr0 + S * TILE;
         vbase = kaddr0 + (3 + S2) * TILE;
-#ifndef BS_PROBE_NO_X
         bf16x8 fa[4], fb[4], fc[4];
         if constexpr (NDB < 4) {
 #pragma unroll
@@ -655,61 +610,77 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(
 #pragma unroll
                 for (int e = 0; e < 8; ++e) { fa[i][e] = (__bf16)0.f; fb[i][e] = (__bf16)0.f; fc[i][e] = (__bf16)0.f; }
         }
-        if constexpr (D == 128) {
-            // batch order: PV0 S0 PV1 S1 PV2 S2 PV3 S3, four reads each
-#ifdef BS_TWO_SETS
-            read_pv(I0{}, fa); read_s(I0{}, fb);
-            lds_wait<4>(fa); mul_pv(I0{}, fa); read_pv(I1{}, fa);
-            lds_wait<4>(fb); mul_s(I0{}, fb); read_s(I1{}, fb);
-            lds_wait<4>(fa); mul_pv(I1{}, fa); read_pv(I2{}, fa);
-            lds_wait<4>(fb); mul_s(I1{}, fb); read_s(I2{}, fb);
-            lds_wait<4>(fa); mul_pv(I2{}, fa); read_pv(I3{}, fa);
-            lds_wait<4>(fb); mul_s(I2{}, fb); read_s(I3{}, fb);
-            lds_wait<4>(fa); mul_pv(I3{}, fa);
-            lds_wait<0>(fb); mul_s(I3{}, fb);
-#else
-            read_pv(I0{}, fa); read_s(I0{}, fb); read_pv(I1{}, fc);
-            lds_wait<8>(fa); mul_pv(I0{}, fa); read_s(I1{}, fa);
-            lds_wait<8>(fb); mul_s(I0{}, fb); read_pv(I2{}, fb);
-            lds_wait<8>(fc); mul_pv(I1{}, fc); read_s(I2{}, fc);
-            lds_wait<8>(fa); mul_s(I1{}, fa); read_pv(I3{}, fa);
-            lds_wait<8>(fb); mul_pv(I2{}, fb); read_s(I3{}, fb);
-            lds_wait<8>(fc); mul_s(I2{}, fc);
-            lds_wait<4>(fa); mul_pv(I3{}, fa);
-            lds_wait<0>(fb); mul_s(I3{}, fb);
+        // whole-batch reads of the pipeline head
+        auto read_batch = [&](auto tag, bf16x8 (&f)[4]) __attribute__((always_inline)) {
+            read_one(tag, I0{}, f[0]); read_one(tag, I1{}, f[1]);
+            read_one(tag, I2{}, f[2]); read_one(tag, I3{}, f[3]);
+        };
+        // MFMA batch `cur` on fragment set f, each MFMA followed by the read that refills its
+        // operand register for batch `nxt` (three batches ahead)
+        auto batch = [&](auto cur, auto nxt, bf16x8 (&f)[4]) __attribute__((always_inline)) {
+            mul_one(cur, I0{}, f[0]); read_one(nxt, I0{}, f[0]);
+            mul_one(cur, I1{}, f[1]); read_one(nxt, I1{}, f[1]);
+            mul_one(cur, I2{}, f[2]); read_one(nxt, I2{}, f[2]);
+            mul_one(cur, I3{}, f[3]); read_one(nxt, I3{}, f[3]);
+        };
+        // Refill addresses: computed while the first operand reads are in flight.
+        const char *ksrc = nullptr, *vsrc = nullptr;
+        auto refill_prepare = [&]() __attribute__((always_inline)) {
+#ifndef BS_PROBE_NO_DMA
+            __builtin_amdgcn_sched_barrier(0);
+            ksrc = tile_ptr(kph, w2.n);
+            vsrc = tile_ptr(vth, w1.n);
+            w1.next();
+            w2.next();
+            __builtin_amdgcn_sched_barrier(0);
 #endif
+        };
+#ifndef BS_PROBE_NO_X
+        if constexpr (D == 128) {
+            // batch order: PV0 S0 PV1 S1 PV2 S2 PV3 S3, four reads / MFMAs each
+            read_batch(PvBatch<0>{}, fa); read_batch(ScBatch<0, true>{}, fb); read_batch(PvBatch<1>{}, fc);
+            refill_prepare();
+            lds_wait<8>(fa); batch(PvBatch<0>{}, ScBatch<1, false>{}, fa);
+            lds_wait<8>(fb); batch(ScBatch<0, true>{}, PvBatch<2>{}, fb);
+            lds_wait<8>(fc); batch(PvBatch<1>{}, ScBatch<2, false>{}, fc);
+            lds_wait<8>(fa); batch(ScBatch<1, false>{}, PvBatch<3>{}, fa);
+            lds_wait<8>(fb); batch(PvBatch<2>{}, ScBatch<3, false>{}, fb);
+            lds_wait<8>(fc); batch(ScBatch<2, false>{}, NoBatch{}, fc);
+            lds_wait<4>(fa); batch(PvBatch<3>{}, NoBatch{}, fa);
+            lds_wait<0>(fb); batch(ScBatch<3, false>{}, NoBatch{}, fb);
             mfma_drain(s[0], s[1]);   // the PV accumulators finished four MFMAs earlier
         } else {
-            // D == 64: PV batches hold two reads, S has two batches of four
-            read_pv(I0{}, fa); read_s(I0{}, fb); read_pv(I1{}, fc);   // 2 + 4 + 2
-            lds_wait<6>(fa); mul_pv(I0{}, fa); read_pv(I2{}, fa);                // 4 2 | 2
-            lds_wait<4>(fb); mul_s(I0{}, fb); read_s(I1{}, fb);                  // 2 2 | 4
-            lds_wait<6>(fc); mul_pv(I1{}, fc); read_pv(I3{}, fc);                // 2 4 | 2
-            lds_wait<6>(fa); mul_pv(I2{}, fa);
-            lds_wait<2>(fb); mul_s(I1{}, fb);
-            lds_wait<0>(fc); mul_pv(I3{}, fc);
+            // D == 64: PV batches hold two reads / MFMAs, S has two batches of four
+            read_batch(PvBatch<0>{}, fa); read_batch(ScBatch<0, true>{}, fb); read_batch(PvBatch<1>{}, fc);   // 2 + 4 + 2
+            refill_prepare();
+            lds_wait<6>(fa); batch(PvBatch<0>{}, PvBatch<2>{}, fa);                     // 4 2 | 2
+            lds_wait<4>(fb); batch(ScBatch<0, true>{}, ScBatch<1, false>{}, fb);        // 2 2 | 4
+            lds_wait<6>(fc); batch(PvBatch<1>{}, PvBatch<3>{}, fc);                     // 2 4 | 2
+            lds_wait<6>(fa); batch(PvBatch<2>{}, NoBatch{}, fa);
+            lds_wait<2>(fb); batch(ScBatch<1, false>{}, NoBatch{}, fb);
+            lds_wait<0>(fc); batch(PvBatch<3>{}, NoBatch{}, fc);
             mfma_drain(o[0], o[1]);   // the scores finished two MFMAs earlier
         }
+#else
+        refill_prepare();
 #endif
         // Refill: this wave's share of K(k+2) -> K slot (S+2)%3 and V^T(k+1) -> V^T slot (S+1)%3,
-        // both last read one step ago by the other group.  Issued here, after the last MFMA,
-        // because LDS-direct loads issue several times slower while a wave of the same SIMD is
-        // feeding the matrix pipe.  Unconditional: past the end of the list a valid tile is
-        // fetched again and never used.  Then wait for the loads issued one step ago (only the
-        // new ones may stay in flight): with the barriers that follow, every tile is complete
-        // two half-steps before its first reader.
+        // both last read one step ago by the other group.  Unconditional: past the end of the
+        // list a valid tile is fetched again and never used.  Issued after the last MFMA:
+        // an LDS-direct load issued while the matrix pipe of the SIMD is being fed stalls the
+        // wave several times longer (measured both between the MFMAs of this phase and from
+        // the other group's vector phase).
 #ifndef BS_PROBE_NO_DMA
-        {
-            __builtin_amdgcn_sched_barrier(0);
-            const char *ksrc = tile_ptr(kph, w2.n), *vsrc = tile_ptr(vth, w1.n);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int r = 0; r < DMA_PER_WAVE; ++r) dma(r, ksrc, S2 * TILE);
+        for (int r = 0; r < DMA_PER_WAVE; ++r) dma(r, ksrc, S2 * TILE);
 #pragma unroll
-            for (int r = 0; r < DMA_PER_WAVE; ++r) dma(r, vsrc, 3 * TILE + S1 * TILE);
-        }
+        for (int r = 0; r < DMA_PER_WAVE; ++r) dma(r, vsrc, 3 * TILE + S1 * TILE);
+        __builtin_amdgcn_sched_barrier(0);
 #endif
-        w1.next();
-        w2.next();
+        // Wait for the loads issued one step ago (only this step's may stay in flight): with
+        // the barriers that follow, every tile is complete two half-steps before its first
+        // reader.
         asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * DMA_PER_WAVE));
     };
 
@@ -793,7 +764,7 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(
     __builtin_amdgcn_s_barrier();
     if (grp == 1) __builtin_amdgcn_s_barrier();  // second group runs half a step behind
     BS_T0();
-    auto step = [&](int slot, int k) __attribute__((always_inline)) {
+    for (int k = 0, slot = 0; k < n_steps; ++k) {
         phase_x(slot);
         BS_TICK(0);
         BS_LOOP_BARRIER();
@@ -802,23 +773,8 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(
         BS_TICK(2);
         BS_LOOP_BARRIER();
         BS_TICK(3);
-    };
-#ifdef BS_UNROLL3
-    // three copies of the step, one per ring slot; both groups share n_steps, so the exits are
-    // uniform over the workgroup and every wave passes the same number of barriers
-    for (int k = 0; k < n_steps; k += 3) {
-        step(0, k);
-        if (k + 1 >= n_steps) break;
-        step(1, k + 1);
-        if (k + 2 >= n_steps) break;
-        step(2, k + 2);
-    }
-#else
-    for (int k = 0, slot = 0; k < n_steps; ++k) {
-        step(slot, k);
         slot = slot == 2 ? 0 : slot + 1;
     }
-#endif
     if (grp == 0) __builtin_amdgcn_s_barrier();  // same barrier count for every wave of the workgroup
     BS_TFLUSH();
 
