@@ -77,8 +77,9 @@ class HipEvents:
 # HBM traffic per launch of the attention kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # runs, scaled by the same counters' reading for a 1 GiB copy (see profiles/).  Bytes.
 MEASURED_TRAFFIC = {
-    # profiles/attn_prefill_bf16_d128_cfg2_36k.md: 13.49 GB read + 0.28 GB written
-    "cfg2-qwen2vl7b-36k/paper10/seed0": 1.377e10,
+    # profiles/attn_prefill_bf16_d128_cfg2_36k.md: 10.82 GB read + 0.28 GB written (measured where L2
+    # meets the fabric: the 256 MB memory-side cache sits behind that point)
+    "cfg2-qwen2vl7b-36k/paper10/seed0": 1.110e10,
 }
 
 
@@ -94,17 +95,18 @@ def class_totals(tm, head_class):
 
 def timed_steps(bs, torch, p, q, k, v, out, steps, warmup, hev):
     """Returns (wall ms per step, mean attention-kernel ms, mean device ms of the whole call
-    incl. the tile-pack pre-pass, mean tile-map build+upload ms, last tile map)."""
+    incl. map upload and the tile-pack pre-pass, mean host ms of the tile-map build, mean host ms
+    inside the attention call (work-unit planning, staging, launches), last tile map)."""
     dt = bs.BS_BF16 if p.dtype == "bf16" else bs.BS_F32
     stream = torch.cuda.current_stream()
     keep = []
     build_s = []
+    call_s = []
     ev = []
 
     def step(record):
         t0 = time.perf_counter()
         tm = bs.bs_build_tilemap(p.spans, p.seq_len, p.head_class, p.sink_len, 128, 64)
-        tm.upload()
         t1 = time.perf_counter()
         e0 = torch.cuda.Event(enable_timing=True)
         e1 = torch.cuda.Event(enable_timing=True)
@@ -113,9 +115,11 @@ def timed_steps(bs, torch, p, q, k, v, out, steps, warmup, hev):
         bs.bs_attn_prefill_ex(q, k, v, out, tm, dt, p.n_q_heads, p.gqa_group, p.head_dim, p.scale,
                               stream.cuda_stream, k0.value if k0 else None, k1.value if k1 else None)
         e1.record(stream)
-        keep.append(tm)
+        t2 = time.perf_counter()
+        keep[:] = [tm]   # the previous map is destroyed here; its device blocks go back to the library's cache
         if record:
             build_s.append(t1 - t0)
+            call_s.append(t2 - t1)
             ev.append((e0, e1, k0, k1))
 
     for _ in range(warmup):
@@ -131,7 +135,7 @@ def timed_steps(bs, torch, p, q, k, v, out, steps, warmup, hev):
     for _, _, c, d in ev:
         hev.destroy(c)
         hev.destroy(d)
-    return wall * 1e3, kern_ms, call_ms, 1e3 * sum(build_s) / len(build_s), keep[-1]
+    return wall * 1e3, kern_ms, call_ms, 1e3 * sum(build_s) / len(build_s), 1e3 * sum(call_s) / len(call_s), keep[-1]
 
 
 def cpu_baseline(p, q, k, v, target_seconds):
@@ -213,20 +217,24 @@ def main():
         torch.cuda.synchronize()
         del a, b
 
-    wall_ms, kern_ms, call_ms, build_ms, tm = timed_steps(bs, torch, p, q, k, v, out, args.steps, args.warmup, hev)
+    wall_ms, kern_ms, call_ms, build_ms, host_call_ms, tm = timed_steps(bs, torch, p, q, k, v, out, args.steps, args.warmup, hev)
     tot, per_class = class_totals(tm, p.head_class)
     d = p.head_dim
     useful_flop = 4.0 * d * tot["allowed_pairs"]
     executed_flop = 4.0 * d * 128 * 64 * tot["visited"]
     esize = 2 if p.dtype == "bf16" else 4
-    kv_stream_bytes = tot["visited"] * 2 * 64 * d * esize
+    plan = tm.pair_plan(p.gqa_group) if p.dtype == "bf16" else None
+    # K and V^T tile bytes the attention kernel requests from L2: one pair of tiles per step of a
+    # work unit (bf16: two items share the stream), else per visited tile
+    kv_steps = plan["unit_tiles"] if plan else tot["visited"]
+    kv_stream_bytes = kv_steps * 2 * 64 * d * esize
     min_bytes = (2 * p.n_q_heads + 2 * p.n_kv_heads) * p.seq_len * d * esize
 
     dense = None
     if not args.all_dense and not args.no_dense_leg:
         pd = p.all_dense()
         dsteps = max(3, min(args.steps, 10))
-        d_wall, d_kern, _, _, d_tm = timed_steps(bs, torch, pd, q, k, v, out, dsteps, 1, hev)
+        d_wall, d_kern, _, _, _, d_tm = timed_steps(bs, torch, pd, q, k, v, out, dsteps, 1, hev)
         d_tot, _ = class_totals(d_tm, pd.head_class)
         dense = {"ms_per_step": round(d_wall, 4), "kernel_ms": round(d_kern, 4), "steps": dsteps,
                  "visited_tiles": d_tot["visited"],
@@ -250,10 +258,12 @@ def main():
                    "head_classes": {n: int((p.head_class == c).sum()) for c, n in enumerate(W.CLASS_NAMES)}},
         "kernel_ms": round(kern_ms, 4),
         "device_ms_per_call": round(call_ms, 4),
-        "tilemap_build_upload_ms": round(build_ms, 4),
+        "tilemap_build_host_ms": round(build_ms, 4),
+        "attn_call_host_ms": round(host_call_ms, 4),
         "executed_tflops": round(executed_flop / (kern_ms * 1e-3) / 1e12, 2),
         "kv_stream_gbs": round(kv_stream_bytes / (kern_ms * 1e-3) / 1e9, 1),
         "min_hbm_gbs": round(min_bytes / (kern_ms * 1e-3) / 1e9, 1),
+        "work_units": plan,
         "tiles": {"visited": tot["visited"], "full": tot["full"], "partial": tot["partial"],
                   "unmasked_pairs": tot["allowed_pairs"],
                   "useful_over_executed": round(useful_flop / executed_flop, 4)},

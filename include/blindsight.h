@@ -73,8 +73,12 @@ int bs_build_tilemap(const bs_span *spans, int32_t n_spans, int32_t seq_len,
                      const uint8_t *head_class, int32_t n_q_heads, int32_t sink_len,
                      int32_t block_m, int32_t block_n, bs_tilemap **out);
 
-/* Frees host arrays and (if uploaded) device buffers.  NULL is allowed.  The caller must
- * make sure no bs_attn_prefill using the map is still in flight. */
+/* Frees the host arrays; device buffers (if any) go back to a per-process cache of the library
+ * and are handed to a later map only after the work queued with this map has finished (the
+ * next owner's stream waits for an event recorded after this map's last call).  So a map may be
+ * destroyed as soon as its last bs_attn_prefill has returned, without waiting for the stream,
+ * and destroying it does not synchronise the device.  The cache keeps at most a few dozen
+ * blocks until the process ends.  NULL is allowed. */
 void bs_tilemap_destroy(bs_tilemap *tm);
 
 /* Geometry: any output pointer may be NULL. */
@@ -107,9 +111,10 @@ int bs_tilemap_stats(const bs_tilemap *tm, int32_t cls, int64_t *visited, int64_
 int bs_tilemap_pair_plan(bs_tilemap *tm, int32_t gqa_group, int64_t *n_units, int64_t *unit_tiles,
                          int64_t *skip_steps);
 
-/* Copy the map to the current HIP device (hipMalloc + synchronous hipMemcpy).  Optional:
- * bs_attn_prefill does it on first use.  Not thread-safe against concurrent calls on the
- * same map.  Errors: BS_EHIP, BS_ENOMEM. */
+/* Copy the map to the current HIP device and wait until the copy is done (default stream,
+ * then hipStreamSynchronize on it).  Optional: bs_attn_prefill uploads on first use, on its own
+ * stream and without waiting.  Not thread-safe against concurrent calls on the same map.
+ * Errors: BS_EHIP, BS_ENOMEM. */
 int bs_tilemap_upload(bs_tilemap *tm);
 
 /*
@@ -127,10 +132,13 @@ int bs_tilemap_upload(bs_tilemap *tm);
  *   stream   hipStream_t (NULL = default stream).  The call only enqueues work; the caller
  *            owns q/k/v/out and keeps them alive until the stream has drained.
  * bf16 path: a pre-pass first packs K and V into per-key-tile blocks (V transposed) in a
- * workspace the map owns (allocated on first use, 2 x the size of K; grown with a synchronising
- * hipFree + hipMalloc if a later call needs more).  Calls that share a map must therefore be
- * ordered on one stream: they share that workspace.
- * The first call on a map uploads it (see bs_tilemap_upload), which synchronises once.
+ * workspace the map owns (2 x the size of K, taken from the library's block cache or hipMalloc
+ * on first use).  Calls that share a map share that workspace: the library orders a call after
+ * the map's previous call when the stream changes, but two threads must not call with one map
+ * at the same time.
+ * The first call on a map uploads it: the arrays are staged through pinned host buffers and
+ * copied on `stream`; the host does not wait for the device (it may wait for an upload queued
+ * eight uploads earlier, whose staging buffer it reuses).
  * Errors: BS_EINVAL (null pointers, head counts that do not match), BS_EUNSUPPORTED,
  * BS_EHIP, BS_ENOMEM.  Nothing is launched on error.
  */

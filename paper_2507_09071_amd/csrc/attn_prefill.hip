@@ -27,6 +27,8 @@
 #include <algorithm>
 #include <cstdio>
 #include <cstring>
+#include <memory>
+#include <mutex>
 #include <new>
 #include <type_traits>
 #include <vector>
@@ -48,6 +50,7 @@ static int fail_hip(hipError_t e, const char *what)
 struct DeviceMap {
     int device = -1;
     void *blob = nullptr;                 // one allocation holding everything below
+    size_t blob_cap = 0;
     const uint32_t *code = nullptr;       // [L] per-token code
     const uint64_t *text_bits = nullptr;  // [N] text keys of each key tile
     const uint64_t *sink_bits = nullptr;  // [N] sink keys of each key tile
@@ -61,9 +64,18 @@ struct DeviceMap {
     void *vt_buf = nullptr;               // workspace: packed K and V^T tiles of the last bf16 call
     size_t vt_bytes = 0;
     void *pair_blob = nullptr;            // bf16 work units for pair_G: items, then ranges
+    size_t pair_cap = 0;
     const int4 *pair_items = nullptr;
     const int2 *pair_ranges = nullptr;
     int32_t n_pairs = 0, pair_G = 0;
+    hipStream_t last_stream = nullptr;    // stream of the most recent upload / launch (compared, never used)
+    std::shared_ptr<struct EventHolder> last_use;   // recorded after the most recent upload / launch
+};
+
+// An event that dies with its last owner (a map, or cached blocks that wait to be reused).
+struct EventHolder {
+    hipEvent_t ev = nullptr;
+    ~EventHolder() { if (ev) (void)hipEventDestroy(ev); }
 };
 
 // Read-only tile-map arrays; passed as separate __restrict__ kernel parameters so that loads
@@ -908,18 +920,117 @@ __global__ __launch_bounds__(kThreads, 1) void attn_prefill_f32(KernelArgs a, BS
 template <int D>
 constexpr size_t f32_lds_bytes() { return (size_t)kBlockN * (D + 1) * 4 + (size_t)kBlockN * (D + 8) * 4; }
 
+// ---------------------------------------------------------------- device memory for tile maps
+//
+// A serving loop builds a tile map per prompt.  hipMalloc / hipFree per map would cost more than
+// the pre-pass kernels and hipFree would drain the device, so the blocks a destroyed map held go
+// back to a small per-process cache instead, tagged with an event recorded on the stream that
+// last used them; the next owner's stream waits for that event before touching the block.
+// Host-to-device copies are staged through a ring of pinned buffers and queued on the caller's
+// stream, so nothing here blocks the host or drains the device once the cache is warm.  Cached
+// blocks and pinned buffers are kept until the process ends.
+
+struct CachedBlock {
+    int device;
+    void *ptr;
+    size_t cap;
+    std::shared_ptr<EventHolder> released;   // last use of the block by its previous owner (may be null: never used)
+};
+struct StagingBuffer {
+    void *host = nullptr;
+    size_t cap = 0;
+    hipEvent_t done = nullptr;   // the copy out of this buffer
+    bool used = false;
+};
+constexpr size_t kCacheMaxBlocks = 24;
+constexpr int kStagingBuffers = 8;
+std::mutex g_mem_mutex;
+// never destroyed: at process exit the HIP runtime may already be gone
+std::vector<CachedBlock> &g_cache = *new std::vector<CachedBlock>();
+StagingBuffer g_staging[kStagingBuffers];
+int g_staging_next = 0;
+
+// A device block of at least `bytes`, safe to use in work queued on `st` after this call.
+hipError_t pool_acquire(int device, size_t bytes, hipStream_t st, void **out, size_t *cap_out)
+{
+    const size_t want = (bytes + ((size_t)1 << 20) - 1) & ~(((size_t)1 << 20) - 1);   // 1 MiB granules
+    {
+        std::lock_guard<std::mutex> lock(g_mem_mutex);
+        size_t best = g_cache.size();
+        for (size_t i = 0; i < g_cache.size(); ++i)
+            if (g_cache[i].device == device && g_cache[i].cap >= want && g_cache[i].cap <= 2 * want &&
+                (best == g_cache.size() || g_cache[i].cap < g_cache[best].cap))
+                best = i;
+        if (best < g_cache.size()) {
+            const CachedBlock b = g_cache[best];
+            g_cache.erase(g_cache.begin() + best);
+            const hipError_t e = b.released ? hipStreamWaitEvent(st, b.released->ev, 0) : hipSuccess;
+            if (e != hipSuccess) { (void)hipFree(b.ptr); return e; }
+            *out = b.ptr; *cap_out = b.cap;
+            return hipSuccess;
+        }
+    }
+    hipError_t e = hipMalloc(out, want);
+    if (e == hipSuccess) *cap_out = want;
+    return e;
+}
+
+// Hand a block back; `last_use` is the event after which nobody reads or writes it any more.
+void pool_release(int device, void *ptr, size_t cap, const std::shared_ptr<EventHolder> &last_use)
+{
+    if (!ptr) return;
+    std::lock_guard<std::mutex> lock(g_mem_mutex);
+    g_cache.push_back({device, ptr, cap, last_use});
+    if (g_cache.size() > kCacheMaxBlocks) {   // drop the oldest block (hipFree waits for its users)
+        const CachedBlock b = g_cache.front();
+        g_cache.erase(g_cache.begin());
+        (void)hipFree(b.ptr);
+    }
+}
+
+// Queue a host-to-device copy of `bytes` from pageable memory on `st` without blocking the host
+// on the device: the data is copied into a pinned buffer first.
+hipError_t staged_upload(void *dst, const void *src, size_t bytes, hipStream_t st)
+{
+    if (bytes == 0) return hipSuccess;
+    std::lock_guard<std::mutex> lock(g_mem_mutex);
+    StagingBuffer &sb = g_staging[g_staging_next];
+    g_staging_next = (g_staging_next + 1) % kStagingBuffers;
+    hipError_t e;
+    if (sb.used) {   // the copy that last read this buffer must be over (it was queued eight uploads ago)
+        e = hipEventSynchronize(sb.done);
+        if (e != hipSuccess) return e;
+    }
+    if (sb.cap < bytes) {
+        if (sb.host) (void)hipHostFree(sb.host);
+        sb.host = nullptr; sb.cap = 0;
+        const size_t cap = (bytes + ((size_t)1 << 20) - 1) & ~(((size_t)1 << 20) - 1);
+        e = hipHostMalloc(&sb.host, cap, hipHostMallocDefault);
+        if (e != hipSuccess) { sb.host = nullptr; return e; }
+        sb.cap = cap;
+    }
+    if (!sb.done) {
+        e = hipEventCreateWithFlags(&sb.done, hipEventDisableTiming);
+        if (e != hipSuccess) { sb.done = nullptr; return e; }
+    }
+    std::memcpy(sb.host, src, bytes);
+    e = hipMemcpyAsync(dst, sb.host, bytes, hipMemcpyHostToDevice, st);
+    if (e != hipSuccess) return e;
+    e = hipEventRecord(sb.done, st);
+    sb.used = (e == hipSuccess);
+    return e;
+}
+
 void free_device_map(DeviceMap *d)
 {
     if (!d) return;
-    if (d->blob) {
-        int cur = -1;
-        (void)hipGetDevice(&cur);
-        if (cur != d->device) (void)hipSetDevice(d->device);
-        (void)hipFree(d->blob);
-        if (d->vt_buf) (void)hipFree(d->vt_buf);
-        if (d->pair_blob) (void)hipFree(d->pair_blob);
-        if (cur >= 0 && cur != d->device) (void)hipSetDevice(cur);
-    }
+    int cur = -1;
+    (void)hipGetDevice(&cur);
+    if (d->device >= 0 && cur != d->device) (void)hipSetDevice(d->device);
+    pool_release(d->device, d->blob, d->blob_cap, d->last_use);
+    pool_release(d->device, d->vt_buf, d->vt_bytes, d->last_use);
+    pool_release(d->device, d->pair_blob, d->pair_cap, d->last_use);
+    if (cur >= 0 && cur != d->device) (void)hipSetDevice(cur);
     delete d;
 }
 
@@ -927,7 +1038,8 @@ void free_device_map(DeviceMap *d)
 
 using bs::DeviceMap;
 
-extern "C" int bs_tilemap_upload(bs_tilemap *tm)
+// Copies the arrays of the map to the current device with work queued on `st` (no host-side wait).
+static int upload_on_stream(bs_tilemap *tm, hipStream_t st)
 {
     if (!tm) return BS_EINVAL;
     if (tm->dev) return BS_OK;
@@ -984,20 +1096,34 @@ extern "C" int bs_tilemap_upload(bs_tilemap *tm)
     std::memcpy(host.data() + off_class, tm->head_class.data(), tm->head_class.size());
 
     void *blob = nullptr;
-    e = hipMalloc(&blob, bytes);
+    size_t blob_cap = 0;
+    e = bs::pool_acquire(dev, bytes, st, &blob, &blob_cap);
     if (e != hipSuccess) {
         delete d;
         return bs::fail_hip(e, "hipMalloc(tile map)");
     }
-    e = hipMemcpy(blob, host.data(), bytes, hipMemcpyHostToDevice);
+    e = bs::staged_upload(blob, host.data(), bytes, st);
+    std::shared_ptr<bs::EventHolder> holder;
+    if (e == hipSuccess) {
+        try {
+            holder = std::make_shared<bs::EventHolder>();
+        } catch (const std::bad_alloc &) {
+            e = hipErrorOutOfMemory;
+        }
+    }
+    if (e == hipSuccess) e = hipEventCreateWithFlags(&holder->ev, hipEventDisableTiming);
+    if (e == hipSuccess) e = hipEventRecord(holder->ev, st);
     if (e != hipSuccess) {
         (void)hipFree(blob);
         delete d;
-        return bs::fail_hip(e, "hipMemcpy(tile map)");
+        return bs::fail_hip(e, "hipMemcpyAsync(tile map)");
     }
     unsigned char *b = static_cast<unsigned char *>(blob);
     d->device = dev;
     d->blob = blob;
+    d->blob_cap = blob_cap;
+    d->last_stream = st;
+    d->last_use = holder;
     d->code = reinterpret_cast<const uint32_t *>(b + off_code);
     d->text_bits = reinterpret_cast<const uint64_t *>(b + off_tbits);
     d->sink_bits = reinterpret_cast<const uint64_t *>(b + off_sbits);
@@ -1011,6 +1137,16 @@ extern "C" int bs_tilemap_upload(bs_tilemap *tm)
     tm->dev = d;
     tm->dev_free = bs::free_device_map;
     return BS_OK;
+}
+
+extern "C" int bs_tilemap_upload(bs_tilemap *tm)
+{
+    if (!tm) return BS_EINVAL;
+    if (tm->dev) return BS_OK;
+    const int rc = upload_on_stream(tm, nullptr);
+    if (rc != BS_OK) return rc;
+    const hipError_t e = hipStreamSynchronize(nullptr);   // this entry point promises a finished upload
+    return e == hipSuccess ? BS_OK : bs::fail_hip(e, "hipStreamSynchronize");
 }
 
 extern "C" int bs_attn_prefill(const void *q, const void *k, const void *v, void *out, bs_tilemap *tm,
@@ -1033,20 +1169,26 @@ extern "C" int bs_attn_prefill_ex(const void *q, const void *k, const void *v, v
     if (dtype != BS_BF16 && dtype != BS_F32) return BS_EUNSUPPORTED;
     if (((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)out) & 15) return BS_EINVAL;
 
-    int rc = bs_tilemap_upload(tm);
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    int rc = upload_on_stream(tm, st);
     if (rc != BS_OK) return rc;
     DeviceMap *d = tm->dev;
     int dev = -1;
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return bs::fail_hip(e, "hipGetDevice");
     if (dev != d->device) return BS_EINVAL;  // the map lives on another device
+    if (d->last_stream != st) {
+        // the buffers of the map were last written or read on another stream: order this call after that
+        e = hipStreamWaitEvent(st, d->last_use->ev, 0);
+        if (e != hipSuccess) return bs::fail_hip(e, "hipStreamWaitEvent");
+        d->last_stream = st;
+    }
 
     bs::KernelArgs a;
     a.q = q; a.k = k; a.v = v; a.out = out;
     a.L = tm->L; a.M = tm->M; a.G = gqa_group;
     a.scale_log2e = scale * 1.4426950408889634f;
 
-    hipStream_t st = static_cast<hipStream_t>(stream);
     const dim3 grid((unsigned)d->n_work), block(bs::kThreads);
     if (dtype == BS_BF16) {
         // pre-pass: pack V into transposed, swizzled key tiles (workspace owned by the map)
@@ -1054,14 +1196,10 @@ extern "C" int bs_attn_prefill_ex(const void *q, const void *k, const void *v, v
         const size_t pack_bytes = (size_t)n_kv_heads * tm->N * (size_t)head_dim * bs::kBlockN * 2;
         const size_t vt_need = 2 * pack_bytes;  // packed K tiles, then packed V^T tiles
         if (d->vt_bytes < vt_need) {
-            if (d->vt_buf) {
-                e = hipFree(d->vt_buf);  // synchronises: earlier launches that read it are done
-                d->vt_buf = nullptr; d->vt_bytes = 0;
-                if (e != hipSuccess) return bs::fail_hip(e, "hipFree(V^T workspace)");
-            }
-            e = hipMalloc(&d->vt_buf, vt_need);
-            if (e != hipSuccess) { d->vt_buf = nullptr; return bs::fail_hip(e, "hipMalloc(V^T workspace)"); }
-            d->vt_bytes = vt_need;
+            bs::pool_release(dev, d->vt_buf, d->vt_bytes, d->last_use);
+            d->vt_buf = nullptr; d->vt_bytes = 0;
+            e = bs::pool_acquire(dev, vt_need, st, &d->vt_buf, &d->vt_bytes);
+            if (e != hipSuccess) { d->vt_buf = nullptr; d->vt_bytes = 0; return bs::fail_hip(e, "hipMalloc(K / V^T workspace)"); }
         }
         __bf16 *kp = static_cast<__bf16 *>(d->vt_buf);
         __bf16 *vt = reinterpret_cast<__bf16 *>(static_cast<char *>(d->vt_buf) + pack_bytes);
@@ -1074,20 +1212,17 @@ extern "C" int bs_attn_prefill_ex(const void *q, const void *k, const void *v, v
             }
             const bs::PairPlan &plan = tm->pairs;
             if (plan.ranges.size() >= (size_t)INT32_MAX) return BS_EUNSUPPORTED;
-            if (d->pair_blob) {
-                e = hipFree(d->pair_blob);  // synchronises: earlier launches that read it are done
-                d->pair_blob = nullptr; d->pair_G = 0;
-                if (e != hipSuccess) return bs::fail_hip(e, "hipFree(work units)");
-            }
+            bs::pool_release(dev, d->pair_blob, d->pair_cap, d->last_use);
+            d->pair_blob = nullptr; d->pair_cap = 0; d->pair_G = 0;
             const size_t items_bytes = (plan.items.size() * sizeof(bs::PairItem) + 255) & ~(size_t)255;
             const size_t ranges_bytes = std::max<size_t>(plan.ranges.size(), 1) * sizeof(bs::PairRange);
-            e = hipMalloc(&d->pair_blob, items_bytes + ranges_bytes);
-            if (e != hipSuccess) { d->pair_blob = nullptr; return bs::fail_hip(e, "hipMalloc(work units)"); }
-            e = hipMemcpy(d->pair_blob, plan.items.data(), plan.items.size() * sizeof(bs::PairItem), hipMemcpyHostToDevice);
-            if (e == hipSuccess && !plan.ranges.empty())
-                e = hipMemcpy(static_cast<char *>(d->pair_blob) + items_bytes, plan.ranges.data(),
-                              plan.ranges.size() * sizeof(bs::PairRange), hipMemcpyHostToDevice);
-            if (e != hipSuccess) return bs::fail_hip(e, "hipMemcpy(work units)");
+            e = bs::pool_acquire(dev, items_bytes + ranges_bytes, st, &d->pair_blob, &d->pair_cap);
+            if (e != hipSuccess) { d->pair_blob = nullptr; d->pair_cap = 0; return bs::fail_hip(e, "hipMalloc(work units)"); }
+            e = bs::staged_upload(d->pair_blob, plan.items.data(), plan.items.size() * sizeof(bs::PairItem), st);
+            if (e == hipSuccess)
+                e = bs::staged_upload(static_cast<char *>(d->pair_blob) + items_bytes, plan.ranges.data(),
+                                      plan.ranges.size() * sizeof(bs::PairRange), st);
+            if (e != hipSuccess) return bs::fail_hip(e, "hipMemcpyAsync(work units)");
             d->pair_items = static_cast<const int4 *>(d->pair_blob);
             d->pair_ranges = reinterpret_cast<const int2 *>(static_cast<char *>(d->pair_blob) + items_bytes);
             d->n_pairs = (int32_t)plan.items.size();
@@ -1132,6 +1267,8 @@ extern "C" int bs_attn_prefill_ex(const void *q, const void *k, const void *v, v
     e = hipGetLastError();
     if (e != hipSuccess) return bs::fail_hip(e, "kernel launch");
     if (ev_main_stop) (void)hipEventRecord(static_cast<hipEvent_t>(ev_main_stop), st);
+    e = hipEventRecord(d->last_use->ev, st);
+    if (e != hipSuccess) return bs::fail_hip(e, "hipEventRecord");
     return BS_OK;
 }
 

@@ -478,8 +478,35 @@ void bs_plan_pairs(bs_tilemap *tm, int32_t G)
             }
         }
     }
-    std::stable_sort(plan.items.begin(), plan.items.end(),
-                     [](const bs::PairItem &a, const bs::PairItem &b) { return a.n_tiles > b.n_tiles; });
+    // Launch order.  Heaviest units first (longest-processing-time rule), but in coarse cost
+    // buckets inside which units of one KV head stay together, walking the same tiles at about
+    // the same time.  Workgroup b runs on XCD b mod 8 (each XCD has its own L2), so the sorted
+    // list is then dealt to the XCDs in blocks of kXcdBlock consecutive units: the units of a
+    // block run side by side on one XCD and find each other's K / V^T tiles in its L2.
+    // Block size: 8 for a few thousand units (a bigger block costs load balance at the tail),
+    // 16 for tens of thousands (measured on the 36K and 300K workloads).
+    constexpr int32_t kCostBucket = 32, kXcds = 8;
+    const int32_t kXcdBlock = std::min<int64_t>(16, std::max<int64_t>(8, (int64_t)plan.items.size() / 2048));
+    std::stable_sort(plan.items.begin(), plan.items.end(), [G](const bs::PairItem &a, const bs::PairItem &b) {
+        const int32_t ba = a.n_tiles / kCostBucket, bb = b.n_tiles / kCostBucket;
+        if (ba != bb) return ba > bb;
+        const int32_t ka = a.head_a / G, kb = b.head_a / G;
+        if (ka != kb) return ka < kb;
+        return a.n_tiles > b.n_tiles;
+    });
+    {
+        const size_t n = plan.items.size();
+        std::vector<std::pair<int64_t, int32_t>> slot(n);
+        for (size_t p = 0; p < n; ++p) {
+            const int64_t q = (int64_t)p / kXcdBlock, j = (int64_t)p % kXcdBlock;
+            const int64_t x = q % kXcds, r = (q / kXcds) * kXcdBlock + j;   // XCD, rank on that XCD
+            slot[p] = {r * kXcds + x, (int32_t)p};
+        }
+        std::sort(slot.begin(), slot.end());
+        std::vector<bs::PairItem> dealt(n);
+        for (size_t b = 0; b < n; ++b) dealt[b] = plan.items[slot[b].second];
+        plan.items.swap(dealt);
+    }
     plan.gqa_group = G;
 }
 

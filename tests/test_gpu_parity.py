@@ -4,6 +4,7 @@ import numpy as np
 import pytest
 import torch
 
+import paper_2507_09071_amd as bs
 import workloads as W
 from gpu_util import assert_close, errors, oracle_rows, rows_of_tiles, run_prefill
 from test_oracle_pins import uniform_attention_closed_form
@@ -148,3 +149,29 @@ def test_determinism_and_tilemap_reuse():
     with torch.cuda.stream(s):
         c, _ = run_prefill(p, q, k, v, tm, s.cuda_stream)
     assert torch.equal(a, c)
+
+
+def test_map_recycling_without_synchronisation():
+    """A serving loop: one map per prompt, destroyed right after its launch was queued, no
+    device synchronisation in between.  The library recycles the device blocks of destroyed
+    maps; every result must still match the oracle (sizes go down and up again, and the
+    second half runs on another stream)."""
+    lengths = [900, 300, 1500, 128, 700, 1500]
+    prompts = [W.custom_prompt([("T", 16)] + [("I", max(32, L // 4)), ("T", 8)] * 3 + [("T", L // 8)],
+                               [D, S, I, IS], n_kv_heads=2, head_dim=128, dtype="bf16", sink_len=7)
+               for L in lengths]
+    data = [W.make_qkv(p, 10 + i, DEV) for i, p in enumerate(prompts)]
+    outs = [torch.full_like(q, float("nan")) for q, _, _ in data]
+    side = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    for i, (p, (q, k, v)) in enumerate(zip(prompts, data)):
+        st = torch.cuda.current_stream() if i < 3 else side
+        tm = bs.bs_build_tilemap(p.spans, p.seq_len, p.head_class, p.sink_len, 128, 64)
+        bs.bs_attn_prefill(q, k, v, outs[i], tm, bs.BS_BF16, p.n_q_heads, p.gqa_group, p.head_dim, p.scale,
+                           st.cuda_stream)
+        tm.close()   # destroyed while its kernels may still be queued or running
+    torch.cuda.synchronize()
+    for i, (p, (q, k, v)) in enumerate(zip(prompts, data)):
+        want = oracle_rows(p, q, k, v)
+        for h in range(p.n_q_heads):
+            assert_close(outs[i][h].float().cpu().numpy(), want[h], "bf16", f"prompt {i} head {h}")
