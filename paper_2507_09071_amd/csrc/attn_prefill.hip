@@ -431,8 +431,9 @@ template <int G> struct PvBatch { static constexpr int kind = 1, idx = G; static
 template <int B, bool FIRST> struct ScBatch { static constexpr int kind = 2, idx = B; static constexpr bool first = FIRST; }; // S += K(slices 2B, 2B+1) Q^T
 struct NoBatch { static constexpr int kind = 0, idx = 0; static constexpr bool first = false; };
 
+constexpr int kRing = 4;   // K slots = V^T slots of the LDS ring
 template <int D>
-constexpr int bf16_lds_bytes() { return 6 /*3 K + 3 V^T slots*/ * kBlockN * D * 2; }
+constexpr int bf16_lds_bytes() { return 2 * kRing * kBlockN * D * 2; }
 
 // Walks the merged key-tile list of a work unit: runs of [begin, end) with a state per item.
 struct PairWalker {
@@ -466,13 +467,14 @@ struct PairWalker {
 // One workgroup = two groups of four waves = one work unit: two (head, query tile) items that
 // read the same KV head and walk one merged key-tile list (heads of a GQA group with the same
 // class, or two neighbouring query tiles of one head), so each K / V^T tile is fetched ONCE for
-// 256 query rows.  The tiles live in a shared ring of 3 K + 3 V^T slots.  Per key tile a group
+// 256 query rows.  The tiles live in a shared ring of 4 K + 4 V^T slots.  Per key tile a group
 // runs two phases:
 //   X (matrix):  O += P(k-1) V(k-1)  and  S(k) = K(k) Q^T        -- MFMA + LDS reads only
 //   Y (vector):  mask, online softmax of S(k) -> P(k), rescale O  -- VALU only
-// separated by workgroup barriers.  The second group runs half a step late, so on every SIMD
-// one wave is in X while the other is in Y: the matrix pipe and the vector ALU stay busy
-// together instead of the two waves queueing for the same unit.
+// and the workgroup meets at ONE barrier per tile, placed so that the two groups run the phases
+// in opposite order between two barriers (X then Y / Y then X): on every SIMD one wave is in X
+// while the other is in Y, and the matrix pipe and the vector ALU stay busy together instead
+// of the two waves queueing for the same unit.
 template <int D>
 __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(
     KernelArgs a, const uint32_t *__restrict__ map_code, const uint64_t *__restrict__ map_text_bits,
@@ -486,7 +488,7 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(
     constexpr int DMA_PER_WAVE = D / 64;  // LDS-direct loads per wave per matrix per tile (8 waves)
     constexpr int NDB = D / 32;           // 32-channel blocks of the output
     constexpr int NT = D / 16;            // 16-wide slices of the head dim
-    extern __shared__ __align__(1024) unsigned char lds[];   // K slots 0..2, then V^T slots 0..2
+    extern __shared__ __align__(1024) unsigned char lds[];   // K slots 0..3, then V^T slots 0..3
 
     const int tid = threadIdx.x, lane = tid & 63, hl = lane >> 5, col = lane & 31;
     const int grp = __builtin_amdgcn_readfirstlane(tid >> 8);          // wave group 0 / 1
@@ -549,8 +551,14 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(
     // w1 the next tile (V^T refill), w2 the one after (K refill)
     PairWalker w0, w1, w2;
     w0.init(pair_ranges, it1.x, it1.y);
+    // the second group's matrix phase k runs one barrier interval before the first group's phase
+    // k + 1, in which the first group fetches the same tiles: it fetches one tile further ahead
+    const int ahead = grp;
     w1 = w0; if (w1.valid()) w1.next();
+    PairWalker wt1 = w1;                                   // tile 1 (prologue)
+    if (ahead && w1.valid()) w1.next();
     w2 = w1; if (w2.valid()) w2.next();
+    PairWalker wt2 = wt1; if (wt2.valid()) wt2.next();     // tile 2 (prologue of the second group)
 
     // LDS-direct loads of packed tiles into ring slots: straight TILE-byte copies.  Each wave
     // instruction moves 1 KB (lane l -> bytes 16l..16l+15); instruction r of wave w (0..7) covers
@@ -567,7 +575,7 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(
         return base + (size_t)min(n, n_k_tiles - 1) * TILE;  // a walker past its end names no tile
     };
 
-    // ---- phase X building blocks (step k reads K slot k mod 3 and V^T slot (k + 2) mod 3) ----
+    // ---- phase X building blocks (step k reads K slot k mod 4 and V^T slot (k - 1) mod 4) ----
     // A batch is four 128-bit operand reads feeding four MFMAs:
     //   PV batch g (D = 128): O^T block db += V^T(db, group g) . P^T(group g), db = 0..3
     //   S  batch b          : head-dim slices 2b, 2b+1 for both 32-key blocks
@@ -611,10 +619,12 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(
     // issued after the batch waited for.  A register is refilled right after the MFMA that
     // read it has issued (operands are read at issue, LDS data returns later), so the reads
     // issue in the shadow of the MFMAs.
-    auto phase_x = [&](int S) __attribute__((always_inline)) {  // S = k mod 3
-        const int S1 = S == 2 ? 0 : S + 1, S2 = S == 0 ? 2 : S - 1;  // (S+1)%3, (S+2)%3
+    auto phase_x = [&](int S) __attribute__((always_inline)) {  // S = k mod 4
+        auto ring = [](int x) { return x >= kRing ? x - kRing : x; };
+        const int Sv = ring(S + kRing - 1);                          // V^T(k-1)
+        const int Sk_dst = ring(ring(S + 2) + ahead), Sv_dst = ring(S + 1 + ahead);
         kbase = kaddr0 + S * TILE;
-        vbase = kaddr0 + (3 + S2) * TILE;
+        vbase = kaddr0 + (kRing + Sv) * TILE;
         bf16x8 fa[4], fb[4], fc[4];
         if constexpr (NDB < 4) {
 #pragma unroll
@@ -676,8 +686,8 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(
 #else
         refill_prepare();
 #endif
-        // Refill: this wave's share of K(k+2) -> K slot (S+2)%3 and V^T(k+1) -> V^T slot (S+1)%3,
-        // both last read one step ago by the other group.  Unconditional: past the end of the
+        // Refill: this wave's share of K(k+2+ahead) and V^T(k+1+ahead) into the slots of the tiles
+        // four steps older, which nobody reads after the last barrier.  Unconditional: past the end of the
         // list a valid tile is fetched again and never used.  Issued after the last MFMA:
         // an LDS-direct load issued while the matrix pipe of the SIMD is being fed stalls the
         // wave several times longer (measured both between the MFMAs of this phase and from
@@ -685,14 +695,14 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(
 #ifndef BS_PROBE_NO_DMA
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int r = 0; r < DMA_PER_WAVE; ++r) dma(r, ksrc, S2 * TILE);
+        for (int r = 0; r < DMA_PER_WAVE; ++r) dma(r, ksrc, Sk_dst * TILE);
 #pragma unroll
-        for (int r = 0; r < DMA_PER_WAVE; ++r) dma(r, vsrc, 3 * TILE + S1 * TILE);
+        for (int r = 0; r < DMA_PER_WAVE; ++r) dma(r, vsrc, (kRing + Sv_dst) * TILE);
         __builtin_amdgcn_sched_barrier(0);
 #endif
-        // Wait for the loads issued one step ago (only this step's may stay in flight): with
-        // the barriers that follow, every tile is complete two half-steps before its first
-        // reader.
+        // Wait for the loads issued one step ago (only this step's may stay in flight): after
+        // the next barrier every wave has passed this wait, and the tile is read in the interval
+        // that follows it.
         asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * DMA_PER_WAVE));
     };
 
@@ -756,38 +766,62 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(
     // could be NaN patterns (0 * NaN would poison the accumulators).
     {
         const uint4 z4 = make_uint4(0, 0, 0, 0);
-        for (int i = tid * 16; i < 6 * TILE; i += kPingPongThreads * 16) *reinterpret_cast<uint4 *>(lds + i) = z4;
+        for (int i = tid * 16; i < 2 * kRing * TILE; i += kPingPongThreads * 16) *reinterpret_cast<uint4 *>(lds + i) = z4;
     }
     __syncthreads();
     // prologue: K(0) -> K slot 0, K(1) -> K slot 1, V^T(0) -> V^T slot 0 (unconditional, clamped)
     {
-        const char *k0 = tile_ptr(kph, w0.n), *k1 = tile_ptr(kph, w1.n), *v0 = tile_ptr(vth, w0.n);
+        const char *k0 = tile_ptr(kph, w0.n), *k1 = tile_ptr(kph, wt1.n), *v0 = tile_ptr(vth, w0.n);
 #pragma unroll
         for (int r = 0; r < DMA_PER_WAVE; ++r) dma(r, k0, 0);
 #pragma unroll
         for (int r = 0; r < DMA_PER_WAVE; ++r) dma(r, k1, TILE);
 #pragma unroll
-        for (int r = 0; r < DMA_PER_WAVE; ++r) dma(r, v0, 3 * TILE);
+        for (int r = 0; r < DMA_PER_WAVE; ++r) dma(r, v0, kRing * TILE);
+        if (ahead) {
+            // the second group's share of K(2) and V^T(1): the first group fetches its share in
+            // its first matrix phase, which this group has no counterpart for
+            const char *k2 = tile_ptr(kph, wt2.n), *v1 = tile_ptr(vth, wt1.n);
+#pragma unroll
+            for (int r = 0; r < DMA_PER_WAVE; ++r) dma(r, k2, 2 * TILE);
+#pragma unroll
+            for (int r = 0; r < DMA_PER_WAVE; ++r) dma(r, v1, (kRing + 1) * TILE);
+        }
     }
     // Raw barriers: every LDS access of this kernel is an LDS-direct load (drained with vmcnt
     // at the end of phase X) or an asm read (drained with lgkmcnt inside phase X), so no fence
     // is wanted here -- a fence would drain loads that are meant to stay in flight.
     __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0)
     __builtin_amdgcn_s_barrier();
-    if (grp == 1) __builtin_amdgcn_s_barrier();  // second group runs half a step behind
+    // ONE barrier per step.  Group 0 runs  X(k) | barrier | Y(k),  group 1  barrier | X(k) Y(k):
+    // between two barriers group 0 does Y(k) then X(k+1) while group 1 does X(k) then Y(k), so
+    // the waves of a SIMD are in opposite phases by program order but nothing holds them to a
+    // half-step grid.  Between barrier k and k+1 the ring is read at K(k), K(k+1), V^T(k-1),
+    // V^T(k) and written at K(k+3), V^T(k+2), whose slots (of K(k-1), V^T(k-2)) nobody reads
+    // after barrier k; a tile written in one interval is waited for (vmcnt) in the next and
+    // read in the one after: four slots each.
     BS_T0();
-    for (int k = 0, slot = 0; k < n_steps; ++k) {
-        phase_x(slot);
-        BS_TICK(0);
-        BS_LOOP_BARRIER();
-        BS_TICK(1);
-        phase_y(k);
-        BS_TICK(2);
-        BS_LOOP_BARRIER();
-        BS_TICK(3);
-        slot = slot == 2 ? 0 : slot + 1;
+    if (grp == 0) {
+        for (int k = 0, slot = 0; k < n_steps; ++k) {
+            phase_x(slot);
+            BS_TICK(0);
+            BS_LOOP_BARRIER();
+            BS_TICK(1);
+            phase_y(k);
+            BS_TICK(2);
+            slot = slot == kRing - 1 ? 0 : slot + 1;
+        }
+    } else {
+        for (int k = 0, slot = 0; k < n_steps; ++k) {
+            BS_LOOP_BARRIER();
+            BS_TICK(1);
+            phase_x(slot);
+            BS_TICK(0);
+            phase_y(k);
+            BS_TICK(2);
+            slot = slot == kRing - 1 ? 0 : slot + 1;
+        }
     }
-    if (grp == 0) __builtin_amdgcn_s_barrier();  // same barrier count for every wave of the workgroup
     BS_TFLUSH();
 
     // epilogue: divide by the running sum, round, store.  Empty rows (l = 0) give zeros.
