@@ -1,0 +1,35 @@
+"""The bf16 kernel's matrix phase is inline asm: check in the compiled ISA that the compiler put no
+vector access of its own right behind an MFMA (it would read the register before the matrix pipe
+has written it).  Needs hipcc (cross-compiles without a GPU); the checker itself is also tested on
+hand-written listings."""
+import shutil
+
+import pytest
+
+from paper_2507_09071_amd import build as bs_build
+from paper_2507_09071_amd import isa_check
+
+
+def test_checker_flags_a_copy_right_behind_an_mfma():
+    ins = ["v_mfma_f32_32x32x16_bf16 v[0:15], v[16:19], v[20:23], v[0:15]",
+           "ds_read_b128 v[16:19], v40",
+           "v_mov_b64_e32 v[32:33], v[14:15]"]
+    found = isa_check.mfma_hazards(ins)
+    assert len(found) == 1 and found[0][1] == 1
+
+
+def test_checker_accepts_waits_accumulation_and_branches():
+    acc = "v_mfma_f32_32x32x16_bf16 v[0:15], v[16:19], v[20:23], v[0:15]"
+    assert isa_check.mfma_hazards([acc, acc, "s_nop 15", "v_mul_f32_e32 v0, v0, v30"]) == []
+    assert isa_check.mfma_hazards([acc, "s_nop 11", "v_mul_f32_e32 v0, v0, v30"]) == []       # 12 wait states
+    assert len(isa_check.mfma_hazards([acc, "s_nop 10", "v_mul_f32_e32 v0, v0, v30"])) == 1   # one short of the margin
+    assert isa_check.mfma_hazards([acc, "s_barrier", "v_mul_f32_e32 v0, v0, v30"]) == []
+    assert isa_check.mfma_hazards([acc, "v_add_f32_e32 v40, v41, v42"]) == []
+
+
+@pytest.mark.skipif(shutil.which(bs_build.hipcc()) is None, reason="hipcc not available")
+def test_compiled_bf16_kernels_have_no_mfma_hazard():
+    res = isa_check.check()
+    assert set(res) == set(isa_check.KERNELS)
+    for k, hazards in res.items():
+        assert hazards == [], f"{k}: {hazards[:3]}"
