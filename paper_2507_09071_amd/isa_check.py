@@ -75,6 +75,38 @@ def mfma_hazards(ins: list) -> list:
     return found
 
 
+def lds_read_hazards(ins: list) -> list:
+    """The operand reads of the matrix phase are asm `ds_read_b128` waited for by hand-counted
+    `s_waitcnt lgkmcnt(N)`.  The compiler believes the destination holds the value as soon as
+    the asm statement is over; check that nothing names a destination register while its read
+    may still be in flight.  LDS reads complete in order: after `lgkmcnt(N)` all but the N
+    youngest are done (scalar loads share the counter and only make the wait stricter).
+    Straight-line code only: the list of reads in flight is dropped at branches and labels,
+    which the kernel never crosses with a read outstanding.  Returns (read, offending
+    instruction) pairs."""
+    found = []
+    inflight = []   # (instruction, destination registers), oldest first
+    for t in ins:
+        if t.startswith(("s_cbranch", "s_branch", "s_barrier", "s_endpgm")):
+            inflight = []
+            continue
+        m = re.match(r"s_waitcnt .*lgkmcnt\((\d+)\)", t)
+        if m:
+            n = int(m.group(1))
+            inflight = inflight[len(inflight) - n:] if n else []
+            continue
+        if t.startswith("s_waitcnt") and "lgkmcnt" not in t and "vmcnt" not in t:
+            inflight = []   # a bare immediate: treat as a full wait only if it names no counter
+            continue
+        named = _regs(t)
+        for r, dst in inflight:
+            if named & dst:
+                found.append((r, t))
+        if t.startswith("ds_read"):
+            inflight.append((t, _regs(t.split(",")[0])))
+    return found
+
+
 def check(isa_path: str | None = None) -> dict:
     """Compile (unless a listing is given) and return {kernel symbol prefix: [hazards]}."""
     if isa_path is None:
@@ -84,13 +116,17 @@ def check(isa_path: str | None = None) -> dict:
             isa = open(isa_path).read()
     else:
         isa = open(isa_path).read()
-    return {k: mfma_hazards(kernel_instructions(isa, k)) for k in KERNELS}
+    out = {}
+    for k in KERNELS:
+        ins = kernel_instructions(isa, k)
+        out[k] = mfma_hazards(ins) + lds_read_hazards(ins)
+    return out
 
 
 if __name__ == "__main__":
     res = check()
     for k, h in res.items():
         print(k, "hazards:", len(h))
-        for t, ws, u in h[:10]:
-            print("  ", t[:70], "-> after", ws, "wait states:", u[:70])
+        for item in h[:10]:
+            print("  ", *[str(x)[:70] for x in item])
     raise SystemExit(1 if any(res.values()) else 0)

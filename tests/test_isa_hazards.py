@@ -27,6 +27,17 @@ def test_checker_accepts_waits_accumulation_and_branches():
     assert isa_check.mfma_hazards([acc, "v_add_f32_e32 v40, v41, v42"]) == []
 
 
+def test_checker_tracks_lds_reads_in_flight():
+    rd = lambda a: f"ds_read_b128 v[{a}:{a + 3}], v60"
+    ok = [rd(0), rd(4), rd(8), "s_waitcnt lgkmcnt(2)", "v_mfma_f32_32x32x16_bf16 v[64:79], v[0:3], v[40:43], v[64:79]",
+          "s_waitcnt lgkmcnt(0)", "v_mov_b32_e32 v70, v9"]
+    assert isa_check.lds_read_hazards(ok) == []
+    early = [rd(0), rd(4), "s_waitcnt lgkmcnt(1)", "v_mov_b32_e32 v70, v5"]        # second read still in flight
+    assert len(isa_check.lds_read_hazards(early)) == 1
+    overwritten = [rd(0), "v_mov_b32_e32 v2, 0", "s_waitcnt lgkmcnt(0)"]           # compiler reuses the register
+    assert len(isa_check.lds_read_hazards(overwritten)) == 1
+
+
 @pytest.mark.skipif(shutil.which(bs_build.hipcc()) is None, reason="hipcc not available")
 def test_compiled_bf16_kernels_have_no_mfma_hazard():
     res = isa_check.check()
