@@ -77,9 +77,9 @@ class HipEvents:
 # HBM traffic per launch of the attention kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # runs, scaled by the same counters' reading for a 1 GiB copy (see profiles/).  Bytes.
 MEASURED_TRAFFIC = {
-    # profiles/attn_prefill_bf16_d128_cfg2_36k.md: 10.82 GB read + 0.28 GB written (measured where L2
+    # profiles/attn_prefill_bf16_d128_cfg2_36k.md: 4.56 GB read + 0.28 GB written (measured where L2
     # meets the fabric: the 256 MB memory-side cache sits behind that point)
-    "cfg2-qwen2vl7b-36k/paper10/seed0": 1.110e10,
+    "cfg2-qwen2vl7b-36k/paper10/seed0": 4.85e9,
 }
 
 
