@@ -181,9 +181,10 @@ __device__ inline void apply_mask(floatx16 (&s)[2], uint64_t allowed, int hl)
         }
 }
 
-// The same masking with the three instructions of one score kept together, so that the
-// scheduler cannot hoist the 32 bit tests in front of the 32 selects (32 registers of pressure
-// in a kernel that has none to spare).
+// The same masking in two instructions per score, kept together so that the scheduler cannot
+// hoist the 32 bit tests in front of the 32 selects (32 registers of pressure in a kernel that
+// has none to spare): the allowed bit is spread over a word (0 / all ones) and a bit-field
+// insert then keeps the score or takes -inf.
 __device__ inline void apply_mask_tight(floatx16 (&s)[2], uint64_t allowed, int hl)
 {
     const uint32_t w[2] = {(uint32_t)allowed >> (4 * hl), (uint32_t)(allowed >> 32) >> (4 * hl)};
@@ -193,12 +194,10 @@ __device__ inline void apply_mask_tight(floatx16 (&s)[2], uint64_t allowed, int 
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
             uint32_t t;
-            asm("v_and_b32 %1, %3, %2\n\t"
-                "v_cmp_ne_u32 vcc, 0, %1\n\t"
-                "v_cndmask_b32 %0, %4, %0, vcc"
+            asm("v_bfe_i32 %1, %2, %3, 1\n\t"
+                "v_bfi_b32 %0, %1, %0, %4"
                 : "+v"(s[kb][v]), "=&v"(t)
-                : "v"(w[kb]), "n"(1u << (8 * (v / 4) + (v % 4))), "v"(ninf)
-                : "vcc");
+                : "v"(w[kb]), "n"(8 * (v / 4) + (v % 4)), "v"(ninf));
         }
 }
 
