@@ -73,6 +73,26 @@ int bs_build_tilemap(const bs_span *spans, int32_t n_spans, int32_t seq_len,
                      const uint8_t *head_class, int32_t n_q_heads, int32_t sink_len,
                      int32_t block_m, int32_t block_n, bs_tilemap **out);
 
+/*
+ * Same, with options (flags = 0 is bs_build_tilemap):
+ *   BS_MAP_REGROUP_ROWS   the query rows are taken in another order than their positions: all
+ *       image rows first, then all text rows, each group in position order and padded to whole
+ *       query tiles.  Why: a text query attends to every earlier token (Sec. 3.2), so a query
+ *       tile that holds a single text row has to walk every causal key tile for every head
+ *       class; with the text rows in tiles of their own, the image rows of the sparse classes
+ *       keep their skipped tiles (the Q-side counterpart of the paper kernel's packing of
+ *       sink keys, App. kernel "Notation").  Only the grouping of rows into work items changes:
+ *       q, k, v, out keep their layout and the result is the same function of the inputs.
+ *       n_q_tiles becomes ceil(image rows / block_m) + ceil(text rows / block_m); query tile m
+ *       covers the rows bs_tilemap_row_order reports.  No effect on a prompt without text or
+ *       without image tokens.
+ * Errors: BS_EINVAL (also for unknown flag bits), BS_ENOMEM.
+ */
+#define BS_MAP_REGROUP_ROWS 1u
+int bs_build_tilemap_ex(const bs_span *spans, int32_t n_spans, int32_t seq_len,
+                        const uint8_t *head_class, int32_t n_q_heads, int32_t sink_len,
+                        int32_t block_m, int32_t block_n, uint32_t flags, bs_tilemap **out);
+
 /* Frees the host arrays; device buffers (if any) go back to a per-process cache of the library
  * and are handed to a later map only after the work queued with this map has finished (the
  * next owner's stream waits for an event recorded after this map's last call).  So a map may be
@@ -84,6 +104,10 @@ void bs_tilemap_destroy(bs_tilemap *tm);
 /* Geometry: any output pointer may be NULL. */
 int bs_tilemap_dims(const bs_tilemap *tm, int32_t *seq_len, int32_t *n_q_tiles,
                     int32_t *n_k_tiles, int32_t *n_q_heads);
+
+/* rows[n_q_tiles * block_m] (host): the position of every row of every query tile, -1 where a
+ * tile has no row (the last tile of the prompt, or of a group of regrouped rows). */
+int bs_tilemap_row_order(const bs_tilemap *tm, int32_t *rows);
 
 /* Expand the range lists of class `cls` for query tiles [q_tile_begin, +q_tile_count) into
  * states[q_tile_count][n_k_tiles] (host, row-major): 0 skip, 1 partial, 2 full. */

@@ -48,6 +48,8 @@ def _load():
         lib.bso_pair_count.restype = i64
         lib.bso_tile_states.argtypes = [ctypes.c_int, i32, i32p, u8p, i32, i32, i32p, i32, u8p]
         lib.bso_tile_states.restype = None
+        lib.bso_tile_states_rows.argtypes = [ctypes.c_int, i32, i32p, u8p, i32, i32, i32p, i32, u8p]
+        lib.bso_tile_states_rows.restype = None
         lib.bso_attention.argtypes = [f32p, f32p, f32p, i32, i32, i32, i32, u8p, i32p, u8p,
                                       ctypes.c_double, i32p, i32, f64p]
         lib.bso_attention.restype = ctypes.c_int
@@ -104,6 +106,19 @@ def tile_states(cls: int, imgid, issink, block_m: int, block_n: int, q_tiles=Non
     out = np.empty((len(qt), N), dtype=np.uint8)
     _load().bso_tile_states(int(cls), L, _p(imgid, ctypes.c_int32), _p(issink, ctypes.c_uint8),
                             block_m, block_n, _p(qt, ctypes.c_int32), len(qt), _p(out, ctypes.c_uint8))
+    return out
+
+
+def tile_states_rows(cls: int, imgid, issink, rows, block_n: int) -> np.ndarray:
+    """Tile states for query tiles given as row lists: rows int32 [n_tiles, block_m], -1 = no row."""
+    L = len(imgid)
+    rows = np.ascontiguousarray(rows, dtype=np.int32)
+    assert rows.ndim == 2
+    N = -(-L // block_n)
+    out = np.empty((rows.shape[0], N), dtype=np.uint8)
+    _load().bso_tile_states_rows(int(cls), L, _p(imgid, ctypes.c_int32), _p(issink, ctypes.c_uint8),
+                                 rows.shape[1], block_n, _p(rows, ctypes.c_int32), rows.shape[0],
+                                 _p(out, ctypes.c_uint8))
     return out
 
 

@@ -122,6 +122,31 @@ void bso_tile_states(int cls, int32_t L, const int32_t *imgid, const uint8_t *is
     }
 }
 
+/* The same reduction for query tiles given as explicit row lists (a tile map may group the
+ * query rows in another order than their positions): rows is [n_qtiles][bm], entries < 0 or
+ * >= L are slots without a row and count as not allowed, like positions past the end above. */
+void bso_tile_states_rows(int cls, int32_t L, const int32_t *imgid, const uint8_t *issink,
+                          int32_t bm, int32_t bn, const int32_t *rows, int32_t n_qtiles,
+                          uint8_t *states)
+{
+    int32_t N = (L + bn - 1) / bn;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int32_t t = 0; t < n_qtiles; ++t) {
+        for (int32_t n = 0; n < N; ++n) {
+            int64_t cnt = 0;
+            for (int32_t r = 0; r < bm; ++r) {
+                int32_t i = rows[(size_t)t * bm + r];
+                if (i < 0 || i >= L) continue;
+                for (int32_t j = n * bn; j < n * bn + bn; ++j) {
+                    if (j >= L) continue;
+                    cnt += bso_allowed(cls, i, j, imgid, issink);
+                }
+            }
+            states[(size_t)t * N + n] = (uint8_t)(cnt == 0 ? 0 : (cnt == (int64_t)bm * bn ? 2 : 1));
+        }
+    }
+}
+
 /* Masked softmax attention for the listed rows of every query head.
  *   q   [Hq][L][d], k, v [Hq/G][L][d] fp32;  query head h reads KV head h / G.
  *   rows: n_rows query positions (NULL = all L rows, n_rows ignored)

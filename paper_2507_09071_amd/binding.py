@@ -17,7 +17,7 @@ from . import build as _build
 BS_BF16, BS_F32 = 0, 1
 DENSE, SINK, INTRA, INTRA_SINK = 0, 1, 2, 3
 
-EXPORTS = ("bs_build_tilemap", "bs_tilemap_destroy", "bs_tilemap_dims", "bs_tilemap_tile_states",
+EXPORTS = ("bs_build_tilemap", "bs_build_tilemap_ex", "bs_tilemap_destroy", "bs_tilemap_dims", "bs_tilemap_row_order", "bs_tilemap_tile_states",
            "bs_tilemap_stats", "bs_tilemap_pair_plan", "bs_tilemap_upload", "bs_attn_prefill", "bs_attn_prefill_ex", "bs_strerror",
            "bs_last_error")
 
@@ -67,6 +67,11 @@ def load_library():
     lib.bs_build_tilemap.argtypes = [ctypes.POINTER(_Span), i32, i32, u8p, i32, i32, i32, i32,
                                      ctypes.POINTER(vp)]
     lib.bs_build_tilemap.restype = ctypes.c_int
+    lib.bs_build_tilemap_ex.argtypes = [ctypes.POINTER(_Span), i32, i32, u8p, i32, i32, i32, i32, ctypes.c_uint32,
+                                        ctypes.POINTER(ctypes.c_void_p)]
+    lib.bs_build_tilemap_ex.restype = ctypes.c_int
+    lib.bs_tilemap_row_order.argtypes = [vp, i32p]
+    lib.bs_tilemap_row_order.restype = ctypes.c_int
     lib.bs_tilemap_destroy.argtypes = [vp]
     lib.bs_tilemap_destroy.restype = None
     lib.bs_tilemap_dims.argtypes = [vp, i32p, i32p, i32p, i32p]
@@ -124,6 +129,13 @@ class TileMap:
             out.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8))), "bs_tilemap_tile_states")
         return out
 
+    def row_order(self, block_m: int = 128) -> np.ndarray:
+        """int32 [n_q_tiles, block_m]: position of every row of every query tile, -1 = no row."""
+        out = np.empty((self.n_q_tiles, block_m), dtype=np.int32)
+        _check(load_library().bs_tilemap_row_order(self._h, out.ctypes.data_as(ctypes.POINTER(ctypes.c_int32))),
+               "bs_tilemap_row_order")
+        return out
+
     def stats(self, cls: int) -> dict:
         v = [ctypes.c_int64() for _ in range(6)]
         _check(load_library().bs_tilemap_stats(self._h, cls, *[ctypes.byref(x) for x in v]),
@@ -152,18 +164,27 @@ class TileMap:
             pass
 
 
+BS_MAP_REGROUP_ROWS = 1
+
+
 def bs_build_tilemap(spans, seq_len: int, head_class, sink_len: int = 0,
-                     block_m: int = 128, block_n: int = 64) -> TileMap:
-    """spans: int array [G,3] of (start, end, sink); head_class: uint8 [n_q_heads]."""
+                     block_m: int = 128, block_n: int = 64, flags: int = 0) -> TileMap:
+    """spans: int array [G,3] of (start, end, sink); head_class: uint8 [n_q_heads];
+    flags: 0 or BS_MAP_REGROUP_ROWS (goes through bs_build_tilemap_ex)."""
     lib = load_library()
     sp = np.ascontiguousarray(np.asarray(spans, dtype=np.int32).reshape(-1, 3))
     hc = np.ascontiguousarray(head_class, dtype=np.uint8)
     handle = ctypes.c_void_p()
     sp_ptr = sp.ctypes.data_as(ctypes.POINTER(_Span)) if len(sp) else None
-    rc = lib.bs_build_tilemap(sp_ptr, len(sp), int(seq_len),
-                              hc.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8)), len(hc),
-                              int(sink_len), int(block_m), int(block_n), ctypes.byref(handle))
-    _check(rc, "bs_build_tilemap")
+    hc_ptr = hc.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8))
+    if flags:
+        rc = lib.bs_build_tilemap_ex(sp_ptr, len(sp), int(seq_len), hc_ptr, len(hc), int(sink_len),
+                                     int(block_m), int(block_n), int(flags), ctypes.byref(handle))
+        _check(rc, "bs_build_tilemap_ex")
+    else:
+        rc = lib.bs_build_tilemap(sp_ptr, len(sp), int(seq_len), hc_ptr, len(hc), int(sink_len),
+                                  int(block_m), int(block_n), ctypes.byref(handle))
+        _check(rc, "bs_build_tilemap")
     return TileMap(handle.value)
 
 

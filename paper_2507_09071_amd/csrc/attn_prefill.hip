@@ -52,6 +52,7 @@ struct DeviceMap {
     void *blob = nullptr;                 // one allocation holding everything below
     size_t blob_cap = 0;
     const uint32_t *code = nullptr;       // [L] per-token code
+    const int32_t *row_order = nullptr;   // [M * 128] position of each query-tile row, -1 = none
     const uint64_t *text_bits = nullptr;  // [N] text keys of each key tile
     const uint64_t *sink_bits = nullptr;  // [N] sink keys of each key tile
     const int2 *span_range = nullptr;     // [G+1] (start, end) by imgid; entry 0 unused
@@ -91,8 +92,9 @@ struct KernelArgs {
     const uint32_t *__restrict__ map_code, const uint64_t *__restrict__ map_text_bits,             \
         const uint64_t *__restrict__ map_sink_bits, const int2 *__restrict__ map_span_range,       \
         const int32_t *__restrict__ map_row_ptr, const int2 *__restrict__ map_ranges,              \
-        const int2 *__restrict__ map_work, const uint8_t *__restrict__ map_head_class
-#define BS_MAP_ARGS(d) (d)->code, (d)->text_bits, (d)->sink_bits, (d)->span_range, (d)->row_ptr, (d)->ranges, (d)->work, (d)->head_class
+        const int2 *__restrict__ map_work, const uint8_t *__restrict__ map_head_class,             \
+        const int32_t *__restrict__ map_row_order
+#define BS_MAP_ARGS(d) (d)->code, (d)->text_bits, (d)->sink_bits, (d)->span_range, (d)->row_ptr, (d)->ranges, (d)->work, (d)->head_class, (d)->row_order
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
@@ -478,7 +480,8 @@ template <int D>
 __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(
     KernelArgs a, const uint32_t *__restrict__ map_code, const uint64_t *__restrict__ map_text_bits,
     const uint64_t *__restrict__ map_sink_bits, const int2 *__restrict__ map_span_range,
-    const uint8_t *__restrict__ map_head_class, const int4 *__restrict__ pair_items,
+    const uint8_t *__restrict__ map_head_class, const int32_t *__restrict__ map_row_order,
+    const int4 *__restrict__ pair_items,
     const int2 *__restrict__ pair_ranges, const __bf16 *__restrict__ kp, const __bf16 *__restrict__ vt,
     int32_t n_k_tiles)
 {
@@ -505,7 +508,10 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(
     const int hsafe = max(head, 0);
     const int cls = __builtin_amdgcn_readfirstlane((int)map_head_class[hsafe]);
     const int kvh = __builtin_amdgcn_readfirstlane(it0.x / a.G);    // both items share it
-    const int row = m * kBlockM + wave * 32 + col;
+    // the query position of this lane's row; a tile slot without a row behaves like a row past
+    // the end of the prompt (computed on a copy of the last row, never stored)
+    const int row_slot = map_row_order[max(m, 0) * kBlockM + wave * 32 + col];
+    const int row = row_slot < 0 ? L : row_slot;
 
     const __bf16 *qh = reinterpret_cast<const __bf16 *>(a.q) + (size_t)hsafe * L * D;
     // packed K and V^T tiles of this KV head (one TILE-byte block per key tile)
@@ -858,7 +864,8 @@ __global__ __launch_bounds__(kThreads, 1) void attn_prefill_f32(KernelArgs a, BS
     const int kvh = head / a.G;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6, hl = lane >> 5, col = lane & 31;
     const int L = a.L;
-    const int row = m * kBlockM + wave * 32 + col;
+    const int row_slot = map_row_order[m * kBlockM + wave * 32 + col];
+    const int row = row_slot < 0 ? L : row_slot;
 
     const float *qh = reinterpret_cast<const float *>(a.q) + (size_t)head * L * D;
     const float *kh = reinterpret_cast<const float *>(a.k) + (size_t)kvh * L * D;
@@ -1089,7 +1096,8 @@ static int upload_on_stream(bs_tilemap *tm, hipStream_t st)
 
     auto align = [](size_t x) { return (x + 255) & ~(size_t)255; };
     const size_t off_code = 0;
-    const size_t off_tbits = align(off_code + (size_t)tm->L * 4);
+    const size_t off_rows = align(off_code + (size_t)tm->L * 4);
+    const size_t off_tbits = align(off_rows + tm->row_order.size() * 4);
     const size_t off_sbits = align(off_tbits + (size_t)tm->N * 8);
     const size_t off_spans = align(off_sbits + (size_t)tm->N * 8);
     const size_t off_rowptr = align(off_spans + G1 * 8);
@@ -1108,6 +1116,7 @@ static int upload_on_stream(bs_tilemap *tm, hipStream_t st)
         return BS_ENOMEM;
     }
     std::memcpy(host.data() + off_code, tm->code.data(), (size_t)tm->L * 4);
+    std::memcpy(host.data() + off_rows, tm->row_order.data(), tm->row_order.size() * 4);
     std::memcpy(host.data() + off_tbits, tm->text_bits.data(), (size_t)tm->N * 8);
     std::memcpy(host.data() + off_sbits, tm->sink_bits.data(), (size_t)tm->N * 8);
     int2 *sp = reinterpret_cast<int2 *>(host.data() + off_spans);
@@ -1158,6 +1167,7 @@ static int upload_on_stream(bs_tilemap *tm, hipStream_t st)
     d->last_stream = st;
     d->last_use = holder;
     d->code = reinterpret_cast<const uint32_t *>(b + off_code);
+    d->row_order = reinterpret_cast<const int32_t *>(b + off_rows);
     d->text_bits = reinterpret_cast<const uint64_t *>(b + off_tbits);
     d->sink_bits = reinterpret_cast<const uint64_t *>(b + off_sbits);
     d->span_range = reinterpret_cast<const int2 *>(b + off_spans);
@@ -1272,7 +1282,7 @@ extern "C" int bs_attn_prefill_ex(const void *q, const void *k, const void *v, v
             hipLaunchKernelGGL(bs::pack_vt_tiles<128>, tgrid, dim3(256), 0, st, static_cast<const __bf16 *>(v), vt, tm->L, tm->N);
             if (ev_main_start) (void)hipEventRecord(static_cast<hipEvent_t>(ev_main_start), st);
             hipLaunchKernelGGL(bs::attn_prefill_bf16<128>, pgrid, pblock, lds, st, a, d->code, d->text_bits, d->sink_bits,
-                               d->span_range, d->head_class, d->pair_items, d->pair_ranges, kp, vt, tm->N);
+                               d->span_range, d->head_class, d->row_order, d->pair_items, d->pair_ranges, kp, vt, tm->N);
         } else {
             constexpr int lds = bs::bf16_lds_bytes<64>();
             e = hipFuncSetAttribute(reinterpret_cast<const void *>(bs::attn_prefill_bf16<64>),
@@ -1282,7 +1292,7 @@ extern "C" int bs_attn_prefill_ex(const void *q, const void *k, const void *v, v
             hipLaunchKernelGGL(bs::pack_vt_tiles<64>, tgrid, dim3(256), 0, st, static_cast<const __bf16 *>(v), vt, tm->L, tm->N);
             if (ev_main_start) (void)hipEventRecord(static_cast<hipEvent_t>(ev_main_start), st);
             hipLaunchKernelGGL(bs::attn_prefill_bf16<64>, pgrid, pblock, lds, st, a, d->code, d->text_bits, d->sink_bits,
-                               d->span_range, d->head_class, d->pair_items, d->pair_ranges, kp, vt, tm->N);
+                               d->span_range, d->head_class, d->row_order, d->pair_items, d->pair_ranges, kp, vt, tm->N);
         }
     } else {
         if (ev_main_start) (void)hipEventRecord(static_cast<hipEvent_t>(ev_main_start), st);

@@ -45,11 +45,14 @@ struct QueryTile {
     std::vector<Segment> segs;
 };
 
-void describe_query_tile(const Geometry &G, int32_t m, QueryTile &qt)
+// Describe rows [r0, r1) of one query tile.  `ragged`: the tile holds fewer than bm rows (then
+// no key tile can be FULL: the missing rows count as masked).  A query tile whose rows are
+// not contiguous (regrouped order) is described run by run.
+void describe_query_rows(const Geometry &G, int32_t r0, int32_t r1, bool ragged, QueryTile &qt)
 {
-    qt.r0 = m * G.bm;
-    qt.r1 = std::min(qt.r0 + G.bm, G.L);
-    qt.ragged = (qt.r1 - qt.r0) < G.bm;
+    qt.r0 = r0;
+    qt.r1 = r1;
+    qt.ragged = ragged;
     int32_t lt = G.last_text[qt.r1 - 1];
     qt.last_text = (lt >= qt.r0) ? lt : -1;
     qt.segs.clear();
@@ -136,70 +139,135 @@ void candidate_tiles(const Geometry &G, const QueryTile &qt, int cls, std::vecto
     }
 }
 
-void build_class(const Geometry &G, int cls, ClassLists &out)
+// Key-tile ranges (FULL / PARTIAL; skipped tiles are absent) of one run of contiguous query rows.
+void build_run(const Geometry &G, int cls, const QueryTile &qt, std::vector<int32_t> &cand,
+               std::vector<TileRange> &out)
+{
+    out.clear();
+    int32_t run_begin = -1, run_end = -1, run_state = 0;
+    auto flush = [&]() {
+        if (run_begin >= 0) out.push_back({run_begin, (run_end << 1) | (run_state == 2)});
+        run_begin = -1;
+    };
+    // append tiles [b, e) of one state (1 partial, 2 full), merging adjacent runs
+    auto emit = [&](int32_t b, int32_t e, int st) {
+        if (e <= b) return;
+        if (run_begin >= 0 && b == run_end && st == run_state) {
+            run_end = e;
+        } else {
+            flush();
+            run_begin = b; run_end = e; run_state = st;
+        }
+    };
+    const int32_t n_last = (qt.r1 - 1) / G.bn;
+    // key tiles wholly at or before the first row of a complete query tile can be FULL
+    const int32_t n_full_limit = qt.ragged ? 0 : (qt.r0 + 1) / G.bn;
+
+    if (cls == BS_DENSE || qt.segs.empty()) {
+        // every earlier key is visible: FULL below the diagonal, PARTIAL on it
+        emit(0, n_full_limit, 2);
+        emit(n_full_limit, n_last + 1, 1);
+    } else if (qt.last_text >= 0) {
+        // mixed text/image rows: every causal key tile up to the last text row is visited.
+        // Only a few of them can differ from PARTIAL: all-free tiles and tiles overlapping an
+        // own image (candidates for FULL), and the tiles past the last text row (may be SKIP).
+        // Those are classified exactly; the rest are PARTIAL.
+        cand.clear();
+        const auto &naf = G.next_allfree(cls);
+        for (int32_t n = naf[0]; n < n_full_limit; n = naf[n + 1]) cand.push_back(n);
+        const auto &sp = *G.spans;
+        for (const Segment &sg : qt.segs)
+            for (int32_t n = sp[sg.g].start / G.bn; n <= (sg.b - 1) / G.bn && n < n_full_limit; ++n) cand.push_back(n);
+        for (int32_t n = qt.last_text / G.bn + 1; n <= n_last; ++n) cand.push_back(n);
+        std::sort(cand.begin(), cand.end());
+        cand.erase(std::unique(cand.begin(), cand.end()), cand.end());
+        int32_t cur = 0;
+        for (int32_t n : cand) {
+            emit(cur, n, 1);
+            const int st = tile_state(G, qt, cls, n);
+            if (st) emit(n, n + 1, st);
+            cur = n + 1;
+        }
+        emit(cur, qt.last_text / G.bn + 1, 1);
+    } else {
+        candidate_tiles(G, qt, cls, cand);
+        for (int32_t n : cand) {
+            const int st = tile_state(G, qt, cls, n);
+            if (st) emit(n, n + 1, st);
+        }
+    }
+    flush();
+}
+
+// Union of two range lists of one query tile's runs.  A key tile is FULL for the tile only if
+// it is FULL for every run; visited by some run and not FULL for all of them: PARTIAL.
+// `a_runs` tells how many runs list a stands for (a tile absent from a is skipped by all of them).
+void combine_runs(const std::vector<TileRange> &a, const std::vector<TileRange> &b, std::vector<TileRange> &out)
+{
+    out.clear();
+    size_t ia = 0, ib = 0;
+    int32_t pos = 0;
+    auto push = [&](int32_t bg, int32_t en, bool full) {
+        if (en <= bg) return;
+        if (!out.empty() && out.back().end() == bg && out.back().full() == full) out.back().end_state = (en << 1) | full;
+        else out.push_back({bg, (en << 1) | (int32_t)full});
+    };
+    while (ia < a.size() || ib < b.size()) {
+        // state of a and b at `pos` and the next boundary
+        int32_t next = INT32_MAX;
+        int sa = 0, sb = 0;
+        if (ia < a.size()) {
+            if (a[ia].end() <= pos) { ++ia; continue; }
+            if (a[ia].begin <= pos) { sa = a[ia].full() ? 2 : 1; next = std::min(next, a[ia].end()); }
+            else next = std::min(next, a[ia].begin);
+        }
+        if (ib < b.size()) {
+            if (b[ib].end() <= pos) { ++ib; continue; }
+            if (b[ib].begin <= pos) { sb = b[ib].full() ? 2 : 1; next = std::min(next, b[ib].end()); }
+            else next = std::min(next, b[ib].begin);
+        }
+        if (next == INT32_MAX) break;
+        if (sa || sb) push(pos, next, sa == 2 && sb == 2);
+        pos = next;
+    }
+}
+
+void build_class(const Geometry &G, int cls, const std::vector<int32_t> &row_order, ClassLists &out)
 {
     out.row_ptr.assign(G.M + 1, 0);
     out.row_tiles.assign(G.M, 0);
     out.ranges.clear();
     QueryTile qt;
     std::vector<int32_t> cand;
+    std::vector<TileRange> run, acc, tmp;
     for (int32_t m = 0; m < G.M; ++m) {
-        describe_query_tile(G, m, qt);
-        int32_t run_begin = -1, run_end = -1, run_state = 0;
-        auto flush = [&]() {
-            if (run_begin >= 0) out.ranges.push_back({run_begin, (run_end << 1) | (run_state == 2)});
-            run_begin = -1;
-        };
-        // append tiles [b, e) of one state (1 partial, 2 full) to the row, merging runs
-        auto emit = [&](int32_t b, int32_t e, int st) {
-            if (e <= b) return;
-            if (run_begin >= 0 && b == run_end && st == run_state) {
-                run_end = e;
+        // the tile's rows as runs of consecutive positions (one run in the natural order)
+        const int32_t *rows = row_order.data() + (size_t)m * G.bm;
+        int32_t n_rows = 0;
+        while (n_rows < G.bm && rows[n_rows] >= 0) ++n_rows;
+        const bool ragged = n_rows < G.bm;
+        acc.clear();
+        bool first = true;
+        for (int32_t i = 0; i < n_rows;) {
+            int32_t j = i + 1;
+            while (j < n_rows && rows[j] == rows[j - 1] + 1) ++j;
+            describe_query_rows(G, rows[i], rows[j - 1] + 1, ragged, qt);
+            build_run(G, cls, qt, cand, run);
+            if (first) {
+                acc.swap(run);
+                first = false;
             } else {
-                flush();
-                run_begin = b; run_end = e; run_state = st;
+                combine_runs(acc, run, tmp);
+                acc.swap(tmp);
             }
-            out.row_tiles[m] += e - b;
-            if (st == 2) out.full += e - b; else out.partial += e - b;
-        };
-        const int32_t n_last = (qt.r1 - 1) / G.bn;
-        // key tiles wholly at or before the first row of a complete query tile can be FULL
-        const int32_t n_full_limit = qt.ragged ? 0 : (qt.r0 + 1) / G.bn;
-
-        if (cls == BS_DENSE || qt.segs.empty()) {
-            // every earlier key is visible: FULL below the diagonal, PARTIAL on it
-            emit(0, n_full_limit, 2);
-            emit(n_full_limit, n_last + 1, 1);
-        } else if (qt.last_text >= 0) {
-            // mixed text/image query tile: every causal key tile up to the last text row is
-            // visited.  Only a few of them can differ from PARTIAL: all-free tiles and tiles
-            // overlapping an own image (candidates for FULL), and the tiles past the last text
-            // row (may be SKIP).  Those are classified exactly; the rest are PARTIAL.
-            cand.clear();
-            const auto &naf = G.next_allfree(cls);
-            for (int32_t n = naf[0]; n < n_full_limit; n = naf[n + 1]) cand.push_back(n);
-            const auto &sp = *G.spans;
-            for (const Segment &sg : qt.segs)
-                for (int32_t n = sp[sg.g].start / G.bn; n <= (sg.b - 1) / G.bn && n < n_full_limit; ++n) cand.push_back(n);
-            for (int32_t n = qt.last_text / G.bn + 1; n <= n_last; ++n) cand.push_back(n);
-            std::sort(cand.begin(), cand.end());
-            cand.erase(std::unique(cand.begin(), cand.end()), cand.end());
-            int32_t cur = 0;
-            for (int32_t n : cand) {
-                emit(cur, n, 1);
-                const int st = tile_state(G, qt, cls, n);
-                if (st) emit(n, n + 1, st);
-                cur = n + 1;
-            }
-            emit(cur, qt.last_text / G.bn + 1, 1);
-        } else {
-            candidate_tiles(G, qt, cls, cand);
-            for (int32_t n : cand) {
-                const int st = tile_state(G, qt, cls, n);
-                if (st) emit(n, n + 1, st);
-            }
+            i = j;
         }
-        flush();
+        for (const TileRange &r : acc) {
+            const int32_t len = r.end() - r.begin;
+            out.row_tiles[m] += len;
+            if (r.full()) out.full += len; else out.partial += len;
+            out.ranges.push_back(r);
+        }
         out.row_ptr[m + 1] = (int64_t)out.ranges.size();
     }
     out.visited = out.full + out.partial;
@@ -249,6 +317,14 @@ extern "C" int bs_build_tilemap(const bs_span *spans, int32_t n_spans, int32_t s
                                 const uint8_t *head_class, int32_t n_q_heads, int32_t sink_len,
                                 int32_t block_m, int32_t block_n, bs_tilemap **out)
 {
+    return bs_build_tilemap_ex(spans, n_spans, seq_len, head_class, n_q_heads, sink_len, block_m, block_n, 0, out);
+}
+
+extern "C" int bs_build_tilemap_ex(const bs_span *spans, int32_t n_spans, int32_t seq_len,
+                                   const uint8_t *head_class, int32_t n_q_heads, int32_t sink_len,
+                                   int32_t block_m, int32_t block_n, uint32_t flags, bs_tilemap **out)
+{
+    if (flags & ~(uint32_t)BS_MAP_REGROUP_ROWS) return BS_EINVAL;
     if (!out || !head_class || n_q_heads <= 0 || seq_len <= 0 || n_spans < 0) return BS_EINVAL;
     if (n_spans > 0 && !spans) return BS_EINVAL;
     if (sink_len < 0 || sink_len > seq_len || block_m <= 0 || block_n <= 0) return BS_EINVAL;
@@ -262,7 +338,6 @@ extern "C" int bs_build_tilemap(const bs_span *spans, int32_t n_spans, int32_t s
         tm = new bs_tilemap();
         const int32_t L = seq_len;
         tm->L = L; tm->bm = block_m; tm->bn = block_n; tm->sink_len = sink_len;
-        tm->M = (L + block_m - 1) / block_m;
         tm->N = (L + block_n - 1) / block_n;
         tm->n_q_heads = n_q_heads;
         tm->spans.assign(spans, spans + n_spans);
@@ -286,6 +361,31 @@ extern "C" int bs_build_tilemap(const bs_span *spans, int32_t n_spans, int32_t s
                 const uint64_t bit = 1ull << (t % block_n);
                 if (tm->code[t] & bs::kCodeText) tm->text_bits[t / block_n] |= bit;
                 if (tm->code[t] & bs::kCodeSink) tm->sink_bits[t / block_n] |= bit;
+            }
+        }
+
+        // Order of the query rows.  Natural: tile m holds rows m*bm ... .  Regrouped: the image
+        // rows first, then the text rows, each group in position order and padded to whole
+        // tiles (-1).  A text row attends to every earlier token, so a tile that holds even one
+        // walks every causal key tile for every class; gathered into tiles of their own, the
+        // text rows stop costing the image rows of the sparse classes their skipped tiles.
+        {
+            const int64_t bm = block_m;
+            std::vector<int32_t> img_rows, txt_rows;
+            if (flags & BS_MAP_REGROUP_ROWS) {
+                for (int32_t t = 0; t < L; ++t) ((tm->code[t] & bs::kCodeText) ? txt_rows : img_rows).push_back(t);
+            }
+            if (img_rows.empty() || txt_rows.empty()) {   // natural order (also: nothing to separate)
+                tm->M = (int32_t)((L + bm - 1) / bm);
+                tm->row_order.assign((size_t)tm->M * bm, -1);
+                for (int32_t t = 0; t < L; ++t) tm->row_order[t] = t;
+            } else {
+                const int64_t m_img = ((int64_t)img_rows.size() + bm - 1) / bm, m_txt = ((int64_t)txt_rows.size() + bm - 1) / bm;
+                tm->M = (int32_t)(m_img + m_txt);
+                tm->row_order.assign((size_t)tm->M * bm, -1);
+                std::copy(img_rows.begin(), img_rows.end(), tm->row_order.begin());
+                std::copy(txt_rows.begin(), txt_rows.end(), tm->row_order.begin() + m_img * bm);
+                tm->regrouped = true;
             }
         }
 
@@ -319,7 +419,7 @@ extern "C" int bs_build_tilemap(const bs_span *spans, int32_t n_spans, int32_t s
                 G.next_allfree_tile[b][n] = allfree ? n : G.next_allfree_tile[b][n + 1];
             }
         }
-        for (int c = 0; c < 4; ++c) build_class(G, c, tm->cls[c]);
+        for (int c = 0; c < 4; ++c) build_class(G, c, tm->row_order, tm->cls[c]);
         count_pairs(G, tm->code, tm->cls);
 
         // work list: heaviest (head, query tile) first so the tail of the launch is short;
@@ -574,6 +674,13 @@ extern "C" int bs_tilemap_dims(const bs_tilemap *tm, int32_t *seq_len, int32_t *
     if (n_q_tiles) *n_q_tiles = tm->M;
     if (n_k_tiles) *n_k_tiles = tm->N;
     if (n_q_heads) *n_q_heads = tm->n_q_heads;
+    return BS_OK;
+}
+
+extern "C" int bs_tilemap_row_order(const bs_tilemap *tm, int32_t *rows)
+{
+    if (!tm || !rows) return BS_EINVAL;
+    std::memcpy(rows, tm->row_order.data(), tm->row_order.size() * sizeof(int32_t));
     return BS_OK;
 }
 

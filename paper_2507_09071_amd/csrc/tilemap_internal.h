@@ -63,6 +63,8 @@ struct bs_tilemap {
     int32_t L = 0, bm = 0, bn = 0, M = 0, N = 0, n_q_heads = 0, sink_len = 0;
     std::vector<bs_span> spans;
     std::vector<uint8_t> head_class;
+    std::vector<int32_t> row_order;        // M * bm: position of each query-tile row, -1 = no row
+    bool regrouped = false;                // row_order is not the natural order
     std::vector<uint32_t> code;            // L
     std::vector<uint64_t> text_bits;       // N: bit b of entry n = key n*bn + b is a text key (bn <= 64 only)
     std::vector<uint64_t> sink_bits;       // N: same for sink keys

@@ -9,11 +9,11 @@ BF16_MAX_ABS, BF16_REL_L2 = 2e-2, 5e-3     # tolerance for bf16 inputs
 F32_TOL = 1e-5                              # max-abs and relative-L2 for the fp32 configuration
 
 
-def run_prefill(p, q, k, v, tm=None, stream=None):
+def run_prefill(p, q, k, v, tm=None, stream=None, flags=0):
     """Launch bs_attn_prefill on the tensors' device; returns (out, tilemap)."""
     assert q.is_cuda and q.is_contiguous() and k.is_contiguous() and v.is_contiguous()
     if tm is None:
-        tm = bs.bs_build_tilemap(p.spans, p.seq_len, p.head_class, p.sink_len, 128, 64)
+        tm = bs.bs_build_tilemap(p.spans, p.seq_len, p.head_class, p.sink_len, 128, 64, flags=flags)
     out = torch.full_like(q, float("nan"))
     dt = bs.BS_BF16 if q.dtype == torch.bfloat16 else bs.BS_F32
     st = torch.cuda.current_stream().cuda_stream if stream is None else stream

@@ -14,9 +14,9 @@ D, S, I, IS = 0, 1, 2, 3
 DEV = "cuda:0"
 
 
-def full_parity(p, seed=0, what=None):
+def full_parity(p, seed=0, what=None, flags=0):
     q, k, v = W.make_qkv(p, seed, DEV)
-    out, tm = run_prefill(p, q, k, v)
+    out, tm = run_prefill(p, q, k, v, flags=flags)
     want = oracle_rows(p, q, k, v)
     print(what or p.name, "L", p.seq_len, flush=True)
     res = []
@@ -102,9 +102,9 @@ def test_rows_sum_to_one_and_uniform_closed_form_config2():
         assert_close(out0[h].float().cpu().numpy(), want[h], "bf16", f"uniform head {h}")
 
 
-def sampled_parity(p, seed, n_random, max_tiles, row_step):
+def sampled_parity(p, seed, n_random, max_tiles, row_step, flags=0):
     q, k, v = W.make_qkv(p, seed, DEV)
-    out, tm = run_prefill(p, q, k, v)
+    out, tm = run_prefill(p, q, k, v, flags=flags)
     tiles = W.sample_q_tiles(p, 128, n_random=n_random, seed=seed, max_tiles=max_tiles)
     rows = rows_of_tiles(p, tiles, row_step)
     print(p.name, "L", p.seq_len, "rows checked", len(rows), flush=True)
@@ -133,6 +133,37 @@ def test_config3_sampled_rows():
 
 def test_config4_sampled_rows():
     sampled_parity(W.config(4), 0, n_random=2, max_tiles=8, row_step=32)
+
+
+# --- regrouped query rows (BS_MAP_REGROUP_ROWS): same function of the inputs, other work items
+
+@pytest.mark.parametrize("dtype,d", [("bf16", 128), ("bf16", 64), ("f32", 128)])
+def test_regrouped_small_prompt_all_classes(dtype, d):
+    p = W.custom_prompt(RUNS_A, [D, S, I, IS, IS, I, S, D], 4, d, dtype=dtype, sink_len=5,
+                        name=f"regrouped-{dtype}-d{d}", value_recipe={"std": 1.0, "first_key_scale": 4.0})
+    full_parity(p, seed=5, flags=bs.BS_MAP_REGROUP_ROWS)
+
+
+def test_regrouped_many_small_images_and_single_text_tokens():
+    runs = [("T", 3)]
+    for i in range(30):
+        runs += [("I", 40 + 7 * (i % 5)), ("T", 1 + (i % 3))]
+    p = W.custom_prompt(runs, [S, I, IS, D], 2, 128, dtype="bf16", sink_len=2, name="regrouped-many")
+    full_parity(p, seed=6, flags=bs.BS_MAP_REGROUP_ROWS)
+
+
+def test_regrouped_matches_natural_order_bitwise_on_text_only():
+    p = W.custom_prompt([("T", 700)], [D, S, I, IS], 2, 128, dtype="bf16")
+    q, k, v = W.make_qkv(p, 7, DEV)
+    a, _ = run_prefill(p, q, k, v)
+    b, _ = run_prefill(p, q, k, v, flags=bs.BS_MAP_REGROUP_ROWS)
+    assert torch.equal(a, b)
+
+
+@pytest.mark.parametrize("cfg", [2, 4])
+def test_regrouped_configs_sampled_rows(cfg):
+    sampled_parity(W.config(cfg), 0, n_random=3, max_tiles=10, row_step=[0, 0, 4, 16, 32][cfg],
+                   flags=bs.BS_MAP_REGROUP_ROWS)
 
 
 def test_config5_stress_72k_sampled_rows():

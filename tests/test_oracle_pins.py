@@ -142,6 +142,32 @@ def test_tile_states_from_bitmap():
             assert np.array_equal(oracle.tile_states(c, imgid, issink, bm, bn, sub), want[sub])
 
 
+def test_tile_states_for_row_lists_from_bitmap():
+    """Tile states of query tiles given as row lists: numpy gather + reduction of the bitmap.
+    The natural order reproduces the contiguous reduction; a shuffled order and tiles with
+    missing rows (slots of -1) are checked too."""
+    rng = np.random.default_rng(7)
+    for seed, (bm, bn) in enumerate([(8, 4), (16, 8), (4, 4)]):
+        p = small_prompt(seed)
+        imgid, issink = oracle.token_arrays(p.spans, p.seq_len, p.sink_len)
+        L = p.seq_len
+        M, N = -(-L // bm), -(-L // bn)
+        natural = np.full(M * bm, -1, dtype=np.int32)
+        natural[:L] = np.arange(L)
+        shuffled = natural.copy()
+        rng.shuffle(shuffled)
+        for c in range(4):
+            bitmap = np.zeros((L + 1, N * bn), dtype=np.int64)   # row L: "no row"
+            bitmap[:L, :L] = oracle.mask(c, imgid, issink)
+            for order in (natural, shuffled):
+                rows = order.reshape(M, bm)
+                cnt = bitmap[np.where(rows < 0, L, rows)].reshape(M, bm, N, bn).sum(axis=(1, 3))
+                want = np.where(cnt == 0, 0, np.where(cnt == bm * bn, 2, 1)).astype(np.uint8)
+                assert np.array_equal(oracle.tile_states_rows(c, imgid, issink, rows, bn), want)
+            assert np.array_equal(oracle.tile_states_rows(c, imgid, issink, natural.reshape(M, bm), bn),
+                                  oracle.tile_states(c, imgid, issink, bm, bn))
+
+
 # ----------------------------------------------------------------------------- softmax . V numerics
 
 def sdpa_fp64(q, k, v, G, scale, mask=None):

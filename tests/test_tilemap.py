@@ -105,6 +105,98 @@ def test_states_do_not_depend_on_head_classes():
         assert a.stats(c) == b.stats(c)
 
 
+# ------------------------------------------------------------------------- regrouped query rows
+
+def check_regrouped(spans, L, sink_len, bm, bn, hc=None, q_tiles=None):
+    """Map built with BS_MAP_REGROUP_ROWS against the oracle's reduction over the map's own row lists."""
+    hc = np.zeros(1, np.uint8) if hc is None else hc
+    tm = bs.bs_build_tilemap(spans, L, hc, sink_len, bm, bn, flags=bs.BS_MAP_REGROUP_ROWS)
+    imgid, issink = oracle.token_arrays(spans, L, sink_len)
+    rows = tm.row_order(bm)
+    # a permutation of the positions, image rows first, each group in position order
+    flat = rows[rows >= 0]
+    assert np.array_equal(np.sort(flat), np.arange(L))
+    n_img = int((imgid > 0).sum())
+    if 0 < n_img < L:
+        m_img = -(-n_img // bm)
+        img_part, txt_part = rows[:m_img].ravel(), rows[m_img:].ravel()
+        assert np.array_equal(img_part[img_part >= 0], np.flatnonzero(imgid > 0))
+        assert np.array_equal(txt_part[txt_part >= 0], np.flatnonzero(imgid == 0))
+        assert (img_part[:n_img] >= 0).all() and (img_part[n_img:] < 0).all()
+        assert tm.n_q_tiles == m_img + -(-(L - n_img) // bm)
+    else:
+        assert np.array_equal(rows.ravel()[:L], np.arange(L))
+    sel = np.arange(tm.n_q_tiles) if q_tiles is None else np.asarray(q_tiles)
+    for c in range(4):
+        want = oracle.tile_states_rows(c, imgid, issink, rows[sel], bn)
+        got = tm.tile_states(c) if q_tiles is None else np.stack([tm.tile_states(c, int(m), 1)[0] for m in sel])
+        assert np.array_equal(got, want), (c, np.argwhere(got != want)[:5])
+        st = tm.stats(c)
+        if q_tiles is None:
+            assert st["visited"] == int((want > 0).sum()) and st["full"] == int((want == 2).sum())
+        assert st["allowed_pairs"] == oracle.pair_count(c, imgid, issink)   # the grouping changes no pair
+    return tm
+
+
+@pytest.mark.parametrize("seed", range(30))
+def test_regrouped_random_prompts_small_tiles(seed):
+    rng = np.random.default_rng(500 + seed)
+    runs = []
+    for _ in range(int(rng.integers(1, 8))):
+        runs.append(("T", int(rng.integers(0, 14))))
+        runs.append(("I", int(rng.integers(1, 40))))
+        if rng.random() < 0.3:
+            runs.append(("I", int(rng.integers(1, 20))))
+    runs.append(("T", int(rng.integers(0, 10))))
+    L, spans = W.layout_from_runs(runs, ["prefix", "paper10"][seed % 2], [None, None, 3, 1000][seed % 4])
+    if L == 0:
+        return
+    bm, bn = [(8, 4), (16, 8), (4, 4), (8, 16), (32, 16)][seed % 5]
+    check_regrouped(spans, L, int(rng.integers(0, min(L, 12) + 1)), bm, bn)
+
+
+@pytest.mark.parametrize("path", all_fixtures())
+def test_regrouped_golden_prompts(path):
+    L, spans, sink_len, _ = load(path)
+    check_regrouped(spans, L, sink_len, 4, 2)
+
+
+def test_regrouped_single_text_tokens_between_images():
+    """Worst case for the number of runs in a text tile: every text row is its own run."""
+    runs = [("T", 1)]
+    for _ in range(40):
+        runs += [("I", 9), ("T", 1)]
+    L, spans = W.layout_from_runs(runs, "paper10")
+    check_regrouped(spans, L, 0, 16, 8)
+    check_regrouped(spans, L, 3, 128, 64)
+
+
+@pytest.mark.parametrize("cfg", [2, 4])
+def test_regrouped_large_configs_sampled(cfg):
+    p = W.config(cfg)
+    probe = bs.bs_build_tilemap(p.spans, p.seq_len, p.head_class, p.sink_len, flags=bs.BS_MAP_REGROUP_ROWS)
+    M = probe.n_q_tiles
+    n_img_tiles = -(-int(sum(e - s for s, e, _ in p.spans)) // 128)
+    sel = sorted({0, 1, n_img_tiles // 2, n_img_tiles - 1, n_img_tiles, M - 1})   # both groups and their ragged ends
+    tm = check_regrouped(p.spans, p.seq_len, p.sink_len, 128, 64, p.head_class, sel)
+    tm.pair_plan(p.gqa_group)   # validates every unit against the per-class lists
+    # the point of the grouping: the sparse classes visit fewer key tiles than in the natural order
+    nat = bs.bs_build_tilemap(p.spans, p.seq_len, p.head_class, p.sink_len)
+    for c in (1, 2, 3):
+        assert tm.stats(c)["visited"] < nat.stats(c)["visited"]
+
+
+def test_regroup_flag_without_effect_and_bad_flags():
+    L, spans = W.layout_from_runs([("T", 100)], "paper10")
+    a = bs.bs_build_tilemap(spans, L, np.zeros(2, np.uint8), 0, flags=bs.BS_MAP_REGROUP_ROWS)
+    b = bs.bs_build_tilemap(spans, L, np.zeros(2, np.uint8), 0)
+    assert np.array_equal(a.row_order(), b.row_order())
+    for c in range(4):
+        assert np.array_equal(a.tile_states(c), b.tile_states(c))
+    with pytest.raises(bs.BlindsightError):
+        bs.bs_build_tilemap(spans, L, np.zeros(2, np.uint8), 0, flags=2)
+
+
 # ------------------------------------------------------------------------- work units (KV-sharing pairs)
 
 @pytest.mark.parametrize("seed", range(12))
