@@ -32,6 +32,9 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=2, help="workload family 1..5 (default: the 36K one)")
     ap.add_argument("--target-len", type=int, default=None, help="config 5 prompt length")
+    ap.add_argument("--natural-order", action="store_true",
+                    help="build the tile map with query rows in position order (default: text rows "
+                         "regrouped into query tiles of their own, BS_MAP_REGROUP_ROWS)")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--sink-mode", default="paper10", choices=["paper10", "prefix"])
     ap.add_argument("--all-dense", action="store_true", help="run the same prompt with every head Dense")
@@ -77,9 +80,10 @@ class HipEvents:
 # HBM traffic per launch of the attention kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # runs, scaled by the same counters' reading for a 1 GiB copy (see profiles/).  Bytes.
 MEASURED_TRAFFIC = {
-    # profiles/attn_prefill_bf16_d128_cfg2_36k.md: 4.56 GB read + 0.28 GB written (measured where L2
-    # meets the fabric: the 256 MB memory-side cache sits behind that point)
-    "cfg2-qwen2vl7b-36k/paper10/seed0": 4.85e9,
+    # profiles/attn_prefill_bf16_d128_cfg2_36k.md (measured where L2 meets the fabric: the 256 MB
+    # memory-side cache sits behind that point); keyed by workload and row order of the tile map
+    ("cfg2-qwen2vl7b-36k/paper10/seed0", "regrouped"): 4.46e9,
+    ("cfg2-qwen2vl7b-36k/paper10/seed0", "natural"): 4.85e9,
 }
 
 
@@ -93,7 +97,7 @@ def class_totals(tm, head_class):
     return tot, per_class
 
 
-def timed_steps(bs, torch, p, q, k, v, out, steps, warmup, hev):
+def timed_steps(bs, torch, p, q, k, v, out, steps, warmup, hev, flags):
     """Returns (wall ms per step, mean attention-kernel ms, mean device ms of the whole call
     incl. map upload and the tile-pack pre-pass, mean host ms of the tile-map build, mean host ms
     inside the attention call (work-unit planning, staging, launches), last tile map)."""
@@ -106,7 +110,7 @@ def timed_steps(bs, torch, p, q, k, v, out, steps, warmup, hev):
 
     def step(record):
         t0 = time.perf_counter()
-        tm = bs.bs_build_tilemap(p.spans, p.seq_len, p.head_class, p.sink_len, 128, 64)
+        tm = bs.bs_build_tilemap(p.spans, p.seq_len, p.head_class, p.sink_len, 128, 64, flags=flags)
         t1 = time.perf_counter()
         e0 = torch.cuda.Event(enable_timing=True)
         e1 = torch.cuda.Event(enable_timing=True)
@@ -217,7 +221,9 @@ def main():
         torch.cuda.synchronize()
         del a, b
 
-    wall_ms, kern_ms, call_ms, build_ms, host_call_ms, tm = timed_steps(bs, torch, p, q, k, v, out, args.steps, args.warmup, hev)
+    flags = 0 if args.natural_order else bs.BS_MAP_REGROUP_ROWS
+    order = "natural" if args.natural_order else "regrouped"
+    wall_ms, kern_ms, call_ms, build_ms, host_call_ms, tm = timed_steps(bs, torch, p, q, k, v, out, args.steps, args.warmup, hev, flags)
     tot, per_class = class_totals(tm, p.head_class)
     d = p.head_dim
     useful_flop = 4.0 * d * tot["allowed_pairs"]
@@ -234,7 +240,7 @@ def main():
     if not args.all_dense and not args.no_dense_leg:
         pd = p.all_dense()
         dsteps = max(3, min(args.steps, 10))
-        d_wall, d_kern, _, _, _, d_tm = timed_steps(bs, torch, pd, q, k, v, out, dsteps, 1, hev)
+        d_wall, d_kern, _, _, _, d_tm = timed_steps(bs, torch, pd, q, k, v, out, dsteps, 1, hev, flags)
         d_tot, _ = class_totals(d_tm, pd.head_class)
         dense = {"ms_per_step": round(d_wall, 4), "kernel_ms": round(d_kern, 4), "steps": dsteps,
                  "visited_tiles": d_tot["visited"],
@@ -254,7 +260,7 @@ def main():
         "dtype": p.dtype, "data": "synthetic",
         "config": {"workload": p.name, "seq_len": p.seq_len, "n_q_heads": p.n_q_heads,
                    "n_kv_heads": p.n_kv_heads, "head_dim": d, "n_images": int(len(p.spans)),
-                   "sink_mode": args.sink_mode, "seed": args.seed,
+                   "sink_mode": args.sink_mode, "seed": args.seed, "row_order": order,
                    "head_classes": {n: int((p.head_class == c).sum()) for c, n in enumerate(W.CLASS_NAMES)}},
         "kernel_ms": round(kern_ms, 4),
         "device_ms_per_call": round(call_ms, 4),
@@ -269,7 +275,7 @@ def main():
                   "useful_over_executed": round(useful_flop / executed_flop, 4)},
         "all_dense": dense,
         "roofline": {"bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS,
-                     "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": MEASURED_TRAFFIC.get(p.name),
+                     "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": MEASURED_TRAFFIC.get((p.name, order)),
                      "kernel": "attn_prefill_%s<%d>" % (p.dtype, d),
                      "flop_per_launch": useful_flop, "avg_launch_ms": round(kern_ms, 4)},
     }
