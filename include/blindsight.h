@@ -89,6 +89,20 @@ int bs_build_tilemap(const bs_span *spans, int32_t n_spans, int32_t seq_len,
  * Errors: BS_EINVAL (also for unknown flag bits), BS_ENOMEM.
  */
 #define BS_MAP_REGROUP_ROWS 1u
+/*   BS_MAP_PACK_KEYS (implies BS_MAP_REGROUP_ROWS)   the map also gets compact key tiles: the free
+ *       keys of the prompt -- text keys and sink keys, which are what an image query of a sparse
+ *       class may see outside its own image -- gathered in position order into tiles of their
+ *       own, after the prompt's key tiles (n_k_tiles counts both).  The paper's kernel permutes
+ *       K / V so that text and sink keys are contiguous (App. kernel, "Attention Sink Subroutine",
+ *       Alg. 6); here they are a second copy, written by the bf16 pre-pass, because text queries
+ *       and Dense heads keep walking the prompt order.  An image-only query tile of a sparse
+ *       class then walks the compact tiles up to its causal bound (Sink: every slot; Intra-Image:
+ *       the text slots; Intra-Image+Sink: the slots outside its own image) plus, for the classes
+ *       with the intra bit, the prompt tiles of its own image, in which only own-image keys count.
+ *       Every allowed pair is still counted exactly once.  bs_tilemap_key_order reports the key
+ *       of every tile slot.  bf16 only (the fp32 kernel returns BS_EUNSUPPORTED for such a map).
+ *       No effect on a prompt without images, without free keys, or made of free keys only. */
+#define BS_MAP_PACK_KEYS 2u
 int bs_build_tilemap_ex(const bs_span *spans, int32_t n_spans, int32_t seq_len,
                         const uint8_t *head_class, int32_t n_q_heads, int32_t sink_len,
                         int32_t block_m, int32_t block_n, uint32_t flags, bs_tilemap **out);
@@ -108,6 +122,17 @@ int bs_tilemap_dims(const bs_tilemap *tm, int32_t *seq_len, int32_t *n_q_tiles,
 /* rows[n_q_tiles * block_m] (host): the position of every row of every query tile, -1 where a
  * tile has no row (the last tile of the prompt, or of a group of regrouped rows). */
 int bs_tilemap_row_order(const bs_tilemap *tm, int32_t *rows);
+
+/* What the map options did (any pointer may be NULL): regrouped = the row order differs from the
+ * position order; packed = compact key tiles exist; intra_compact = Intra-Image heads take their
+ * text keys from the compact tiles (they keep the prompt's tiles when those hold the text keys in
+ * fewer tiles, e.g. a few long images with little text between them). */
+int bs_tilemap_layout(const bs_tilemap *tm, int32_t *regrouped, int32_t *packed, int32_t *intra_compact);
+
+/* keys[n_k_tiles * block_n] (host, may be NULL): the position of the key in every slot of every
+ * key tile, -1 where a tile has no key; n_prompt_tiles (may be NULL): how many of the tiles are
+ * the prompt in position order (all of them unless the map was built with BS_MAP_PACK_KEYS). */
+int bs_tilemap_key_order(const bs_tilemap *tm, int32_t *keys, int32_t *n_prompt_tiles);
 
 /* Expand the range lists of class `cls` for query tiles [q_tile_begin, +q_tile_count) into
  * states[q_tile_count][n_k_tiles] (host, row-major): 0 skip, 1 partial, 2 full. */

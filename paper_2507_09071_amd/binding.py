@@ -17,7 +17,7 @@ from . import build as _build
 BS_BF16, BS_F32 = 0, 1
 DENSE, SINK, INTRA, INTRA_SINK = 0, 1, 2, 3
 
-EXPORTS = ("bs_build_tilemap", "bs_build_tilemap_ex", "bs_tilemap_destroy", "bs_tilemap_dims", "bs_tilemap_row_order", "bs_tilemap_tile_states",
+EXPORTS = ("bs_build_tilemap", "bs_build_tilemap_ex", "bs_tilemap_destroy", "bs_tilemap_dims", "bs_tilemap_row_order", "bs_tilemap_layout", "bs_tilemap_key_order", "bs_tilemap_tile_states",
            "bs_tilemap_stats", "bs_tilemap_pair_plan", "bs_tilemap_upload", "bs_attn_prefill", "bs_attn_prefill_ex", "bs_strerror",
            "bs_last_error")
 
@@ -72,6 +72,10 @@ def load_library():
     lib.bs_build_tilemap_ex.restype = ctypes.c_int
     lib.bs_tilemap_row_order.argtypes = [vp, i32p]
     lib.bs_tilemap_row_order.restype = ctypes.c_int
+    lib.bs_tilemap_layout.argtypes = [vp, i32p, i32p, i32p]
+    lib.bs_tilemap_layout.restype = ctypes.c_int
+    lib.bs_tilemap_key_order.argtypes = [vp, i32p, i32p]
+    lib.bs_tilemap_key_order.restype = ctypes.c_int
     lib.bs_tilemap_destroy.argtypes = [vp]
     lib.bs_tilemap_destroy.restype = None
     lib.bs_tilemap_dims.argtypes = [vp, i32p, i32p, i32p, i32p]
@@ -136,6 +140,20 @@ class TileMap:
                "bs_tilemap_row_order")
         return out
 
+    def layout(self) -> dict:
+        v = [ctypes.c_int32() for _ in range(3)]
+        _check(load_library().bs_tilemap_layout(self._h, *[ctypes.byref(x) for x in v]), "bs_tilemap_layout")
+        return {n: bool(x.value) for n, x in zip(("regrouped", "packed", "intra_compact"), v)}
+
+    def key_order(self, block_n: int = 64):
+        """(int32 [n_k_tiles, block_n] position of the key in every tile slot, -1 = none;
+        number of leading tiles that are the prompt in position order)."""
+        out = np.empty((self.n_k_tiles, block_n), dtype=np.int32)
+        n0 = ctypes.c_int32()
+        _check(load_library().bs_tilemap_key_order(self._h, out.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)),
+                                                   ctypes.byref(n0)), "bs_tilemap_key_order")
+        return out, int(n0.value)
+
     def stats(self, cls: int) -> dict:
         v = [ctypes.c_int64() for _ in range(6)]
         _check(load_library().bs_tilemap_stats(self._h, cls, *[ctypes.byref(x) for x in v]),
@@ -165,12 +183,13 @@ class TileMap:
 
 
 BS_MAP_REGROUP_ROWS = 1
+BS_MAP_PACK_KEYS = 2
 
 
 def bs_build_tilemap(spans, seq_len: int, head_class, sink_len: int = 0,
                      block_m: int = 128, block_n: int = 64, flags: int = 0) -> TileMap:
     """spans: int array [G,3] of (start, end, sink); head_class: uint8 [n_q_heads];
-    flags: 0 or BS_MAP_REGROUP_ROWS (goes through bs_build_tilemap_ex)."""
+    flags: 0 or BS_MAP_REGROUP_ROWS / BS_MAP_PACK_KEYS (goes through bs_build_tilemap_ex)."""
     lib = load_library()
     sp = np.ascontiguousarray(np.asarray(spans, dtype=np.int32).reshape(-1, 3))
     hc = np.ascontiguousarray(head_class, dtype=np.uint8)

@@ -53,6 +53,9 @@ struct DeviceMap {
     size_t blob_cap = 0;
     const uint32_t *code = nullptr;       // [L] per-token code
     const int32_t *row_order = nullptr;   // [M * 128] position of each query-tile row, -1 = none
+    const int32_t *key_order = nullptr;   // [N * 64] position of each key-tile slot, -1 = none
+    const int32_t *free_before = nullptr; // packed: [L + 1]
+    const int2 *span_free = nullptr;      // packed: [G + 1] compact slots of the free keys inside each image
     const uint64_t *text_bits = nullptr;  // [N] text keys of each key tile
     const uint64_t *sink_bits = nullptr;  // [N] sink keys of each key tile
     const int2 *span_range = nullptr;     // [G+1] (start, end) by imgid; entry 0 unused
@@ -87,6 +90,8 @@ struct KernelArgs {
     void *out;
     int32_t L, M, G;
     float scale_log2e;  // scale * log2(e): softmax runs in the exp2 domain
+    int32_t n_prompt_tiles;   // key tiles that are the prompt in position order (compact tiles follow)
+    int32_t packed, intra_compact;
 };
 #define BS_MAP_PARAMS                                                                              \
     const uint32_t *__restrict__ map_code, const uint64_t *__restrict__ map_text_bits,             \
@@ -135,20 +140,39 @@ struct TileWalker {
 };
 
 // What the lane's query may see (paper Sec. 3.2), in a form that is cheap to apply per tile.
+// With packed keys (see the tile-map builder) an image query of a sparse class reads the free
+// keys -- text and sink keys -- from compact tiles and only own-image keys from the prompt's
+// tiles, so that every allowed pair is counted once.
 struct QueryView {
     int32_t row;       // query position i
     int32_t own_lo;    // own image [own_lo, own_hi) if the class attends inside images, else empty
     int32_t own_hi;
+    int32_t free_bound;  // packed: free keys at positions <= i (the visible compact slots are [0, free_bound))
+    int32_t cfree_lo;    // packed, Intra-Image+Sink: compact slots of the free keys inside the own image
+    int32_t cfree_hi;
     bool sees_all;     // text query or Dense head: every earlier key
-    __device__ void init(const uint32_t *__restrict__ code, const int2 *__restrict__ span_range, int L, int cls, int32_t i)
+    bool own_only;     // packed: in the prompt's tiles only own-image keys count for this query
+    __device__ void init(const uint32_t *__restrict__ code, const int2 *__restrict__ span_range,
+                         const int32_t *__restrict__ free_before, const int2 *__restrict__ span_free,
+                         int L, int cls, int32_t i, bool packed, bool intra_compact)
     {
         row = i;
         const uint32_t qcode = i < L ? code[i] : kCodeText;
         sees_all = (qcode & kCodeText) || cls == BS_DENSE;
         own_lo = own_hi = 0;
+        free_bound = cfree_lo = cfree_hi = 0;
+        own_only = false;
         if (!sees_all && (cls & 2)) {
             const int2 sp = span_range[qcode & kCodeImgMask];
             own_lo = sp.x; own_hi = sp.y;
+        }
+        if (packed && !sees_all && (cls != BS_INTRA || intra_compact)) {
+            free_bound = free_before[i + 1];
+            own_only = true;
+            if (cls == BS_INTRA_SINK) {
+                const int2 cr = span_free[qcode & kCodeImgMask];
+                cfree_lo = cr.x; cfree_hi = cr.y;
+            }
         }
     }
 };
@@ -157,16 +181,27 @@ __device__ inline uint64_t bits_below(int x)  // bits [0, x), x in [0, 64]
 {
     return x >= 64 ? ~0ull : ((1ull << x) - 1ull);
 }
-
-// Bit b set <=> key n0 + b is allowed for this lane's query.  tbits / sbits: text keys and
-// (class-enabled) sink keys of the tile.
-__device__ inline uint64_t allowed_keys(const QueryView &qv, uint64_t tbits, uint64_t sbits, int n0)
+__device__ inline uint64_t bits_between(int lo, int hi)  // bits [lo, hi) clipped to [0, 64)
 {
-    const uint64_t base = qv.sees_all ? ~0ull : (tbits | sbits);
-    const int lo = min(max(qv.own_lo - n0, 0), 64), hi = min(max(qv.own_hi - n0, 0), 64);
-    const uint64_t own = bits_below(hi) & ~bits_below(lo);
-    const int cz = min(max(qv.row - n0 + 1, 0), 64);  // causal: keys n0 .. row
-    return (base | own) & bits_below(cz);
+    return bits_below(min(max(hi, 0), 64)) & ~bits_below(min(max(lo, 0), 64));
+}
+
+// Bit b set <=> the key in slot b of key tile n is allowed for this lane's query.  tbits / sbits:
+// text keys and sink keys of the tile; n_prompt: number of key tiles that are the prompt in
+// position order (the tiles after them are compact tiles of free keys).
+__device__ inline uint64_t allowed_keys(const QueryView &qv, int cls, uint64_t tbits, uint64_t sbits, int n, int n_prompt)
+{
+    if (n < n_prompt) {
+        const int n0 = n * kBlockN;
+        const uint64_t base = qv.sees_all ? ~0ull : (qv.own_only ? 0ull : (tbits | ((cls & 1) ? sbits : 0ull)));
+        const uint64_t own = bits_between(qv.own_lo - n0, qv.own_hi - n0);
+        return (base | own) & bits_below(min(max(qv.row - n0 + 1, 0), 64));   // causal: keys n0 .. row
+    }
+    // compact tile: slots are free keys in position order, visible up to the row's bound
+    const int s0 = (n - n_prompt) * kBlockN;
+    const uint64_t base = qv.sees_all ? 0ull : ((cls & 1) ? ~0ull : tbits);   // Intra-Image: text keys only
+    const uint64_t excl = bits_between(qv.cfree_lo - s0, qv.cfree_hi - s0);   // counted with the own image
+    return base & ~excl & bits_below(min(max(qv.free_bound - s0, 0), 64));
 }
 
 // Score block layout (two 32x32 MFMA C tiles): lane (hl = lane/32, col = lane%32) holds, for
@@ -346,20 +381,23 @@ __device__ inline void mfma_drain(floatx16 &c0, floatx16 &c1)
 //            as two halves h holding keys 16g + {4h..4h+3, 8+4h..8+4h+3} (the contraction slots
 //            of lane half h), stored at half h ^ ((channel >> 3) & 1)
 // A 128-bit read of 16 consecutive keys (channels) then touches every bank exactly once.
-// Keys past the end of the prompt are zero-filled.
+// The key of every tile slot comes from the map's key order (the prompt in position order, then
+// the compact tiles of a packed map); slots without a key are zero-filled.
 template <int D>
-__global__ __launch_bounds__(256) void pack_vt_tiles(const __bf16 *__restrict__ v, __bf16 *__restrict__ vt, int L, int N)
+__global__ __launch_bounds__(256) void pack_vt_tiles(const __bf16 *__restrict__ v, __bf16 *__restrict__ vt,
+                                                     const int32_t *__restrict__ key_order, int L, int N)
 {
     constexpr int PAD = D + 2;  // odd word stride: the column gathers below spread over banks
     __shared__ __bf16 tile[kBlockN * PAD];
     const int n = blockIdx.x, kvh = blockIdx.y, tid = threadIdx.x;
-    const __bf16 *src = v + ((size_t)kvh * L + (size_t)n * kBlockN) * D;
+    const __bf16 *src = v + (size_t)kvh * L * D;
     for (int idx = tid; idx < kBlockN * (D / 8); idx += 256) {
         const int key = idx / (D / 8), ch = idx % (D / 8);
+        const int pos = key_order[n * kBlockN + key];   // -1: the slot holds no key
         bf16x8 val;
 #pragma unroll
         for (int e = 0; e < 8; ++e) val[e] = (__bf16)0.f;
-        if (n * kBlockN + key < L) val = *reinterpret_cast<const bf16x8 *>(src + (size_t)key * D + ch * 8);
+        if (pos >= 0) val = *reinterpret_cast<const bf16x8 *>(src + (size_t)pos * D + ch * 8);
 #pragma unroll
         for (int e = 0; e < 8; ++e) tile[key * PAD + ch * 8 + e] = val[e];
     }
@@ -376,16 +414,18 @@ __global__ __launch_bounds__(256) void pack_vt_tiles(const __bf16 *__restrict__ 
 }
 
 template <int D>
-__global__ __launch_bounds__(256) void pack_k_tiles(const __bf16 *__restrict__ k, __bf16 *__restrict__ kp, int L, int N)
+__global__ __launch_bounds__(256) void pack_k_tiles(const __bf16 *__restrict__ k, __bf16 *__restrict__ kp,
+                                                    const int32_t *__restrict__ key_order, int L, int N)
 {
     const int n = blockIdx.x, kvh = blockIdx.y;
-    const __bf16 *src = k + ((size_t)kvh * L + (size_t)n * kBlockN) * D;
+    const __bf16 *src = k + (size_t)kvh * L * D;
     __bf16 *dst = kp + ((size_t)kvh * N + n) * (size_t)(D * kBlockN);
     for (int idx = threadIdx.x; idx < kBlockN * (D / 8); idx += 256) {   // one 16-byte half per iteration
         const int hp = idx & 1, key = (idx >> 1) % kBlockN, t = idx / (2 * kBlockN);
         const int h = hp ^ ((key >> 3) & 1);
+        const int pos = key_order[n * kBlockN + key];   // -1: the slot holds no key
         uint4 val = make_uint4(0, 0, 0, 0);
-        if (n * kBlockN + key < L) val = *reinterpret_cast<const uint4 *>(src + (size_t)key * D + 16 * t + 8 * h);
+        if (pos >= 0) val = *reinterpret_cast<const uint4 *>(src + (size_t)pos * D + 16 * t + 8 * h);
         *reinterpret_cast<uint4 *>(dst + (size_t)idx * 8) = val;
     }
 }
@@ -481,6 +521,7 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(
     KernelArgs a, const uint32_t *__restrict__ map_code, const uint64_t *__restrict__ map_text_bits,
     const uint64_t *__restrict__ map_sink_bits, const int2 *__restrict__ map_span_range,
     const uint8_t *__restrict__ map_head_class, const int32_t *__restrict__ map_row_order,
+    const int32_t *__restrict__ map_free_before, const int2 *__restrict__ map_span_free,
     const int4 *__restrict__ pair_items,
     const int2 *__restrict__ pair_ranges, const __bf16 *__restrict__ kp, const __bf16 *__restrict__ vt,
     int32_t n_k_tiles)
@@ -527,7 +568,7 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(
             qreg[t] = *reinterpret_cast<const bf16x8 *>(qh + (size_t)qrow * D + 16 * t + 8 * hl);
     }
     QueryView qv;
-    qv.init(map_code, map_span_range, L, cls, row);
+    qv.init(map_code, map_span_range, map_free_before, map_span_free, L, cls, row, a.packed != 0, a.intra_compact != 0);
 
     // LDS byte address of this lane's MFMA operand fragments inside a K / V^T tile (see the
     // tile layouts above): key or channel `col`, half hl; slices, blocks and groups are
@@ -735,7 +776,7 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(
                 softmax_pack<0>(s, pf, m_run, l_run, alpha, a.scale_log2e, false);
             } else {
                 const int nu = __builtin_amdgcn_readfirstlane(w0.n);
-                uint64_t allowed = allowed_keys(qv, tb_cur, (cls & 1) ? sb_cur : 0ull, nu * kBlockN);
+                uint64_t allowed = allowed_keys(qv, cls, tb_cur, sb_cur, nu, a.n_prompt_tiles);
                 if (st == 0) allowed = 0ull;
                 if (__all(allowed == 0ull || allowed == ~0ull)) {
                     // every query of the wave sees all 64 keys or none (e.g. a text row and an
@@ -878,7 +919,7 @@ __global__ __launch_bounds__(kThreads, 1) void attn_prefill_f32(KernelArgs a, BS
         for (int t = 0; t < D / 2; ++t) qreg[t] = qh[(size_t)qrow * D + 2 * t + hl];
     }
     QueryView qv;
-    qv.init(map_code, map_span_range, a.L, cls, row);
+    qv.init(map_code, map_span_range, nullptr, nullptr, a.L, cls, row, false, false);
 
     floatx16 o[D / 32];
 #pragma unroll
@@ -920,8 +961,8 @@ __global__ __launch_bounds__(kThreads, 1) void attn_prefill_f32(KernelArgs a, BS
             softmax_block<false>(s, m_run, l_run, alpha, a.scale_log2e);
         } else {
             const uint64_t tb = map_text_bits[tw.n];
-            const uint64_t sb = (cls & 1) ? map_sink_bits[tw.n] : 0ull;
-            apply_mask(s, allowed_keys(qv, tb, sb, n0), hl);
+            const uint64_t sb = map_sink_bits[tw.n];
+            apply_mask(s, allowed_keys(qv, cls, tb, sb, tw.n, a.n_prompt_tiles), hl);
             softmax_block<true>(s, m_run, l_run, alpha, a.scale_log2e);
         }
 #pragma unroll
@@ -1097,7 +1138,10 @@ static int upload_on_stream(bs_tilemap *tm, hipStream_t st)
     auto align = [](size_t x) { return (x + 255) & ~(size_t)255; };
     const size_t off_code = 0;
     const size_t off_rows = align(off_code + (size_t)tm->L * 4);
-    const size_t off_tbits = align(off_rows + tm->row_order.size() * 4);
+    const size_t off_keys = align(off_rows + tm->row_order.size() * 4);
+    const size_t off_fbefore = align(off_keys + tm->key_order.size() * 4);
+    const size_t off_sfree = align(off_fbefore + std::max<size_t>(tm->free_before.size(), 1) * 4);
+    const size_t off_tbits = align(off_sfree + std::max<size_t>(tm->span_free_range.size(), 2) * 4);
     const size_t off_sbits = align(off_tbits + (size_t)tm->N * 8);
     const size_t off_spans = align(off_sbits + (size_t)tm->N * 8);
     const size_t off_rowptr = align(off_spans + G1 * 8);
@@ -1117,6 +1161,10 @@ static int upload_on_stream(bs_tilemap *tm, hipStream_t st)
     }
     std::memcpy(host.data() + off_code, tm->code.data(), (size_t)tm->L * 4);
     std::memcpy(host.data() + off_rows, tm->row_order.data(), tm->row_order.size() * 4);
+    std::memcpy(host.data() + off_keys, tm->key_order.data(), tm->key_order.size() * 4);
+    if (!tm->free_before.empty()) std::memcpy(host.data() + off_fbefore, tm->free_before.data(), tm->free_before.size() * 4);
+    if (!tm->span_free_range.empty())
+        std::memcpy(host.data() + off_sfree, tm->span_free_range.data(), tm->span_free_range.size() * 4);
     std::memcpy(host.data() + off_tbits, tm->text_bits.data(), (size_t)tm->N * 8);
     std::memcpy(host.data() + off_sbits, tm->sink_bits.data(), (size_t)tm->N * 8);
     int2 *sp = reinterpret_cast<int2 *>(host.data() + off_spans);
@@ -1168,6 +1216,9 @@ static int upload_on_stream(bs_tilemap *tm, hipStream_t st)
     d->last_use = holder;
     d->code = reinterpret_cast<const uint32_t *>(b + off_code);
     d->row_order = reinterpret_cast<const int32_t *>(b + off_rows);
+    d->key_order = reinterpret_cast<const int32_t *>(b + off_keys);
+    d->free_before = reinterpret_cast<const int32_t *>(b + off_fbefore);
+    d->span_free = reinterpret_cast<const int2 *>(b + off_sfree);
     d->text_bits = reinterpret_cast<const uint64_t *>(b + off_tbits);
     d->sink_bits = reinterpret_cast<const uint64_t *>(b + off_sbits);
     d->span_range = reinterpret_cast<const int2 *>(b + off_spans);
@@ -1231,6 +1282,10 @@ extern "C" int bs_attn_prefill_ex(const void *q, const void *k, const void *v, v
     a.q = q; a.k = k; a.v = v; a.out = out;
     a.L = tm->L; a.M = tm->M; a.G = gqa_group;
     a.scale_log2e = scale * 1.4426950408889634f;
+    a.n_prompt_tiles = tm->N0;
+    a.packed = tm->packed;
+    a.intra_compact = tm->intra_compact;
+    if (tm->packed && dtype != BS_BF16) return BS_EUNSUPPORTED;   // the fp32 kernel reads K / V in place
 
     const dim3 grid((unsigned)d->n_work), block(bs::kThreads);
     if (dtype == BS_BF16) {
@@ -1278,21 +1333,21 @@ extern "C" int bs_attn_prefill_ex(const void *q, const void *k, const void *v, v
             e = hipFuncSetAttribute(reinterpret_cast<const void *>(bs::attn_prefill_bf16<128>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, lds);
             if (e != hipSuccess) return bs::fail_hip(e, "hipFuncSetAttribute");
-            hipLaunchKernelGGL(bs::pack_k_tiles<128>, tgrid, dim3(256), 0, st, static_cast<const __bf16 *>(k), kp, tm->L, tm->N);
-            hipLaunchKernelGGL(bs::pack_vt_tiles<128>, tgrid, dim3(256), 0, st, static_cast<const __bf16 *>(v), vt, tm->L, tm->N);
+            hipLaunchKernelGGL(bs::pack_k_tiles<128>, tgrid, dim3(256), 0, st, static_cast<const __bf16 *>(k), kp, d->key_order, tm->L, tm->N);
+            hipLaunchKernelGGL(bs::pack_vt_tiles<128>, tgrid, dim3(256), 0, st, static_cast<const __bf16 *>(v), vt, d->key_order, tm->L, tm->N);
             if (ev_main_start) (void)hipEventRecord(static_cast<hipEvent_t>(ev_main_start), st);
             hipLaunchKernelGGL(bs::attn_prefill_bf16<128>, pgrid, pblock, lds, st, a, d->code, d->text_bits, d->sink_bits,
-                               d->span_range, d->head_class, d->row_order, d->pair_items, d->pair_ranges, kp, vt, tm->N);
+                               d->span_range, d->head_class, d->row_order, d->free_before, d->span_free, d->pair_items, d->pair_ranges, kp, vt, tm->N);
         } else {
             constexpr int lds = bs::bf16_lds_bytes<64>();
             e = hipFuncSetAttribute(reinterpret_cast<const void *>(bs::attn_prefill_bf16<64>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, lds);
             if (e != hipSuccess) return bs::fail_hip(e, "hipFuncSetAttribute");
-            hipLaunchKernelGGL(bs::pack_k_tiles<64>, tgrid, dim3(256), 0, st, static_cast<const __bf16 *>(k), kp, tm->L, tm->N);
-            hipLaunchKernelGGL(bs::pack_vt_tiles<64>, tgrid, dim3(256), 0, st, static_cast<const __bf16 *>(v), vt, tm->L, tm->N);
+            hipLaunchKernelGGL(bs::pack_k_tiles<64>, tgrid, dim3(256), 0, st, static_cast<const __bf16 *>(k), kp, d->key_order, tm->L, tm->N);
+            hipLaunchKernelGGL(bs::pack_vt_tiles<64>, tgrid, dim3(256), 0, st, static_cast<const __bf16 *>(v), vt, d->key_order, tm->L, tm->N);
             if (ev_main_start) (void)hipEventRecord(static_cast<hipEvent_t>(ev_main_start), st);
             hipLaunchKernelGGL(bs::attn_prefill_bf16<64>, pgrid, pblock, lds, st, a, d->code, d->text_bits, d->sink_bits,
-                               d->span_range, d->head_class, d->row_order, d->pair_items, d->pair_ranges, kp, vt, tm->N);
+                               d->span_range, d->head_class, d->row_order, d->free_before, d->span_free, d->pair_items, d->pair_ranges, kp, vt, tm->N);
         }
     } else {
         if (ev_main_start) (void)hipEventRecord(static_cast<hipEvent_t>(ev_main_start), st);

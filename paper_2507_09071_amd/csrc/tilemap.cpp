@@ -32,6 +32,10 @@ struct Geometry {
     // per key tile, for classes without / with the sink bit: smallest n' >= n whose keys are
     // all free (text, or text/sink) and which is a complete tile; N if none
     std::vector<int32_t> next_allfree_tile[2];  // N+1 each
+    // packed keys: compact tiles N .. N + Nc - 1 hold the free keys (text or sink) in position order
+    bool packed = false, intra_compact = false;
+    int32_t Nc = 0, n_free = 0;
+    std::vector<int32_t> ctext;        // n_free + 1: text keys among compact slots [0, s)
 
     const std::vector<int32_t> &free_count(int cls) const { return (cls & 1) ? n_free_sink : n_text; }
     const std::vector<int32_t> &next_free(int cls) const { return (cls & 1) ? next_free_sink : next_text; }
@@ -199,6 +203,65 @@ void build_run(const Geometry &G, int cls, const QueryTile &qt, std::vector<int3
     flush();
 }
 
+// Packed keys: range list of rows [a, b), all inside image g (0-based span index), for a sparse
+// class.  Two parts, disjoint by construction:
+//   own-image keys (classes with the intra bit): the prompt's own tiles over [start_g, b);
+//     a pair (i, j) counts there iff start_g <= j <= i;
+//   free keys: compact tiles; row i sees compact slot s iff s < free_before[i + 1] (the free
+//     keys at positions <= i) and
+//       Sink:             every such slot
+//       Intra-Image:      the text slots
+//       Intra-Image+Sink: every slot outside the image's own free keys (those are counted above).
+void build_run_packed(const Geometry &G, int cls, int32_t g, int32_t a, int32_t b, bool ragged,
+                      std::vector<TileRange> &out)
+{
+    out.clear();
+    int32_t run_begin = -1, run_end = -1, run_state = 0;
+    auto flush = [&]() {
+        if (run_begin >= 0) out.push_back({run_begin, (run_end << 1) | (run_state == 2)});
+        run_begin = -1;
+    };
+    auto emit = [&](int32_t bg, int32_t en, int st) {
+        if (en <= bg || st == 0) return;
+        if (run_begin >= 0 && bg == run_end && st == run_state) {
+            run_end = en;
+        } else {
+            flush();
+            run_begin = bg; run_end = en; run_state = st;
+        }
+    };
+    const auto &sp = *G.spans;
+    const auto &nfs = G.n_free_sink;
+    if (cls & 2) {
+        const int32_t s0 = sp[g].start;
+        for (int32_t n = s0 / G.bn; n <= (b - 1) / G.bn; ++n) {
+            const int32_t c0 = n * G.bn, c1 = c0 + G.bn;
+            const bool full = !ragged && c0 >= s0 && c1 - 1 <= a && c1 <= G.L;
+            emit(n, n + 1, full ? 2 : 1);
+        }
+    }
+    const int32_t fb_min = nfs[a + 1], fb_max = nfs[b];   // visible free keys of the first / last row
+    const int32_t own_lo = nfs[sp[g].start], own_hi = nfs[sp[g].end];
+    const int32_t c_end = (fb_max + G.bn - 1) / G.bn;
+    for (int32_t c = 0; c < c_end; ++c) {
+        const int32_t s0 = c * G.bn, s1 = s0 + G.bn, vis = std::min(s1, fb_max);   // slots [s0, vis) are visible to the last row
+        const bool below_all = !ragged && s1 <= fb_min;   // every slot visible to every row (implies a complete tile)
+        int st;
+        if (cls == BS_SINK) {
+            st = below_all ? 2 : 1;
+        } else if (cls == BS_INTRA) {
+            const int32_t t = G.ctext[vis] - G.ctext[s0];
+            st = t == 0 ? 0 : ((below_all && t == G.bn) ? 2 : 1);
+        } else {
+            const int32_t lo = std::max(s0, own_lo), hi = std::min(vis, own_hi);
+            const int32_t own = hi > lo ? hi - lo : 0;
+            st = own == vis - s0 ? 0 : ((below_all && own == 0) ? 2 : 1);
+        }
+        emit(G.N + c, G.N + c + 1, st);
+    }
+    flush();
+}
+
 // Union of two range lists of one query tile's runs.  A key tile is FULL for the tile only if
 // it is FULL for every run; visited by some run and not FULL for all of them: PARTIAL.
 // `a_runs` tells how many runs list a stands for (a tile absent from a is skipped by all of them).
@@ -239,7 +302,7 @@ void build_class(const Geometry &G, int cls, const std::vector<int32_t> &row_ord
     out.ranges.clear();
     QueryTile qt;
     std::vector<int32_t> cand;
-    std::vector<TileRange> run, acc, tmp;
+    std::vector<TileRange> run, seg_run, acc, tmp;
     for (int32_t m = 0; m < G.M; ++m) {
         // the tile's rows as runs of consecutive positions (one run in the natural order)
         const int32_t *rows = row_order.data() + (size_t)m * G.bm;
@@ -252,7 +315,21 @@ void build_class(const Geometry &G, int cls, const std::vector<int32_t> &row_ord
             int32_t j = i + 1;
             while (j < n_rows && rows[j] == rows[j - 1] + 1) ++j;
             describe_query_rows(G, rows[i], rows[j - 1] + 1, ragged, qt);
-            build_run(G, cls, qt, cand, run);
+            if (G.packed && cls != BS_DENSE && (cls != BS_INTRA || G.intra_compact) && qt.last_text < 0 && !qt.segs.empty()) {
+                // image rows of a sparse class: one packed list per image the run touches
+                // (two images can be adjacent without a text token between them)
+                bool first_seg = true;
+                for (const Segment &sg : qt.segs) {
+                    build_run_packed(G, cls, sg.g, sg.a, sg.b, ragged, first_seg ? run : seg_run);
+                    if (!first_seg) {
+                        combine_runs(run, seg_run, tmp);
+                        run.swap(tmp);
+                    }
+                    first_seg = false;
+                }
+            } else {
+                build_run(G, cls, qt, cand, run);
+            }
             if (first) {
                 acc.swap(run);
                 first = false;
@@ -324,7 +401,8 @@ extern "C" int bs_build_tilemap_ex(const bs_span *spans, int32_t n_spans, int32_
                                    const uint8_t *head_class, int32_t n_q_heads, int32_t sink_len,
                                    int32_t block_m, int32_t block_n, uint32_t flags, bs_tilemap **out)
 {
-    if (flags & ~(uint32_t)BS_MAP_REGROUP_ROWS) return BS_EINVAL;
+    if (flags & ~(uint32_t)(BS_MAP_REGROUP_ROWS | BS_MAP_PACK_KEYS)) return BS_EINVAL;
+    if (flags & BS_MAP_PACK_KEYS) flags |= BS_MAP_REGROUP_ROWS;   // packed lists exist for image-only query tiles
     if (!out || !head_class || n_q_heads <= 0 || seq_len <= 0 || n_spans < 0) return BS_EINVAL;
     if (n_spans > 0 && !spans) return BS_EINVAL;
     if (sink_len < 0 || sink_len > seq_len || block_m <= 0 || block_n <= 0) return BS_EINVAL;
@@ -338,7 +416,7 @@ extern "C" int bs_build_tilemap_ex(const bs_span *spans, int32_t n_spans, int32_
         tm = new bs_tilemap();
         const int32_t L = seq_len;
         tm->L = L; tm->bm = block_m; tm->bn = block_n; tm->sink_len = sink_len;
-        tm->N = (L + block_n - 1) / block_n;
+        tm->N0 = tm->N = (L + block_n - 1) / block_n;
         tm->n_q_heads = n_q_heads;
         tm->spans.assign(spans, spans + n_spans);
         tm->head_class.assign(head_class, head_class + n_q_heads);
@@ -353,14 +431,37 @@ extern "C" int bs_build_tilemap_ex(const bs_span *spans, int32_t n_spans, int32_
                 tm->code[t] = c;
             }
 
+        // Key tiles: the prompt's keys in position order, then (packed) compact tiles with the
+        // free keys -- text keys and sink keys, what an image query of a sparse class may see
+        // outside its own image -- in position order.  The paper's kernel permutes K / V so that
+        // these keys are contiguous (App. kernel, "Attention Sink Subroutine"); here they are a
+        // second copy, because text queries and Dense heads keep walking the original order.
+        std::vector<int32_t> free_pos;
+        if (flags & BS_MAP_PACK_KEYS) {
+            bool any_image = false;
+            for (int32_t t = 0; t < L; ++t) {
+                if (tm->code[t] & (bs::kCodeText | bs::kCodeSink)) free_pos.push_back(t);
+                if (!(tm->code[t] & bs::kCodeText)) any_image = true;
+            }
+            if (any_image && !free_pos.empty() && free_pos.size() < (size_t)L) {
+                tm->packed = true;
+                tm->N = tm->N0 + (int32_t)((free_pos.size() + block_n - 1) / block_n);
+            }
+        }
+        tm->key_order.assign((size_t)tm->N * block_n, -1);
+        for (int32_t t = 0; t < L; ++t) tm->key_order[t] = t;
+        if (tm->packed) std::copy(free_pos.begin(), free_pos.end(), tm->key_order.begin() + (size_t)tm->N0 * block_n);
+
         // per-key-tile bit masks for the kernel's 64-wide element predicate
         if (block_n <= 64) {
             tm->text_bits.assign(tm->N, 0);
             tm->sink_bits.assign(tm->N, 0);
-            for (int32_t t = 0; t < L; ++t) {
-                const uint64_t bit = 1ull << (t % block_n);
-                if (tm->code[t] & bs::kCodeText) tm->text_bits[t / block_n] |= bit;
-                if (tm->code[t] & bs::kCodeSink) tm->sink_bits[t / block_n] |= bit;
+            for (size_t slot = 0; slot < tm->key_order.size(); ++slot) {
+                const int32_t t = tm->key_order[slot];
+                if (t < 0) continue;
+                const uint64_t bit = 1ull << (slot % block_n);
+                if (tm->code[t] & bs::kCodeText) tm->text_bits[slot / block_n] |= bit;
+                if (tm->code[t] & bs::kCodeSink) tm->sink_bits[slot / block_n] |= bit;
             }
         }
 
@@ -390,7 +491,7 @@ extern "C" int bs_build_tilemap_ex(const bs_span *spans, int32_t n_spans, int32_
         }
 
         Geometry G;
-        G.L = L; G.bm = block_m; G.bn = block_n; G.M = tm->M; G.N = tm->N; G.spans = &tm->spans;
+        G.L = L; G.bm = block_m; G.bn = block_n; G.M = tm->M; G.N = tm->N0; G.spans = &tm->spans;
         G.n_text.assign(L + 1, 0);
         G.n_free_sink.assign(L + 1, 0);
         G.last_text.assign(L, -1);
@@ -412,14 +513,42 @@ extern "C" int bs_build_tilemap_ex(const bs_span *spans, int32_t n_spans, int32_
 
         for (int b = 0; b < 2; ++b) {
             const std::vector<int32_t> &fc = b ? G.n_free_sink : G.n_text;
-            G.next_allfree_tile[b].assign(tm->N + 1, tm->N);
-            for (int32_t n = tm->N - 1; n >= 0; --n) {
+            G.next_allfree_tile[b].assign(tm->N0 + 1, tm->N0);
+            for (int32_t n = tm->N0 - 1; n >= 0; --n) {
                 const int32_t c0 = n * block_n, c1 = std::min(c0 + block_n, L);
                 const bool allfree = (c1 - c0 == block_n) && (fc[c1] - fc[c0] == block_n);
                 G.next_allfree_tile[b][n] = allfree ? n : G.next_allfree_tile[b][n + 1];
             }
         }
+        if (tm->packed) {
+            G.packed = true;
+            G.n_free = (int32_t)free_pos.size();
+            G.Nc = tm->N - tm->N0;
+            G.ctext.assign(free_pos.size() + 1, 0);
+            for (size_t s2 = 0; s2 < free_pos.size(); ++s2)
+                G.ctext[s2 + 1] = G.ctext[s2] + ((tm->code[free_pos[s2]] & bs::kCodeText) ? 1 : 0);
+            // what the kernel needs per row / per image: free keys before a position, and the
+            // compact slots of the free keys that lie inside each image
+            tm->free_before = G.n_free_sink;
+            tm->span_free_range.assign(2 * ((size_t)n_spans + 1), 0);
+            for (int32_t g = 0; g < n_spans; ++g) {
+                tm->span_free_range[2 * (g + 1)] = G.n_free_sink[spans[g].start];
+                tm->span_free_range[2 * (g + 1) + 1] = G.n_free_sink[spans[g].end];
+            }
+        }
         for (int c = 0; c < 4; ++c) build_class(G, c, tm->row_order, tm->cls[c]);
+        if (tm->packed) {
+            // Intra-Image rows need the text keys only.  Among the compact tiles they are mixed
+            // with the sink keys; where text is rare (a few long images) the prompt's own tiles
+            // hold it in fewer tiles.  Both lists are exact: keep the shorter one.
+            G.intra_compact = true;
+            ClassLists alt;
+            build_class(G, BS_INTRA, tm->row_order, alt);
+            if (alt.visited < tm->cls[BS_INTRA].visited) {
+                tm->cls[BS_INTRA] = std::move(alt);
+                tm->intra_compact = true;
+            }
+        }
         count_pairs(G, tm->code, tm->cls);
 
         // work list: heaviest (head, query tile) first so the tail of the launch is short;
@@ -681,6 +810,23 @@ extern "C" int bs_tilemap_row_order(const bs_tilemap *tm, int32_t *rows)
 {
     if (!tm || !rows) return BS_EINVAL;
     std::memcpy(rows, tm->row_order.data(), tm->row_order.size() * sizeof(int32_t));
+    return BS_OK;
+}
+
+extern "C" int bs_tilemap_layout(const bs_tilemap *tm, int32_t *regrouped, int32_t *packed, int32_t *intra_compact)
+{
+    if (!tm) return BS_EINVAL;
+    if (regrouped) *regrouped = tm->regrouped;
+    if (packed) *packed = tm->packed;
+    if (intra_compact) *intra_compact = tm->intra_compact;
+    return BS_OK;
+}
+
+extern "C" int bs_tilemap_key_order(const bs_tilemap *tm, int32_t *keys, int32_t *n_prompt_tiles)
+{
+    if (!tm) return BS_EINVAL;
+    if (keys) std::memcpy(keys, tm->key_order.data(), tm->key_order.size() * sizeof(int32_t));
+    if (n_prompt_tiles) *n_prompt_tiles = tm->N0;
     return BS_OK;
 }
 

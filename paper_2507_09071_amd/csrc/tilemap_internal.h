@@ -61,6 +61,14 @@ void bs_plan_pairs(bs_tilemap *tm, int32_t gqa_group);
 
 struct bs_tilemap {
     int32_t L = 0, bm = 0, bn = 0, M = 0, N = 0, n_q_heads = 0, sink_len = 0;
+    // Key tiles: ids [0, N0) are the prompt's keys in position order; with packed keys, ids
+    // [N0, N) are compact tiles holding the free keys (text and sink keys) in position order.
+    int32_t N0 = 0;
+    bool packed = false;
+    bool intra_compact = false;            // packed: Intra-Image rows take their text keys from the compact tiles
+    std::vector<int32_t> key_order;        // N * bn: position of each key-tile slot, -1 = none
+    std::vector<int32_t> free_before;      // packed: L + 1, free keys at positions < t
+    std::vector<int32_t> span_free_range;  // packed: 2 * (G + 1), compact slots [lo, hi) of the free keys inside span g (1-based)
     std::vector<bs_span> spans;
     std::vector<uint8_t> head_class;
     std::vector<int32_t> row_order;        // M * bm: position of each query-tile row, -1 = no row

@@ -166,6 +166,44 @@ def test_regrouped_configs_sampled_rows(cfg):
                    flags=bs.BS_MAP_REGROUP_ROWS)
 
 
+# --- packed keys (BS_MAP_PACK_KEYS): compact tiles of text and sink keys for the sparse classes
+
+@pytest.mark.parametrize("d", [128, 64])
+def test_packed_small_prompt_all_classes(d):
+    p = W.custom_prompt(RUNS_A, [D, S, I, IS, IS, I, S, D], 4, d, dtype="bf16", sink_len=5,
+                        name=f"packed-d{d}", value_recipe={"std": 1.0, "first_key_scale": 4.0})
+    full_parity(p, seed=8, flags=bs.BS_MAP_PACK_KEYS)
+
+
+def test_packed_many_small_images():
+    runs = [("T", 3)]
+    for i in range(40):
+        runs += [("I", 40 + 7 * (i % 5)), ("T", 1 + (i % 3))]
+        if i % 7 == 3:
+            runs += [("I", 33)]          # two images without text between them
+    p = W.custom_prompt(runs, [S, I, IS, D, IS, S], 3, 128, dtype="bf16", sink_len=2, name="packed-many")
+    full_parity(p, seed=9, flags=bs.BS_MAP_PACK_KEYS)
+
+
+def test_packed_long_images_prefix_sinks():
+    p = W.custom_prompt([("T", 70), ("I", 900), ("T", 3), ("I", 1300), ("T", 40)], [IS, S, I, D], 2, 128,
+                        dtype="bf16", sink_len=37, sink_mode="prefix", name="packed-long")
+    full_parity(p, seed=10, flags=bs.BS_MAP_PACK_KEYS)
+
+
+def test_packed_fp32_is_rejected():
+    p = W.custom_prompt(RUNS_A, [D, S, I, IS], 2, 64, dtype="f32")
+    q, k, v = W.make_qkv(p, 1, DEV)
+    with pytest.raises(bs.BlindsightError):
+        run_prefill(p, q, k, v, flags=bs.BS_MAP_PACK_KEYS)
+
+
+@pytest.mark.parametrize("cfg", [2, 4])
+def test_packed_configs_sampled_rows(cfg):
+    sampled_parity(W.config(cfg), 0, n_random=3, max_tiles=10, row_step=[0, 0, 4, 16, 32][cfg],
+                   flags=bs.BS_MAP_PACK_KEYS)
+
+
 def test_config5_stress_72k_sampled_rows():
     sampled_parity(W.config(5, target_len=W.STRESS_LENGTHS[1]), 0, n_random=2, max_tiles=8, row_step=16)
 

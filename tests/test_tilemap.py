@@ -194,7 +194,114 @@ def test_regroup_flag_without_effect_and_bad_flags():
     for c in range(4):
         assert np.array_equal(a.tile_states(c), b.tile_states(c))
     with pytest.raises(bs.BlindsightError):
-        bs.bs_build_tilemap(spans, L, np.zeros(2, np.uint8), 0, flags=2)
+        bs.bs_build_tilemap(spans, L, np.zeros(2, np.uint8), 0, flags=4)
+
+
+# ------------------------------------------------------------------------- packed keys
+
+def packed_expectation(c, rows, keys, in_prompt_space, mask, imgid, packed=True, intra_compact=True):
+    """Allowed pairs of query rows x key slots of one tile of a packed map, from the oracle's
+    bitmap: text rows and Dense heads use the prompt's tiles with the plain predicate; an image
+    row of a sparse class counts own-image keys in the prompt's tiles and everything else it
+    may see in the compact tiles."""
+    i = rows[rows >= 0][:, None]
+    j = keys[keys >= 0][None, :]
+    if i.size == 0 or j.size == 0:
+        return np.zeros((i.shape[0], j.shape[1]), dtype=bool)
+    allowed = mask[i, j].astype(bool)
+    if not packed:
+        return allowed
+    plain = (imgid[i] == 0) | (c == 0) | (c == 2 and not intra_compact)
+    own = (imgid[i] == imgid[j]) & bool(c & 2)
+    if in_prompt_space:
+        return np.where(plain, allowed, allowed & own)
+    return np.where(plain, False, allowed & ~own)
+
+
+def check_packed(spans, L, sink_len, bm, bn):
+    tm = bs.bs_build_tilemap(spans, L, np.zeros(1, np.uint8), sink_len, bm, bn, flags=bs.BS_MAP_PACK_KEYS)
+    imgid, issink = oracle.token_arrays(spans, L, sink_len)
+    rows = tm.row_order(bm)
+    keys, n0 = tm.key_order(bn)
+    assert np.array_equal(keys[:n0].ravel()[:L], np.arange(L)) and (keys[:n0].ravel()[L:] < 0).all()
+    free = np.flatnonzero((imgid == 0) | (issink == 1))
+    packed = n0 < tm.n_k_tiles
+    lay = tm.layout()
+    assert lay["packed"] == packed and (lay["regrouped"] or not packed)
+    if packed:
+        comp = keys[n0:].ravel()
+        assert np.array_equal(comp[comp >= 0], free) and (comp[:len(free)] >= 0).all()
+    else:
+        assert len(free) in (0, L) or (imgid == 0).all()
+    for c in range(4):
+        mask = oracle.mask(c, imgid, issink)
+        got = tm.tile_states(c)
+        want = np.zeros_like(got)
+        for m in range(tm.n_q_tiles):
+            total = 0
+            for n in range(tm.n_k_tiles):
+                e = packed_expectation(c, rows[m], keys[n], n < n0, mask, imgid, packed, lay["intra_compact"])
+                cnt = int(e.sum())
+                total += cnt
+                want[m, n] = 0 if cnt == 0 else (2 if cnt == bm * bn else 1)
+            valid = rows[m][rows[m] >= 0]
+            assert total == int(mask[valid].sum()), (c, m)      # every allowed pair exactly once
+        assert np.array_equal(got, want), (c, np.argwhere(got != want)[:5], got[got != want][:5], want[got != want][:5])
+        assert tm.stats(c)["allowed_pairs"] == oracle.pair_count(c, imgid, issink)
+    return tm
+
+
+@pytest.mark.parametrize("seed", range(30))
+def test_packed_random_prompts_small_tiles(seed):
+    rng = np.random.default_rng(900 + seed)
+    runs = []
+    for _ in range(int(rng.integers(1, 8))):
+        runs.append(("T", int(rng.integers(0, 14))))
+        runs.append(("I", int(rng.integers(1, 40))))
+        if rng.random() < 0.3:
+            runs.append(("I", int(rng.integers(1, 20))))
+    runs.append(("T", int(rng.integers(0, 10))))
+    L, spans = W.layout_from_runs(runs, ["prefix", "paper10"][seed % 2], [None, None, 3, 1000][seed % 4])
+    if L == 0:
+        return
+    bm, bn = [(8, 4), (16, 8), (4, 4), (8, 16), (32, 16)][seed % 5]
+    check_packed(spans, L, int(rng.integers(0, min(L, 12) + 1)), bm, bn)
+
+
+@pytest.mark.parametrize("path", all_fixtures())
+def test_packed_golden_prompts(path):
+    L, spans, sink_len, _ = load(path)
+    check_packed(spans, L, sink_len, 4, 2)
+
+
+def test_packed_kernel_tile_size_and_plan():
+    runs = [("T", 30)]
+    for i in range(12):
+        runs += [("I", 150 + 37 * (i % 4)), ("T", 1 + 5 * (i % 3))]
+    L, spans = W.layout_from_runs(runs, "paper10")
+    tm = check_packed(spans, L, 9, 128, 64)
+    hc = np.array([0, 1, 2, 3, 3, 1], dtype=np.uint8)
+    tm2 = bs.bs_build_tilemap(spans, L, hc, 9, flags=bs.BS_MAP_PACK_KEYS)
+    tm2.pair_plan(2)
+    tm2.pair_plan(3)
+    reg = bs.bs_build_tilemap(spans, L, hc, 9, flags=bs.BS_MAP_REGROUP_ROWS)
+    for c in (1, 3):
+        assert tm2.stats(c)["visited"] <= reg.stats(c)["visited"]
+
+
+@pytest.mark.parametrize("cfg", [2, 4])
+def test_packed_large_configs_fewer_tiles(cfg):
+    p = W.config(cfg)
+    reg = bs.bs_build_tilemap(p.spans, p.seq_len, p.head_class, p.sink_len, flags=bs.BS_MAP_REGROUP_ROWS)
+    pk = bs.bs_build_tilemap(p.spans, p.seq_len, p.head_class, p.sink_len, flags=bs.BS_MAP_PACK_KEYS)
+    pk.pair_plan(p.gqa_group)
+    assert pk.stats(0) == reg.stats(0) or pk.stats(0)["visited"] == reg.stats(0)["visited"]
+    for c in (1, 2, 3):
+        if c == 2 and not pk.layout()["intra_compact"]:
+            assert pk.stats(c)["visited"] == reg.stats(c)["visited"]   # kept its plain lists
+        else:
+            assert pk.stats(c)["visited"] < reg.stats(c)["visited"]
+        assert pk.stats(c)["allowed_pairs"] == reg.stats(c)["allowed_pairs"]
 
 
 # ------------------------------------------------------------------------- work units (KV-sharing pairs)
