@@ -32,9 +32,10 @@ def parse_args():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=2, help="workload family 1..5 (default: the 36K one)")
     ap.add_argument("--target-len", type=int, default=None, help="config 5 prompt length")
-    ap.add_argument("--natural-order", action="store_true",
-                    help="build the tile map with query rows in position order (default: text rows "
-                         "regrouped into query tiles of their own, BS_MAP_REGROUP_ROWS)")
+    ap.add_argument("--map", choices=["packed", "regrouped", "natural"], default="packed",
+                    help="tile map layout: natural = query rows and keys in position order; regrouped = text "
+                         "rows in query tiles of their own (BS_MAP_REGROUP_ROWS); packed = that plus compact "
+                         "key tiles of text and sink keys for the sparse classes (BS_MAP_PACK_KEYS)")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--sink-mode", default="paper10", choices=["paper10", "prefix"])
     ap.add_argument("--all-dense", action="store_true", help="run the same prompt with every head Dense")
@@ -82,6 +83,7 @@ class HipEvents:
 MEASURED_TRAFFIC = {
     # profiles/attn_prefill_bf16_d128_cfg2_36k.md (measured where L2 meets the fabric: the 256 MB
     # memory-side cache sits behind that point); keyed by workload and row order of the tile map
+    ("cfg2-qwen2vl7b-36k/paper10/seed0", "packed"): 4.63e9,
     ("cfg2-qwen2vl7b-36k/paper10/seed0", "regrouped"): 4.46e9,
     ("cfg2-qwen2vl7b-36k/paper10/seed0", "natural"): 4.85e9,
 }
@@ -221,8 +223,8 @@ def main():
         torch.cuda.synchronize()
         del a, b
 
-    flags = 0 if args.natural_order else bs.BS_MAP_REGROUP_ROWS
-    order = "natural" if args.natural_order else "regrouped"
+    flags = {"natural": 0, "regrouped": bs.BS_MAP_REGROUP_ROWS, "packed": bs.BS_MAP_PACK_KEYS}[args.map]
+    order = args.map
     wall_ms, kern_ms, call_ms, build_ms, host_call_ms, tm = timed_steps(bs, torch, p, q, k, v, out, args.steps, args.warmup, hev, flags)
     tot, per_class = class_totals(tm, p.head_class)
     d = p.head_dim
@@ -260,7 +262,7 @@ def main():
         "dtype": p.dtype, "data": "synthetic",
         "config": {"workload": p.name, "seq_len": p.seq_len, "n_q_heads": p.n_q_heads,
                    "n_kv_heads": p.n_kv_heads, "head_dim": d, "n_images": int(len(p.spans)),
-                   "sink_mode": args.sink_mode, "seed": args.seed, "row_order": order,
+                   "sink_mode": args.sink_mode, "seed": args.seed, "map": order,
                    "head_classes": {n: int((p.head_class == c).sum()) for c, n in enumerate(W.CLASS_NAMES)}},
         "kernel_ms": round(kern_ms, 4),
         "device_ms_per_call": round(call_ms, 4),
