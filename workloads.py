@@ -272,3 +272,61 @@ def sample_q_tiles(p: Prompt, block_m: int = 128, n_random: int = 6, seed: int =
         idx = rng.choice(len(rest), size=max_tiles - 2, replace=False)
         picks = sorted(keep | {rest[i] for i in idx})
     return np.asarray(picks, dtype=np.int32)
+
+
+HEAD_KINDS = ("dense", "sink", "intra", "intra_sink")
+
+
+def make_planted_qkv(p: Prompt, head_kinds, seed: int = 0, boost: float = 30.0, noise: float = 0.5,
+                     device: str = "cpu"):
+    """Q/K/V in which each query head has a planted attention habit, as inputs for the offline
+    characterisation (Alg. 1): a test needs heads for which the sparse masks matter differently.
+
+    Keys: noise, plus a direction `s` on every sink key (prefix sink and image sinks) and a direction
+    `u_g` on the other keys of image g (the directions are orthonormal while images + 1 <= head_dim,
+    then reused cyclically).  Queries of head h, by head_kinds[h]:
+      "dense"       noise only (attention spread over every earlier key)
+      "sink"        + s on every row
+      "intra"       + u_g on the rows of image g
+      "intra_sink"  + s on every row and + u_g on the rows of image g
+    with lengths chosen so that a matching query/key pair scores `boost` logits above the rest.
+    V is N(0, 1).  Returns torch tensors of the prompt's dtype: q [Hq,L,d], k, v [Hkv,L,d].
+    """
+    import torch
+
+    kinds = list(head_kinds)
+    assert len(kinds) == p.n_q_heads and all(kd in HEAD_KINDS for kd in kinds)
+    L, d = p.seq_len, p.head_dim
+    dt = {"bf16": torch.bfloat16, "f32": torch.float32}[p.dtype]
+    rng = np.random.default_rng([4241, seed])
+    basis, _ = np.linalg.qr(rng.standard_normal((d, d)))
+    beta = math.sqrt(boost / p.scale)
+    img = np.zeros(L, dtype=np.int64)        # 0 text, g + 1 inside image g
+    sink = np.zeros(L, dtype=bool)
+    sink[:p.sink_len] = True
+    for g, (s0, e0, sk) in enumerate(np.asarray(p.spans).reshape(-1, 3)):
+        img[s0:e0] = g + 1
+        sink[s0:s0 + sk] = True
+    direction = np.zeros((L, d))
+    in_img = img > 0
+    direction[in_img] = basis[1 + (img[in_img] - 1) % (d - 1)]
+    s_dir = basis[0]
+    key_plant = np.where(sink[:, None], s_dir[None, :], direction) * beta
+    key_plant[~sink & ~in_img] = 0.0
+    g = torch.Generator(device="cpu")
+    g.manual_seed(1000003 * int(seed) + 4241)
+
+    def randn(h, std):
+        return torch.randn((h, L, d), generator=g, dtype=torch.float32) * std
+
+    k = randn(p.n_kv_heads, noise) + torch.from_numpy(key_plant).float()[None]
+    v = randn(p.n_kv_heads, 1.0)
+    q = randn(p.n_q_heads, noise)
+    s_t = torch.from_numpy(s_dir * beta).float()
+    u_t = torch.from_numpy(direction * beta).float()
+    for h, kd in enumerate(kinds):
+        if kd in ("sink", "intra_sink"):
+            q[h] += s_t[None, :]
+        if kd in ("intra", "intra_sink"):
+            q[h] += u_t
+    return q.to(dt).to(device), k.to(dt).to(device), v.to(dt).to(device)
