@@ -205,6 +205,57 @@ int bs_attn_prefill_ex(const void *q, const void *k, const void *v, void *out, b
                        int32_t dtype, int32_t n_q_heads, int32_t gqa_group, int32_t head_dim,
                        float scale, void *stream, void *ev_main_start, void *ev_main_stop);
 
+/*
+ * Offline characterisation, prompt level (paper Sec. 4.1, Alg. 1), for all query heads of one layer:
+ * the attention output under the dense causal mask is the reference; for the masks Sink,
+ * Intra-Image, Intra-Image+Sink, in this order,
+ *     NMSE = || Attn_mask - Attn_ref ||^2 / || Attn_ref ||^2      (over the head's [L, head_dim] output)
+ * and the head takes the first mask with NMSE < alpha (strictly), Dense if none passes.
+ *   q, k, v      device pointers, layouts as for bs_attn_prefill; spans / seq_len / sink_len as for
+ *                bs_build_tilemap (host)
+ *   alpha        the layer's threshold alpha_layer (the paper recommends 0.1 for Qwen-type models)
+ *   map_flags    options for the four tile maps the call builds (BS_MAP_*; dtype BS_F32 needs a map
+ *                without packed keys)
+ *   head_type    host, n_q_heads values out (bs_head_class)
+ *   nmse         host, [3][n_q_heads] out, row m = mask m + 1; may be NULL.  All three masks are
+ *                evaluated for every head (Alg. 1 stops at the first that passes, which only saves
+ *                work: the head types are the same).  A reference of norm zero gives 0 if the masked
+ *                output is zero as well, +inf otherwise.
+ * The four outputs come from bs_attn_prefill in `dtype` (bf16: the outputs are rounded to bf16 before
+ * they are compared, which puts a floor of about 1e-5 under the NMSE), the squared errors are
+ * accumulated in fp64 and the decision is taken in fp64.
+ * Allocates two output-sized device buffers for the duration of the call and returns after `stream`
+ * has drained (this is an offline routine).
+ * Errors: as bs_build_tilemap_ex and bs_attn_prefill; nothing is written to head_type / nmse on error.
+ */
+int bs_characterize_prompt(const void *q, const void *k, const void *v, const bs_span *spans,
+                           int32_t n_spans, int32_t seq_len, int32_t sink_len, int32_t dtype,
+                           int32_t n_q_heads, int32_t gqa_group, int32_t head_dim, float scale,
+                           double alpha, uint32_t map_flags, uint8_t *head_type, double *nmse,
+                           void *stream);
+
+/*
+ * The error measure of Alg. 1 on its own: for each of n_heads contiguous blocks of elems_per_head
+ * elements, sums[2*h] = sum (attn_mask - attn_ref)^2 and sums[2*h+1] = sum attn_ref^2.
+ *   attn_mask, attn_ref   device pointers, 16-byte aligned, dtype BS_BF16 or BS_F32
+ *   sums                  device pointer, 2 * n_heads doubles (cleared by the call)
+ * Enqueues on `stream` and does not wait.  The sums are accumulated in fp64; the order of the
+ * additions across workgroups is not fixed (fp64 atomics), so the last bits may differ between runs.
+ * Errors: BS_EINVAL; BS_EUNSUPPORTED (dtype, misaligned pointers, or several heads whose size in
+ * bytes is not a multiple of 16); BS_EHIP.
+ */
+int bs_head_sq_error(const void *attn_mask, const void *attn_ref, int32_t dtype, int32_t n_heads,
+                     int64_t elems_per_head, double *sums, void *stream);
+
+/*
+ * Offline characterisation, data-set level (paper Sec. 4.2, Alg. 2), for one head: fraction[c] is the
+ * share of characterised prompts on which Alg. 1 chose class c (host, 4 values).  Returns Dense if
+ * fraction[Dense] > gamma_d, else Sink if fraction[Sink] > gamma_s, else Intra-Image if
+ * fraction[Intra-Image] > gamma_i, else Intra-Image+Sink (paper defaults gamma_d = 0.25, gamma_s = 0.6;
+ * it names no value for gamma_i).  Host only.  Returns the class (0..3) or BS_EINVAL.
+ */
+int bs_aggregate_head_type(const double *fraction, double gamma_d, double gamma_s, double gamma_i);
+
 /* Static description of an error code. */
 const char *bs_strerror(int code);
 

@@ -18,7 +18,8 @@ BS_BF16, BS_F32 = 0, 1
 DENSE, SINK, INTRA, INTRA_SINK = 0, 1, 2, 3
 
 EXPORTS = ("bs_build_tilemap", "bs_build_tilemap_ex", "bs_tilemap_destroy", "bs_tilemap_dims", "bs_tilemap_row_order", "bs_tilemap_layout", "bs_tilemap_key_order", "bs_tilemap_tile_states",
-           "bs_tilemap_stats", "bs_tilemap_pair_plan", "bs_tilemap_upload", "bs_attn_prefill", "bs_attn_prefill_ex", "bs_strerror",
+           "bs_tilemap_stats", "bs_tilemap_pair_plan", "bs_tilemap_upload", "bs_attn_prefill", "bs_attn_prefill_ex",
+           "bs_characterize_prompt", "bs_head_sq_error", "bs_aggregate_head_type", "bs_strerror",
            "bs_last_error")
 
 
@@ -92,6 +93,14 @@ def load_library():
     lib.bs_attn_prefill.restype = ctypes.c_int
     lib.bs_attn_prefill_ex.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, ctypes.c_float, vp, vp, vp]
     lib.bs_attn_prefill_ex.restype = ctypes.c_int
+    f64, f64p = ctypes.c_double, ctypes.POINTER(ctypes.c_double)
+    lib.bs_characterize_prompt.argtypes = [vp, vp, vp, ctypes.POINTER(_Span), i32, i32, i32, i32, i32, i32, i32,
+                                           ctypes.c_float, f64, ctypes.c_uint32, u8p, f64p, vp]
+    lib.bs_characterize_prompt.restype = ctypes.c_int
+    lib.bs_head_sq_error.argtypes = [vp, vp, i32, i32, ctypes.c_int64, vp, vp]
+    lib.bs_head_sq_error.restype = ctypes.c_int
+    lib.bs_aggregate_head_type.argtypes = [f64p, f64, f64, f64]
+    lib.bs_aggregate_head_type.restype = ctypes.c_int
     lib.bs_strerror.argtypes = [ctypes.c_int]
     lib.bs_strerror.restype = ctypes.c_char_p
     lib.bs_last_error.argtypes = []
@@ -232,3 +241,41 @@ def bs_attn_prefill(q, k, v, out, tilemap: TileMap, dtype: int, n_q_heads: int, 
                                         int(dtype), int(n_q_heads), int(gqa_group), int(head_dim),
                                         float(scale), ctypes.c_void_p(int(stream) if stream else 0))
     _check(rc, "bs_attn_prefill")
+
+
+def bs_characterize_prompt(q, k, v, spans, seq_len: int, sink_len: int, dtype: int, n_q_heads: int,
+                           gqa_group: int, head_dim: int, scale: float, alpha: float, map_flags: int = 0,
+                           stream=None):
+    """Alg. 1 for every query head of one layer.  Returns (head_type uint8 [Hq], nmse float64 [3, Hq]);
+    waits for the stream."""
+    sp = np.ascontiguousarray(np.asarray(spans, dtype=np.int32).reshape(-1, 3))
+    sp_ptr = sp.ctypes.data_as(ctypes.POINTER(_Span)) if len(sp) else None
+    head_type = np.zeros(int(n_q_heads), dtype=np.uint8)
+    nmse = np.zeros((3, int(n_q_heads)), dtype=np.float64)
+    rc = load_library().bs_characterize_prompt(
+        _ptr(q), _ptr(k), _ptr(v), sp_ptr, len(sp), int(seq_len), int(sink_len), int(dtype), int(n_q_heads),
+        int(gqa_group), int(head_dim), float(scale), float(alpha), int(map_flags),
+        head_type.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8)),
+        nmse.ctypes.data_as(ctypes.POINTER(ctypes.c_double)), ctypes.c_void_p(int(stream) if stream else 0))
+    _check(rc, "bs_characterize_prompt")
+    return head_type, nmse
+
+
+def bs_head_sq_error(attn_mask, attn_ref, dtype: int, n_heads: int, elems_per_head: int, sums, stream=None) -> None:
+    """sums: device buffer of 2 * n_heads float64 (pointer or tensor).  Enqueues only."""
+    rc = load_library().bs_head_sq_error(_ptr(attn_mask), _ptr(attn_ref), int(dtype), int(n_heads),
+                                         int(elems_per_head), _ptr(sums),
+                                         ctypes.c_void_p(int(stream) if stream else 0))
+    _check(rc, "bs_head_sq_error")
+
+
+def bs_aggregate_head_type(fraction, gamma_d: float, gamma_s: float, gamma_i: float) -> int:
+    """Alg. 2 for one head: fraction = 4 shares (Dense, Sink, Intra-Image, Intra-Image+Sink)."""
+    f = np.ascontiguousarray(fraction, dtype=np.float64)
+    if f.shape != (4,):
+        raise ValueError("fraction must hold 4 values")
+    rc = load_library().bs_aggregate_head_type(f.ctypes.data_as(ctypes.POINTER(ctypes.c_double)),
+                                               float(gamma_d), float(gamma_s), float(gamma_i))
+    if rc < 0:
+        _check(rc, "bs_aggregate_head_type")
+    return rc

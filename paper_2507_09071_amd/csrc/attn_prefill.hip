@@ -33,14 +33,14 @@
 #include <type_traits>
 #include <vector>
 
+#include "hip_internal.h"
 #include "tilemap_internal.h"
 
 namespace bs {
 
-// Detail of the last failure on this thread, for bs_last_error().
 thread_local char g_last_error[256] = "";
 
-static int fail_hip(hipError_t e, const char *what)
+int fail_hip(hipError_t e, const char *what)
 {
     snprintf(g_last_error, sizeof g_last_error, "%s: %s (%d)", what, hipGetErrorString(e), (int)e);
     (void)hipGetLastError();

@@ -1,0 +1,212 @@
+"""Offline characterisation (paper Sec. 4, Alg. 1-2) through the C ABI: host logic on the CPU,
+parity of the GPU routine with oracle/characterize.py on the GPU."""
+import ctypes
+import itertools
+import math
+
+import numpy as np
+import pytest
+
+import oracle
+import paper_2507_09071_amd as bs
+import workloads as W
+from oracle import characterize as C
+from paper_2507_09071_amd import binding
+
+D, S, I, IS = 0, 1, 2, 3
+
+
+# ----------------------------------------------------------------------------- host logic (CPU)
+
+def test_aggregation_matches_oracle_on_a_grid_of_fractions():
+    grid = [0.0, 0.1, 0.25, 0.3, 0.4, 0.6, 0.7, 1.0]
+    n = 0
+    for fd, fs, fi in itertools.product(grid, repeat=3):
+        if fd + fs + fi > 1.0 + 1e-12:
+            continue
+        frac = [fd, fs, fi, max(0.0, 1.0 - fd - fs - fi)]
+        for gd, gs, gi in ((0.25, 0.6, 0.6), (0.1, 0.4, 0.3), (0.4, 0.8, 0.0)):
+            assert bs.bs_aggregate_head_type(frac, gd, gs, gi) == C.aggregate(frac, gd, gs, gi), (frac, gd, gs, gi)
+            n += 1
+    assert n > 300
+    assert binding.load_library().bs_aggregate_head_type(None, 0.25, 0.6, 0.6) == -1
+
+
+def test_characterize_rejects_bad_arguments_before_touching_the_device():
+    lib = binding.load_library()
+    one = ctypes.c_void_p(256)
+    ht = (ctypes.c_uint8 * 4)()
+    f = lambda *a: lib.bs_characterize_prompt(*a)
+    ok = (one, one, one, None, 0, 300, 0, 0, 4, 2, 128, 0.1, 0.1, 0, ht, None, None)
+    for pos, bad, want in ((0, None, -1), (1, None, -1), (2, None, -1), (14, None, -1), (5, 0, -1),
+                           (8, 0, -1), (10, 0, -1), (12, float("nan"), -1), (7, 5, -2)):
+        args = list(ok)
+        args[pos] = bad
+        assert f(*args) == want, pos
+    g = lambda *a: lib.bs_head_sq_error(*a)
+    assert g(None, one, 0, 1, 64, one, None) == -1
+    assert g(one, one, 0, 0, 64, one, None) == -1
+    assert g(one, one, 0, 1, 0, one, None) == -1
+    assert g(one, one, 0, 1, 64, None, None) == -1
+    assert g(one, one, 3, 1, 64, one, None) == -2
+    assert g(ctypes.c_void_p(260), one, 0, 1, 64, one, None) == -2   # 16-byte alignment
+    assert g(one, one, 0, 2, 67, one, None) == -2                    # heads would not stay aligned
+
+
+# ----------------------------------------------------------------------------- GPU parity
+
+def nmse_tolerance(nmse_oracle, out_rel_l2):
+    """If both outputs carry a relative-L2 error of at most eps against their exact values, then
+    sqrt(NMSE) moves by at most eps (2 + 2 sqrt(NMSE)) / (1 - eps): the difference a - r moves by
+    at most eps (|a| + |r|) <= eps |r| (2 + sqrt(NMSE)) and the normaliser |r| by a factor 1 +- eps."""
+    r = np.sqrt(nmse_oracle)
+    return out_rel_l2 * (2.0 + 2.0 * r) / (1.0 - out_rel_l2)
+
+
+def check_against_oracle(p, q, k, v, alpha, flags, out_rel_l2, cache=None):
+    import torch
+    dt = bs.BS_BF16 if q.dtype == torch.bfloat16 else bs.BS_F32
+    got_type, got = bs.bs_characterize_prompt(q, k, v, p.spans, p.seq_len, p.sink_len, dt, p.n_q_heads,
+                                              p.gqa_group, p.head_dim, p.scale, alpha, flags,
+                                              torch.cuda.current_stream().cuda_stream)
+    imgid, issink = oracle.token_arrays(p.spans, p.seq_len, p.sink_len)
+    to_np = lambda t: t.float().cpu().numpy()
+    # alpha = 0 makes the oracle evaluate every mask; its decision for `alpha` is re-derived below
+    if cache is not None and "want" in cache:
+        want = cache["want"]
+    else:
+        _, want = C.characterize_prompt(to_np(q), to_np(k), to_np(v), imgid, issink, p.scale, 0.0)
+        if cache is not None:
+            cache["want"] = want
+    want_type, _ = C.characterize_prompt(to_np(q), to_np(k), to_np(v), imgid, issink, p.scale, alpha)
+    tol = nmse_tolerance(want, out_rel_l2)
+    assert np.isfinite(got).all()
+    assert (np.abs(np.sqrt(got) - np.sqrt(want)) <= tol).all(), (got, want)
+    # a decision is compared where the threshold is further from the exact NMSE than the bound above;
+    # in between, either side of it is a valid outcome of the reduced-precision outputs
+    lo, hi = np.maximum(np.sqrt(want) - tol, 0.0) ** 2, (np.sqrt(want) + tol) ** 2
+    decided = ~((lo < alpha) & (alpha <= hi))
+    n_checked = 0
+    for h in range(p.n_q_heads):
+        m_pass = [m for m in range(3) if want[m, h] < alpha]
+        first = m_pass[0] if m_pass else 3
+        if decided[:min(first + 1, 3), h].all():
+            assert got_type[h] == want_type[h], (h, got[:, h], want[:, h])
+            n_checked += 1
+        else:
+            assert got_type[h] in (D, S, I, IS)
+        # the routine's own decision follows from its own numbers
+        own = [m + 1 for m in range(3) if got[m, h] < alpha]
+        assert got_type[h] == (own[0] if own else D)
+    return got_type, got, want_type, want, n_checked
+
+
+PLANTED_RUNS = [("T", 40), ("I", 300), ("T", 12), ("I", 260), ("T", 20), ("I", 333), ("T", 17)]
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("flags", [0, bs.BS_MAP_REGROUP_ROWS, bs.BS_MAP_PACK_KEYS])
+def test_planted_heads_bf16(flags):
+    kinds = ["dense", "sink", "intra", "intra_sink"] * 2
+    p = W.custom_prompt(PLANTED_RUNS, [0] * 8, 2, 64, dtype="bf16")
+    q, k, v = W.make_planted_qkv(p, kinds, seed=0, device="cuda")
+    got_type, _, want_type, _, n = check_against_oracle(p, q, k, v, 0.1, flags, 5e-3)
+    assert n == 8 and list(got_type) == [D, S, I, IS] * 2
+
+
+@pytest.mark.gpu
+def test_planted_heads_fp32():
+    kinds = ["intra_sink", "intra", "sink", "dense"]
+    p = W.custom_prompt(PLANTED_RUNS, [0] * 4, 2, 64, dtype="f32")
+    q, k, v = W.make_planted_qkv(p, kinds, seed=1, device="cuda")
+    got_type, got, _, want, n = check_against_oracle(p, q, k, v, 0.1, bs.BS_MAP_REGROUP_ROWS, 1e-5)
+    assert n == 4 and list(got_type) == [IS, I, S, D]
+
+
+@pytest.mark.gpu
+def test_grouped_heads_d128_several_tiles_and_ragged_tail():
+    """Eight heads on two KV heads at head_dim 128, a prompt of 25 query tiles with a ragged last
+    one, random values with the bench's outlier channels plus planted habits on half of the heads."""
+    rng = np.random.default_rng(5)
+    runs = [("T", 33)]
+    for _ in range(6):
+        runs += [("I", int(rng.integers(300, 700))), ("T", int(rng.integers(4, 40)))]
+    kinds = ["sink", "dense", "intra", "dense", "intra_sink", "intra", "dense", "sink"]
+    p = W.custom_prompt(runs, [0] * 8, 2, 128, dtype="bf16", sink_len=4)
+    assert p.seq_len % 128 != 0 and p.seq_len > 24 * 128
+    q, k, v = W.make_planted_qkv(p, kinds, seed=2, device="cuda")
+    cache = {}
+    for alpha in (0.1, 0.02):
+        _, _, _, _, n = check_against_oracle(p, q, k, v, alpha, bs.BS_MAP_PACK_KEYS, 5e-3, cache)
+        assert n >= 6
+
+
+@pytest.mark.gpu
+def test_threshold_extremes():
+    import torch
+    p = W.custom_prompt(PLANTED_RUNS, [0] * 4, 2, 64, dtype="bf16")
+    q, k, v = W.make_qkv(p, seed=3, device="cuda")
+    args = (q, k, v, p.spans, p.seq_len, p.sink_len, bs.BS_BF16, 4, 2, 64, p.scale)
+    ht, e = bs.bs_characterize_prompt(*args, 0.0, 0, torch.cuda.current_stream().cuda_stream)
+    assert list(ht) == [D] * 4 and (e > 0).all()
+    ht, e2 = bs.bs_characterize_prompt(*args, math.inf, 0, torch.cuda.current_stream().cuda_stream)
+    assert list(ht) == [S] * 4
+    assert np.allclose(e, e2, rtol=1e-12, atol=0)   # same outputs, sums differ at most in the last bits
+
+
+@pytest.mark.gpu
+def test_prompt_without_images_has_zero_error():
+    import torch
+    p = W.custom_prompt([("T", 700)], [0] * 2, 1, 128, dtype="bf16")
+    q, k, v = W.make_qkv(p, seed=4, device="cuda")
+    ht, e = bs.bs_characterize_prompt(q, k, v, p.spans, p.seq_len, 0, bs.BS_BF16, 2, 2, 128, p.scale, 1e-30,
+                                      bs.BS_MAP_PACK_KEYS, torch.cuda.current_stream().cuda_stream)
+    assert list(ht) == [S, S] and (e == 0.0).all()
+
+
+@pytest.mark.gpu
+@pytest.mark.parametrize("dtype,heads,n", [("bf16", 1, 100003), ("bf16", 5, 8 * 12345), ("f32", 1, 77777),
+                                            ("f32", 3, 4 * 25001), ("bf16", 2, 8)])
+def test_head_sq_error_against_fp64_sums(dtype, heads, n):
+    import torch
+    g = torch.Generator(device="cuda")
+    g.manual_seed(heads * 1000 + n)
+    dt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    ref = (torch.randn((heads, n), generator=g, device="cuda") * 3).to(dt)
+    cand = (ref.float() + torch.randn((heads, n), generator=g, device="cuda") * 0.3).to(dt)
+    sums = torch.full((heads, 2), float("nan"), dtype=torch.float64, device="cuda")
+    bs.bs_head_sq_error(cand, ref, bs.BS_BF16 if dtype == "bf16" else bs.BS_F32, heads, n, sums,
+                        torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    got = sums.cpu().numpy()
+    a, r = cand.float().cpu().numpy().astype(np.float64), ref.float().cpu().numpy().astype(np.float64)
+    for h in range(heads):
+        want_nmse = C.nmse(a[h], r[h])
+        assert got[h, 0] / got[h, 1] == pytest.approx(want_nmse, rel=1e-12)
+        assert got[h, 1] == pytest.approx(float((r[h] ** 2).sum()), rel=1e-12)
+
+
+@pytest.mark.gpu
+def test_full_size_constant_values_give_the_share_of_empty_rows():
+    """Bench-sized prompt (28/4 heads, d 128, about 37K tokens, packed map) that begins with an image
+    and has no sink keys: with one value vector on every key, an output row is that vector unless its
+    mask is empty, so NMSE(Sink) = rows of the first image / L and the other two masks have none."""
+    import torch
+    rng = np.random.default_rng(8)
+    runs = []
+    for _ in range(16):
+        runs += [("I", int(rng.integers(1024, 3600))), ("T", int(rng.integers(8, 64)))]
+    p = W.custom_prompt(runs, [0] * 28, 4, 128, dtype="bf16", span_sink=0)
+    q, k, _ = W.make_qkv(p, seed=6, device="cuda")
+    g = torch.Generator(device="cuda")
+    g.manual_seed(99)
+    v = torch.randn((4, 1, 128), generator=g, device="cuda").to(torch.bfloat16).expand(4, p.seq_len, 128).contiguous()
+    first_image = int(p.spans[0][1] - p.spans[0][0])
+    share = first_image / p.seq_len
+    assert 0.02 < share < 0.2
+    ht, e = bs.bs_characterize_prompt(q, k, v, p.spans, p.seq_len, 0, bs.BS_BF16, 28, 7, 128, p.scale, share / 2,
+                                      bs.BS_MAP_PACK_KEYS, torch.cuda.current_stream().cuda_stream)
+    tol = nmse_tolerance(np.array([share, 0.0, 0.0]), 5e-3)
+    assert (np.abs(np.sqrt(e[0]) - math.sqrt(share)) <= tol[0]).all(), e[0]
+    assert (np.sqrt(e[1]) <= tol[1]).all() and (np.sqrt(e[2]) <= tol[2]).all(), e[1:]
+    assert list(ht) == [I] * 28                    # Sink fails by a factor 2, Intra-Image passes
