@@ -42,6 +42,11 @@ def parse_args():
     ap.add_argument("--no-dense-leg", action="store_true", help="skip the all-Dense comparison run")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=40.0, help="target CPU time of the oracle sample")
+    ap.add_argument("--characterize", action="store_true",
+                    help="time the offline prompt-level characterisation (Alg. 1: the kernel under the dense "
+                         "mask and the three sparse masks for every head + error reduction) instead of the "
+                         "prefill step; prints its own JSON line")
+    ap.add_argument("--alpha", type=float, default=0.1, help="NMSE threshold of --characterize")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one 1 GiB device-to-device copy (a kernel of known HBM traffic, "
                          "used to scale rocprofv3 FETCH_SIZE / WRITE_SIZE readings)")
@@ -144,12 +149,31 @@ def timed_steps(bs, torch, p, q, k, v, out, steps, warmup, hev, flags):
     return wall * 1e3, kern_ms, call_ms, 1e3 * sum(build_s) / len(build_s), 1e3 * sum(call_s) / len(call_s), keep[-1]
 
 
+def sampled_pairs(head_class, rows, imgid, issink):
+    """Allowed pairs of the given query rows summed over the heads (plain enumeration)."""
+    per_class_row = {}
+    for c in set(int(x) for x in head_class):
+        cnt = 0
+        for i in rows:
+            i = int(i)
+            if imgid[i] == 0 or c == 0:
+                cnt += i + 1
+            else:
+                ok = imgid[: i + 1] == 0
+                if c & 1:
+                    ok |= issink[: i + 1] == 1
+                if c & 2:
+                    ok |= imgid[: i + 1] == imgid[i]
+                cnt += int(ok.sum())
+        per_class_row[c] = cnt
+    return sum(per_class_row[int(c)] for c in head_class)
+
+
 def cpu_baseline(p, q, k, v, target_seconds):
     """Time the oracle as it stands on a bounded sample of rows of this workload."""
     import numpy as np
 
     import oracle
-    import workloads as W
 
     imgid, issink = oracle.token_arrays(p.spans, p.seq_len, p.sink_len)
     qn, kn, vn = (t.float().cpu().numpy() for t in (q, k, v))
@@ -167,30 +191,100 @@ def cpu_baseline(p, q, k, v, target_seconds):
     oracle.attention(qn, kn, vn, p.head_class, imgid, issink, p.scale, rows)
     t = time.perf_counter() - t0
     # allowed pairs of the sampled rows, summed over heads (enumeration, outside the timed part)
-    pairs = 0
-    per_class_row = {}
-    for c in set(int(x) for x in p.head_class):
-        cnt = 0
-        for i in rows:
-            i = int(i)
-            if imgid[i] == 0 or c == 0:
-                cnt += i + 1
-            else:
-                text = imgid[: i + 1] == 0
-                ok = text.copy()
-                if c & 1:
-                    ok |= issink[: i + 1] == 1
-                if c & 2:
-                    ok |= imgid[: i + 1] == imgid[i]
-                cnt += int(ok.sum())
-        per_class_row[c] = cnt
-    for c in p.head_class:
-        pairs += per_class_row[int(c)]
+    pairs = sampled_pairs(p.head_class, rows, imgid, issink)
     flops = 4.0 * p.head_dim * pairs
     return {"value": flops / t / 1e12, "unit": "TFLOP/s (useful, fp64 oracle)", "cores": oracle.num_threads(),
             "kind": "oracle", "seconds": round(t, 2),
             "sample": f"{n_rows} random query rows x all {p.n_q_heads} heads of the same prompt "
                       f"({pairs} unmasked pairs)"}
+
+
+def characterize_bench(args, bs, torch, p, q, k, v, flags):
+    """Alg. 1 on the GPU for all heads of one layer of the workload; one step = one whole call
+    (four tile maps, four attention launches, three error reductions, decision, read-back)."""
+    import numpy as np
+
+    dt = bs.BS_BF16 if p.dtype == "bf16" else bs.BS_F32
+    st = torch.cuda.current_stream().cuda_stream
+    call = lambda: bs.bs_characterize_prompt(q, k, v, p.spans, p.seq_len, p.sink_len, dt, p.n_q_heads, p.gqa_group,
+                                              p.head_dim, p.scale, args.alpha, flags, st)
+    for _ in range(args.warmup):
+        call()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        head_type, nmse = call()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) / args.steps * 1e3
+    # the error reduction alone: reads two outputs once
+    a, b = torch.randn_like(q), torch.randn_like(q)
+    sums = torch.empty((p.n_q_heads, 2), dtype=torch.float64, device=q.device)
+    n = p.seq_len * p.head_dim
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    for i in range(args.warmup + args.steps):
+        j = i - args.warmup
+        if j >= 0:
+            ev[j][0].record()
+        bs.bs_head_sq_error(a, b, dt, p.n_q_heads, n, sums, st)
+        if j >= 0:
+            ev[j][1].record()
+    torch.cuda.synchronize()
+    red_ms = sum(x.elapsed_time(y) for x, y in ev) / len(ev)   # includes the 1-workgroup clearing kernel
+    red_bytes = 2 * p.n_q_heads * n * (2 if p.dtype == "bf16" else 4)
+    # attention work of the four runs
+    pairs = []
+    for c in range(4):
+        tm = bs.bs_build_tilemap(p.spans, p.seq_len, np.full(p.n_q_heads, c, np.uint8), p.sink_len, 128, 64, flags=flags)
+        pairs.append(tm.stats(c)["allowed_pairs"] * p.n_q_heads)
+    flop = 4.0 * p.head_dim * sum(pairs)
+    res = {
+        "metric": "prompt-level characterisation (Alg. 1), all heads of one layer",
+        "value": round(ms, 4), "unit": "ms per prompt and layer (host wall clock, call returns results)",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 4),
+        "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": p.dtype, "data": "synthetic",
+        "config": {"workload": p.name, "seq_len": p.seq_len, "n_q_heads": p.n_q_heads, "n_kv_heads": p.n_kv_heads,
+                   "head_dim": p.head_dim, "n_images": int(len(p.spans)), "map": args.map, "alpha": args.alpha,
+                   "values": "random (bench tensors): every sparse mask is expected to fail"},
+        "head_types": {nm: int((head_type == c).sum()) for c, nm in enumerate(("dense", "sink", "intra", "intra_sink"))},
+        "nmse_median_per_mask": [float(np.median(nmse[m])) for m in range(3)],
+        "useful_tflops_whole_call": round(flop / (ms * 1e-3) / 1e12, 2),
+        "unmasked_pairs_per_mask": pairs,
+        "roofline": {"bound": "hbm", "kernel": "head_sq_error<%s>" % p.dtype, "achieved": round(red_bytes / (red_ms * 1e-3) / 1e9, 1),
+                     "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": round(red_bytes / (red_ms * 1e-3) / 1e9 / PEAK_HBM_GBS, 4),
+                     "traffic": None, "bytes_per_launch": red_bytes, "avg_launch_ms": round(red_ms, 4)},
+    }
+    if not args.no_cpu_baseline:
+        res["cpu_baseline"] = characterize_cpu_baseline(p, q, k, v, pairs, args.cpu_seconds)
+    print(json.dumps(res))
+
+
+def characterize_cpu_baseline(p, q, k, v, pairs_per_mask, target_seconds):
+    """The oracle's attention under the four masks on a sample of rows, extrapolated to the prompt."""
+    import numpy as np
+
+    import oracle
+
+    imgid, issink = oracle.token_arrays(p.spans, p.seq_len, p.sink_len)
+    qn, kn, vn = (t.float().cpu().numpy() for t in (q, k, v))
+    rng = np.random.default_rng(321)
+    n_rows = 4
+    total, spent, done = 0.0, 0.0, 0
+    for attempt in range(2):
+        rows = np.sort(rng.choice(p.seq_len, size=n_rows, replace=False)).astype(np.int32)
+        total, spent = 0.0, 0.0
+        for c in range(4):
+            hc = np.full(p.n_q_heads, c, np.uint8)
+            t0 = time.perf_counter()
+            oracle.attention(qn, kn, vn, hc, imgid, issink, p.scale, rows)
+            t = time.perf_counter() - t0
+            spent += t
+            total += t * pairs_per_mask[c] / max(1, sampled_pairs(hc, rows, imgid, issink))
+        done = n_rows
+        if attempt == 0:
+            n_rows = int(max(4, min(p.seq_len, n_rows * target_seconds / max(spent, 1e-3))))
+    return {"value": round(total * 1e3, 1), "unit": "ms per prompt and layer (extrapolated, attention of the four masks only)",
+            "cores": oracle.num_threads(), "kind": "oracle", "seconds": round(spent, 2),
+            "sample": f"{done} random query rows x all {p.n_q_heads} heads x 4 masks, scaled by unmasked pairs"}
 
 
 def main():
@@ -225,6 +319,10 @@ def main():
 
     flags = {"natural": 0, "regrouped": bs.BS_MAP_REGROUP_ROWS, "packed": bs.BS_MAP_PACK_KEYS}[args.map]
     order = args.map
+    if args.characterize:
+        del out
+        characterize_bench(args, bs, torch, p, q, k, v, flags)
+        return
     wall_ms, kern_ms, call_ms, build_ms, host_call_ms, tm = timed_steps(bs, torch, p, q, k, v, out, args.steps, args.warmup, hev, flags)
     tot, per_class = class_totals(tm, p.head_class)
     d = p.head_dim

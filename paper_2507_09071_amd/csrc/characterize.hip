@@ -59,6 +59,7 @@ __global__ __launch_bounds__(kNmseThreads) void head_sq_error(const T *__restric
     const int64_t v0 = (int64_t)blockIdx.x * per_chunk;
     const int64_t v1 = v0 + per_chunk < n_vec ? v0 + per_chunk : n_vec;
     double err = 0.0, ref = 0.0;
+#pragma unroll 4
     for (int64_t i = v0 + threadIdx.x; i < v1; i += kNmseThreads) {
         const uint4 ra = reinterpret_cast<const uint4 *>(ah)[i];
         const uint4 rr = reinterpret_cast<const uint4 *>(rh)[i];
