@@ -17,6 +17,11 @@
  *   - imgid[t] = 0 for text, g >= 1 for a token of image g; isimgsink marks the
  *     sink tokens                                                                [App. kernel, Notation]
  *   - the sink of an image is a prefix of that image                             [Sec. 6.1, mask generation]
+ *   - model variant with non-causal attention inside an image (Gemma 3): the dense mask is the
+ *     model's default mask [Sec. 2], here causal OR "query and key in the same image", and every
+ *     sparse mask is its class pattern restricted to that dense mask; the sinks of such a model
+ *     sit at a fixed list of offsets inside every image       [Sec. 6.1, App. "Attention Sink
+ *     Positions in Gemma 3"].  Selected by img_bidir != 0 / a sink offset list.
  *
  * Readings taken where the paper's pseudo-code is loose (Alg. 3-7):
  *   - the running sum l divides the output once at the end (the SoftMax of Sec. 3.1);
@@ -39,9 +44,11 @@ enum { BSO_DENSE = 0, BSO_SINK = 1, BSO_INTRA = 2, BSO_INTRA_SINK = 3 };
 /* spans: n_spans rows of (start, end, sink).  Fills imgid[L] and issink[L].
  * Returns 0, or a negative code naming the first violated rule. */
 int bso_token_arrays(const int32_t *spans, int32_t n_spans, int32_t L, int32_t sink_len,
-                     int32_t *imgid, uint8_t *issink)
+                     const int32_t *sink_offsets, int32_t n_offsets, int32_t *imgid, uint8_t *issink)
 {
-    if (L < 0 || n_spans < 0 || sink_len < 0 || sink_len > L) return -1;
+    if (L < 0 || n_spans < 0 || sink_len < 0 || sink_len > L || n_offsets < 0) return -1;
+    for (int32_t o = 0; o < n_offsets; ++o)
+        if (sink_offsets[o] < 0) return -4;
     int32_t prev_end = 0;
     for (int32_t g = 0; g < n_spans; ++g) {
         int32_t s = spans[3 * g], e = spans[3 * g + 1], k = spans[3 * g + 2];
@@ -59,14 +66,18 @@ int bso_token_arrays(const int32_t *spans, int32_t n_spans, int32_t L, int32_t s
             imgid[t] = g + 1;
             if (t - s < k) issink[t] = 1;
         }
+        /* sinks at fixed offsets inside every image (offsets past the image's end are ignored) */
+        for (int32_t o = 0; o < n_offsets; ++o)
+            if (sink_offsets[o] < e - s) issink[s + sink_offsets[o]] = 1;
     }
     return 0;
 }
 
-/* May query i attend to key j in a head of class cls?  [Sec. 3.2] */
-int bso_allowed(int cls, int32_t i, int32_t j, const int32_t *imgid, const uint8_t *issink)
+/* May query i attend to key j in a head of class cls?  [Sec. 3.2]
+ * img_bidir: tokens of one image also see the later tokens of that image (the model's dense mask). */
+int bso_allowed(int cls, int32_t i, int32_t j, const int32_t *imgid, const uint8_t *issink, int img_bidir)
 {
-    if (j > i) return 0;                 /* causal prefill mask */
+    if (j > i && !(img_bidir && imgid[i] != 0 && imgid[j] == imgid[i])) return 0;  /* the dense mask */
     if (imgid[i] == 0) return 1;         /* text queries see all earlier tokens */
     if (cls == BSO_DENSE) return 1;
     if (imgid[j] == 0) return 1;         /* text keys stay visible: the vertical bands */
@@ -76,21 +87,21 @@ int bso_allowed(int cls, int32_t i, int32_t j, const int32_t *imgid, const uint8
 }
 
 /* Dense L x L bitmap (row-major, 1 = allowed).  Small prompts only. */
-void bso_mask(int cls, int32_t L, const int32_t *imgid, const uint8_t *issink, uint8_t *mask)
+void bso_mask(int cls, int32_t L, const int32_t *imgid, const uint8_t *issink, int img_bidir, uint8_t *mask)
 {
     for (int32_t i = 0; i < L; ++i)
         for (int32_t j = 0; j < L; ++j)
-            mask[(size_t)i * L + j] = (uint8_t)bso_allowed(cls, i, j, imgid, issink);
+            mask[(size_t)i * L + j] = (uint8_t)bso_allowed(cls, i, j, imgid, issink, img_bidir);
 }
 
 /* Number of allowed (i, j) pairs, by enumeration. */
-int64_t bso_pair_count(int cls, int32_t L, const int32_t *imgid, const uint8_t *issink)
+int64_t bso_pair_count(int cls, int32_t L, const int32_t *imgid, const uint8_t *issink, int img_bidir)
 {
     int64_t total = 0;
 #pragma omp parallel for schedule(dynamic, 64) reduction(+ : total)
     for (int32_t i = 0; i < L; ++i) {
         int64_t c = 0;
-        for (int32_t j = 0; j <= i; ++j) c += bso_allowed(cls, i, j, imgid, issink);
+        for (int32_t j = 0; j < L; ++j) c += bso_allowed(cls, i, j, imgid, issink, img_bidir);
         total += c;
     }
     return total;
@@ -100,7 +111,7 @@ int64_t bso_pair_count(int cls, int32_t L, const int32_t *imgid, const uint8_t *
  * Tile (m, n) covers rows [m*bm, m*bm+bm) x keys [n*bn, n*bn+bn); indices >= L count as
  * not allowed.  state: 0 = no element allowed, 2 = all bm*bn allowed, 1 = otherwise.
  * states is [n_qtiles][N], N = ceil(L / bn). */
-void bso_tile_states(int cls, int32_t L, const int32_t *imgid, const uint8_t *issink,
+void bso_tile_states(int cls, int32_t L, const int32_t *imgid, const uint8_t *issink, int img_bidir,
                      int32_t bm, int32_t bn, const int32_t *qtiles, int32_t n_qtiles,
                      uint8_t *states)
 {
@@ -114,7 +125,7 @@ void bso_tile_states(int cls, int32_t L, const int32_t *imgid, const uint8_t *is
                 if (i >= L) continue;
                 for (int32_t j = n * bn; j < n * bn + bn; ++j) {
                     if (j >= L) continue;
-                    cnt += bso_allowed(cls, i, j, imgid, issink);
+                    cnt += bso_allowed(cls, i, j, imgid, issink, img_bidir);
                 }
             }
             states[(size_t)t * N + n] = (uint8_t)(cnt == 0 ? 0 : (cnt == (int64_t)bm * bn ? 2 : 1));
@@ -125,7 +136,7 @@ void bso_tile_states(int cls, int32_t L, const int32_t *imgid, const uint8_t *is
 /* The same reduction for query tiles given as explicit row lists (a tile map may group the
  * query rows in another order than their positions): rows is [n_qtiles][bm], entries < 0 or
  * >= L are slots without a row and count as not allowed, like positions past the end above. */
-void bso_tile_states_rows(int cls, int32_t L, const int32_t *imgid, const uint8_t *issink,
+void bso_tile_states_rows(int cls, int32_t L, const int32_t *imgid, const uint8_t *issink, int img_bidir,
                           int32_t bm, int32_t bn, const int32_t *rows, int32_t n_qtiles,
                           uint8_t *states)
 {
@@ -139,7 +150,7 @@ void bso_tile_states_rows(int cls, int32_t L, const int32_t *imgid, const uint8_
                 if (i < 0 || i >= L) continue;
                 for (int32_t j = n * bn; j < n * bn + bn; ++j) {
                     if (j >= L) continue;
-                    cnt += bso_allowed(cls, i, j, imgid, issink);
+                    cnt += bso_allowed(cls, i, j, imgid, issink, img_bidir);
                 }
             }
             states[(size_t)t * N + n] = (uint8_t)(cnt == 0 ? 0 : (cnt == (int64_t)bm * bn ? 2 : 1));
@@ -155,7 +166,7 @@ void bso_tile_states_rows(int cls, int32_t L, const int32_t *imgid, const uint8_
  * out = sum_j exp(x_j - m) v_j / sum_j exp(x_j - m).  Empty allowed set -> zeros. */
 int bso_attention(const float *q, const float *k, const float *v, int32_t Hq, int32_t G,
                   int32_t L, int32_t d, const uint8_t *head_class, const int32_t *imgid,
-                  const uint8_t *issink, double scale, const int32_t *rows, int32_t n_rows,
+                  const uint8_t *issink, int img_bidir, double scale, const int32_t *rows, int32_t n_rows,
                   double *out)
 {
     if (Hq <= 0 || G <= 0 || Hq % G || L <= 0 || d <= 0) return -1;
@@ -185,8 +196,8 @@ int bso_attention(const float *q, const float *k, const float *v, int32_t Hq, in
                 for (int32_t c = 0; c < d; ++c) { qi[c] = (double)qrow[c]; o[c] = 0.0; }
 
                 double mx = -INFINITY;
-                for (int32_t j = 0; j <= i; ++j) {
-                    if (!bso_allowed(cls, i, j, imgid, issink)) continue;
+                for (int32_t j = 0; j < L; ++j) {
+                    if (!bso_allowed(cls, i, j, imgid, issink, img_bidir)) continue;
                     const float *kj = kh + (size_t)j * d;
                     double acc = 0.0;
 #pragma omp simd reduction(+ : acc)
@@ -196,8 +207,8 @@ int bso_attention(const float *q, const float *k, const float *v, int32_t Hq, in
                 }
                 if (mx == -INFINITY) continue; /* empty allowed set: zeros */
                 double denom = 0.0;
-                for (int32_t j = 0; j <= i; ++j) {
-                    if (!bso_allowed(cls, i, j, imgid, issink)) continue;
+                for (int32_t j = 0; j < L; ++j) {
+                    if (!bso_allowed(cls, i, j, imgid, issink, img_bidir)) continue;
                     double p = exp(x[j] - mx);
                     denom += p;
                     const float *vj = vh + (size_t)j * d;

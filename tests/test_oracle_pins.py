@@ -11,7 +11,7 @@ import torch
 
 import oracle
 import workloads as W
-from golden_masks import all_fixtures, load
+from golden_masks import all_fixtures, full_fixtures, load, load_full
 
 D, S, I, IS = 0, 1, 2, 3
 
@@ -397,3 +397,73 @@ def test_tile_size_independence(bm, bn):
         m = oracle.mask(int(c), imgid, issink)
         want = tiled_online_softmax(q[h], k[h // 2], v[h // 2], m, p.scale, bm, bn)
         assert np.abs(got[h] - want).max() < 1e-12
+
+
+# ----------------------------------------------------------------------------- non-causal images, offset sinks
+
+@pytest.mark.parametrize("path", full_fixtures())
+def test_bidirectional_and_offset_sink_masks_match_hand_derived_bitmaps(path):
+    L, spans, sink_len, offsets, bidir, expected = load_full(path)
+    imgid, issink = oracle.token_arrays(spans, L, sink_len, offsets)
+    assert len(expected) == 4
+    for cls, want in expected.items():
+        got = oracle.mask(cls, imgid, issink, bidir)
+        assert np.array_equal(got, want), f"{path} class {cls}\n{got}\n{want}"
+
+
+def test_offset_sinks_match_numpy_construction():
+    spans = np.array([(3, 20, 2), (20, 27, 0), (40, 90, 5)], dtype=np.int32)
+    offsets = [0, 6, 9, 30, 49, 200]
+    imgid, issink = oracle.token_arrays(spans, 100, 1, offsets)
+    want_id, want_sink = np_token_arrays(spans, 100, 1)
+    for s, e, _ in spans:
+        for o in offsets:
+            if o < e - s:
+                want_sink[s + o] = 1
+    assert np.array_equal(imgid, want_id) and np.array_equal(issink, want_sink)
+    assert issink[26] == 1 and issink[29] == 0 and issink[89] == 1   # offset 6 of image 2; 9 is past its end
+    with pytest.raises(ValueError):
+        oracle.token_arrays(spans, 100, 1, [-1])
+
+
+def test_bidirectional_mask_is_the_causal_mask_plus_later_keys_of_the_own_image():
+    """The dense mask gains exactly the pairs (i, j > i) inside one image; a sparse class keeps of
+    them what its pattern allows: own-image keys for the intra classes, sink keys for Sink."""
+    for seed in range(6):
+        p = small_prompt(seed)
+        imgid, issink = oracle.token_arrays(p.spans, p.seq_len, p.sink_len, [1, 5, 17])
+        L = p.seq_len
+        ii, jj = np.meshgrid(np.arange(L), np.arange(L), indexing="ij")
+        later_own = (jj > ii) & (imgid[ii] == imgid[jj]) & (imgid[ii] > 0)
+        for cls in (D, S, I, IS):
+            causal = oracle.mask(cls, imgid, issink, False).astype(bool)
+            bidir = oracle.mask(cls, imgid, issink, True).astype(bool)
+            extra = later_own & (issink[jj] == 1) if cls == S else later_own
+            assert np.array_equal(bidir, causal | extra), (seed, cls)
+            assert oracle.pair_count(cls, imgid, issink, True) == int((causal | extra).sum())
+        # closed form for the dense mask: the lower triangle plus len (len - 1) / 2 per image
+        lens = p.spans[:, 1] - p.spans[:, 0]
+        assert oracle.pair_count(D, imgid, issink, True) == L * (L + 1) // 2 + int((lens * (lens - 1) // 2).sum())
+
+
+def test_bidirectional_attention_equals_library_attention_with_explicit_mask():
+    p = W.custom_prompt([("T", 5), ("I", 90), ("T", 3), ("I", 120), ("I", 40), ("T", 9)],
+                        [D, S, I, IS, IS, I, S, D], 4, 24, dtype="f32", sink_len=2, scale=0.4,
+                        img_bidir=True, sink_offsets=(0, 7, 33, 100))
+    q, k, v = (t.numpy() for t in W.make_qkv(p, 1))
+    imgid, issink = oracle.token_arrays(p.spans, p.seq_len, p.sink_len, p.sink_offsets)
+    got = oracle.attention_for_prompt(p, q, k, v)
+    L = p.seq_len
+    # the model's own dense mask, written out: lower triangle OR same-image block
+    block = (imgid[:, None] == imgid[None, :]) & (imgid[:, None] > 0)
+    dense = np.tril(np.ones((L, L), dtype=bool)) | block
+    want = sdpa_fp64(q[0:1], k[0:1], v[0:1], 1, p.scale, dense[None])
+    assert np.abs(got[0] - want[0]).max() < 1e-12
+    for h, c in enumerate(p.head_class):
+        m = oracle.mask(int(c), imgid, issink, True)
+        want = sdpa_fp64(q[h:h + 1], k[h // 2:h // 2 + 1], v[h // 2:h // 2 + 1], 1, p.scale, m[None])
+        assert np.abs(got[h] - want[0]).max() < 1e-12, h
+    # and a row subset goes through the same loop
+    rows = np.array([0, 5, 6, 94, 95, 100, 217, L - 1], dtype=np.int32)
+    sub = oracle.attention_for_prompt(p, q, k, v, rows)
+    assert np.array_equal(sub, got[:, rows])
