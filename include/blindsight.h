@@ -103,9 +103,32 @@ int bs_build_tilemap(const bs_span *spans, int32_t n_spans, int32_t seq_len,
  *       of every tile slot.  bf16 only (the fp32 kernel returns BS_EUNSUPPORTED for such a map).
  *       No effect on a prompt without images, without free keys, or made of free keys only. */
 #define BS_MAP_PACK_KEYS 2u
+/*   BS_MAP_BIDIR_IMAGES   model variant in which the tokens of one image attend to each other in
+ *       both directions (Gemma 3; paper Sec. 2: the dense mask is the model's default mask, Sec. 6.1:
+ *       "non-causal attention mechanism within an image").  The causal condition j <= i of the pair
+ *       rule above becomes "j <= i, or i and j belong to the same image", for every class: a sparse
+ *       mask is its class pattern inside the model's dense mask.  An image query then sees exactly
+ *       what the last query of its image sees under the causal rule, which is how the map and the
+ *       kernels treat it.  Text queries are unchanged.  Combines with the other flags. */
+#define BS_MAP_BIDIR_IMAGES 4u
 int bs_build_tilemap_ex(const bs_span *spans, int32_t n_spans, int32_t seq_len,
                         const uint8_t *head_class, int32_t n_q_heads, int32_t sink_len,
                         int32_t block_m, int32_t block_n, uint32_t flags, bs_tilemap **out);
+
+/*
+ * Same, for models whose image sinks are not a prefix of the image: sink_offsets (host, n_sink_offsets
+ * values >= 0, may be NULL when the count is 0) lists offsets inside an image; the token at
+ * start + offset of EVERY image is a sink key as well (offsets at or past an image's length are ignored
+ * for that image), in addition to the spans' `sink` prefixes and the sink_len prefix of the prompt.
+ * Paper Sec. 6.1 and App. "Attention Sink Positions in Gemma 3": that model tokenises every image to
+ * the same length and its sinks sit at fixed locations inside every image (the paper keeps the 10 % most
+ * frequent locations found on its characterisation set; the list itself is the caller's input).
+ * Errors: as bs_build_tilemap_ex; BS_EINVAL for a negative offset or count.
+ */
+int bs_build_tilemap_model(const bs_span *spans, int32_t n_spans, int32_t seq_len,
+                           const uint8_t *head_class, int32_t n_q_heads, int32_t sink_len,
+                           int32_t block_m, int32_t block_n, uint32_t flags,
+                           const int32_t *sink_offsets, int32_t n_sink_offsets, bs_tilemap **out);
 
 /* Frees the host arrays; device buffers (if any) go back to a per-process cache of the library
  * and are handed to a later map only after the work queued with this map has finished (the
@@ -215,7 +238,7 @@ int bs_attn_prefill_ex(const void *q, const void *k, const void *v, void *out, b
  *                bs_build_tilemap (host)
  *   alpha        the layer's threshold alpha_layer (the paper recommends 0.1 for Qwen-type models)
  *   map_flags    options for the four tile maps the call builds (BS_MAP_*; dtype BS_F32 needs a map
- *                without packed keys)
+ *                without packed keys); sink_offsets / n_sink_offsets as for bs_build_tilemap_model
  *   head_type    host, n_q_heads values out (bs_head_class)
  *   nmse         host, [3][n_q_heads] out, row m = mask m + 1; may be NULL.  All three masks are
  *                evaluated for every head (Alg. 1 stops at the first that passes, which only saves
@@ -231,8 +254,8 @@ int bs_attn_prefill_ex(const void *q, const void *k, const void *v, void *out, b
 int bs_characterize_prompt(const void *q, const void *k, const void *v, const bs_span *spans,
                            int32_t n_spans, int32_t seq_len, int32_t sink_len, int32_t dtype,
                            int32_t n_q_heads, int32_t gqa_group, int32_t head_dim, float scale,
-                           double alpha, uint32_t map_flags, uint8_t *head_type, double *nmse,
-                           void *stream);
+                           double alpha, uint32_t map_flags, const int32_t *sink_offsets,
+                           int32_t n_sink_offsets, uint8_t *head_type, double *nmse, void *stream);
 
 /*
  * The error measure of Alg. 1 on its own: for each of n_heads contiguous blocks of elems_per_head

@@ -92,6 +92,7 @@ struct KernelArgs {
     float scale_log2e;  // scale * log2(e): softmax runs in the exp2 domain
     int32_t n_prompt_tiles;   // key tiles that are the prompt in position order (compact tiles follow)
     int32_t packed, intra_compact;
+    int32_t bidir;            // tokens of one image also see the later tokens of that image
 };
 #define BS_MAP_PARAMS                                                                              \
     const uint32_t *__restrict__ map_code, const uint64_t *__restrict__ map_text_bits,             \
@@ -144,7 +145,7 @@ struct TileWalker {
 // keys -- text and sink keys -- from compact tiles and only own-image keys from the prompt's
 // tiles, so that every allowed pair is counted once.
 struct QueryView {
-    int32_t row;       // query position i
+    int32_t row;       // last visible position: the query's own (causal), the end of its image (bidirectional images)
     int32_t own_lo;    // own image [own_lo, own_hi) if the class attends inside images, else empty
     int32_t own_hi;
     int32_t free_bound;  // packed: free keys at positions <= i (the visible compact slots are [0, free_bound))
@@ -154,7 +155,7 @@ struct QueryView {
     bool own_only;     // packed: in the prompt's tiles only own-image keys count for this query
     __device__ void init(const uint32_t *__restrict__ code, const int2 *__restrict__ span_range,
                          const int32_t *__restrict__ free_before, const int2 *__restrict__ span_free,
-                         int L, int cls, int32_t i, bool packed, bool intra_compact)
+                         int L, int cls, int32_t i, bool packed, bool intra_compact, bool bidir)
     {
         row = i;
         const uint32_t qcode = i < L ? code[i] : kCodeText;
@@ -162,12 +163,15 @@ struct QueryView {
         own_lo = own_hi = 0;
         free_bound = cfree_lo = cfree_hi = 0;
         own_only = false;
-        if (!sees_all && (cls & 2)) {
+        if (!(qcode & kCodeText) && (bidir || (cls & 2))) {
             const int2 sp = span_range[qcode & kCodeImgMask];
-            own_lo = sp.x; own_hi = sp.y;
+            // an image query that sees its whole image behaves, for every class, like the
+            // image's last query under the causal mask
+            if (bidir) row = sp.y - 1;
+            if (!sees_all && (cls & 2)) { own_lo = sp.x; own_hi = sp.y; }
         }
         if (packed && !sees_all && (cls != BS_INTRA || intra_compact)) {
-            free_bound = free_before[i + 1];
+            free_bound = free_before[row + 1];
             own_only = true;
             if (cls == BS_INTRA_SINK) {
                 const int2 cr = span_free[qcode & kCodeImgMask];
@@ -568,7 +572,7 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(
             qreg[t] = *reinterpret_cast<const bf16x8 *>(qh + (size_t)qrow * D + 16 * t + 8 * hl);
     }
     QueryView qv;
-    qv.init(map_code, map_span_range, map_free_before, map_span_free, L, cls, row, a.packed != 0, a.intra_compact != 0);
+    qv.init(map_code, map_span_range, map_free_before, map_span_free, L, cls, row, a.packed != 0, a.intra_compact != 0, a.bidir != 0);
 
     // LDS byte address of this lane's MFMA operand fragments inside a K / V^T tile (see the
     // tile layouts above): key or channel `col`, half hl; slices, blocks and groups are
@@ -919,7 +923,7 @@ __global__ __launch_bounds__(kThreads, 1) void attn_prefill_f32(KernelArgs a, BS
         for (int t = 0; t < D / 2; ++t) qreg[t] = qh[(size_t)qrow * D + 2 * t + hl];
     }
     QueryView qv;
-    qv.init(map_code, map_span_range, nullptr, nullptr, a.L, cls, row, false, false);
+    qv.init(map_code, map_span_range, nullptr, nullptr, a.L, cls, row, false, false, a.bidir != 0);
 
     floatx16 o[D / 32];
 #pragma unroll
@@ -1285,6 +1289,7 @@ extern "C" int bs_attn_prefill_ex(const void *q, const void *k, const void *v, v
     a.n_prompt_tiles = tm->N0;
     a.packed = tm->packed;
     a.intra_compact = tm->intra_compact;
+    a.bidir = tm->bidir;
     if (tm->packed && dtype != BS_BF16) return BS_EUNSUPPORTED;   // the fp32 kernel reads K / V in place
 
     const dim3 grid((unsigned)d->n_work), block(bs::kThreads);

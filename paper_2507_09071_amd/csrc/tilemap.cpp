@@ -19,7 +19,10 @@ namespace {
 using bs::ClassLists;
 using bs::TileRange;
 
-struct Segment { int32_t g, a, b; };  // rows [a, b) of the query tile lie in image g (0-based)
+// Rows [a, b) of the query tile lie in image g (0-based).  [ea, eb): the same rows by the last key
+// position they may see (+1 for eb): themselves under the causal mask; with bidirectional images
+// every row of image g sees up to the image's last token, as if it were that token's query.
+struct Segment { int32_t g, a, b, ea, eb; };
 
 struct Geometry {
     int32_t L, bm, bn, M, N;
@@ -34,6 +37,7 @@ struct Geometry {
     std::vector<int32_t> next_allfree_tile[2];  // N+1 each
     // packed keys: compact tiles N .. N + Nc - 1 hold the free keys (text or sink) in position order
     bool packed = false, intra_compact = false;
+    bool bidir = false;                // tokens of one image also see the later tokens of that image
     int32_t Nc = 0, n_free = 0;
     std::vector<int32_t> ctext;        // n_free + 1: text keys among compact slots [0, s)
 
@@ -44,6 +48,7 @@ struct Geometry {
 
 struct QueryTile {
     int32_t r0, r1;       // rows [r0, r1), clipped to L
+    int32_t e0, e1;       // last visible key position of the first row, and of the last row + 1 (r0, r1 if causal)
     bool ragged;          // fewer than bm rows
     int32_t last_text;    // last text row inside, or -1
     std::vector<Segment> segs;
@@ -64,15 +69,20 @@ void describe_query_rows(const Geometry &G, int32_t r0, int32_t r1, bool ragged,
     // first span whose end lies beyond r0
     size_t lo = std::upper_bound(sp.begin(), sp.end(), qt.r0,
                                  [](int32_t r, const bs_span &s) { return r < s.end; }) - sp.begin();
-    for (size_t g = lo; g < sp.size() && sp[g].start < qt.r1; ++g)
-        qt.segs.push_back({(int32_t)g, std::max(sp[g].start, qt.r0), std::min(sp[g].end, qt.r1)});
+    for (size_t g = lo; g < sp.size() && sp[g].start < qt.r1; ++g) {
+        const int32_t a = std::max(sp[g].start, qt.r0), b = std::min(sp[g].end, qt.r1);
+        qt.segs.push_back({(int32_t)g, a, b, G.bidir ? sp[g].end - 1 : a, G.bidir ? sp[g].end : b});
+    }
+    // the visible range grows with the row position, so the first / last row bound the tile
+    qt.e0 = (!qt.segs.empty() && qt.segs.front().a == qt.r0) ? qt.segs.front().ea : qt.r0;
+    qt.e1 = (!qt.segs.empty() && qt.segs.back().b == qt.r1) ? qt.segs.back().eb : qt.r1;
 }
 
 // Exact state of tile (query tile qt, key tile n) for class cls: 0 skip, 1 partial, 2 full.
 int tile_state(const Geometry &G, const QueryTile &qt, int cls, int32_t n)
 {
     const int32_t c0 = n * G.bn, c1 = std::min(c0 + G.bn, G.L);
-    if (c0 > qt.r1 - 1) return 0;  // wholly above the diagonal
+    if (c0 > qt.e1 - 1) return 0;  // beyond what the last row sees
     const auto &sp = *G.spans;
     const auto &freec = G.free_count(cls);
 
@@ -81,7 +91,7 @@ int tile_state(const Geometry &G, const QueryTile &qt, int cls, int32_t n)
         any = true;
     } else {
         for (const Segment &s : qt.segs) {
-            int32_t hi = std::min(c1, s.b);  // keys j <= s.b - 1
+            int32_t hi = std::min(c1, s.eb);  // keys the segment's last row may see
             if (hi <= c0) continue;
             if (freec[hi] - freec[c0] > 0) { any = true; break; }
             if (cls & 2) {
@@ -93,7 +103,7 @@ int tile_state(const Geometry &G, const QueryTile &qt, int cls, int32_t n)
     if (!any) return 0;
 
     bool all;
-    if (qt.ragged || (c1 - c0) < G.bn || c1 - 1 > qt.r0) {
+    if (qt.ragged || (c1 - c0) < G.bn || c1 - 1 > qt.e0) {
         all = false;  // masked out-of-range positions, or the diagonal cuts through
     } else if (cls == BS_DENSE || qt.segs.empty()) {
         all = true;
@@ -117,7 +127,7 @@ int tile_state(const Geometry &G, const QueryTile &qt, int cls, int32_t n)
 void candidate_tiles(const Geometry &G, const QueryTile &qt, int cls, std::vector<int32_t> &cand)
 {
     cand.clear();
-    const int32_t n_last = (qt.r1 - 1) / G.bn;
+    const int32_t n_last = (qt.e1 - 1) / G.bn;
     if (cls == BS_DENSE || qt.last_text >= 0) {
         cand.resize(n_last + 1);
         for (int32_t n = 0; n <= n_last; ++n) cand[n] = n;
@@ -125,9 +135,9 @@ void candidate_tiles(const Geometry &G, const QueryTile &qt, int cls, std::vecto
     }
     // image-only query tile of a sparse class: tiles with a free key (text / enabled sink) ...
     const auto &nf = G.next_free(cls);
-    for (int32_t pos = 0; pos < qt.r1;) {
+    for (int32_t pos = 0; pos < qt.e1;) {
         int32_t j = nf[pos];
-        if (j >= qt.r1) break;
+        if (j >= qt.e1) break;
         int32_t n = j / G.bn;
         cand.push_back(n);
         pos = (n + 1) * G.bn;
@@ -137,7 +147,7 @@ void candidate_tiles(const Geometry &G, const QueryTile &qt, int cls, std::vecto
     if (cls & 2) {
         const auto &sp = *G.spans;
         for (const Segment &s : qt.segs)
-            for (int32_t n = sp[s.g].start / G.bn; n <= (s.b - 1) / G.bn; ++n) cand.push_back(n);
+            for (int32_t n = sp[s.g].start / G.bn; n <= (s.eb - 1) / G.bn; ++n) cand.push_back(n);
         std::sort(cand.begin(), cand.end());
         cand.erase(std::unique(cand.begin(), cand.end()), cand.end());
     }
@@ -163,9 +173,9 @@ void build_run(const Geometry &G, int cls, const QueryTile &qt, std::vector<int3
             run_begin = b; run_end = e; run_state = st;
         }
     };
-    const int32_t n_last = (qt.r1 - 1) / G.bn;
-    // key tiles wholly at or before the first row of a complete query tile can be FULL
-    const int32_t n_full_limit = qt.ragged ? 0 : (qt.r0 + 1) / G.bn;
+    const int32_t n_last = (qt.e1 - 1) / G.bn;
+    // key tiles wholly within what the first row of a complete query tile sees can be FULL
+    const int32_t n_full_limit = qt.ragged ? 0 : (qt.e0 + 1) / G.bn;
 
     if (cls == BS_DENSE || qt.segs.empty()) {
         // every earlier key is visible: FULL below the diagonal, PARTIAL on it
@@ -181,7 +191,7 @@ void build_run(const Geometry &G, int cls, const QueryTile &qt, std::vector<int3
         for (int32_t n = naf[0]; n < n_full_limit; n = naf[n + 1]) cand.push_back(n);
         const auto &sp = *G.spans;
         for (const Segment &sg : qt.segs)
-            for (int32_t n = sp[sg.g].start / G.bn; n <= (sg.b - 1) / G.bn && n < n_full_limit; ++n) cand.push_back(n);
+            for (int32_t n = sp[sg.g].start / G.bn; n <= (sg.eb - 1) / G.bn && n < n_full_limit; ++n) cand.push_back(n);
         for (int32_t n = qt.last_text / G.bn + 1; n <= n_last; ++n) cand.push_back(n);
         std::sort(cand.begin(), cand.end());
         cand.erase(std::unique(cand.begin(), cand.end()), cand.end());
@@ -205,6 +215,7 @@ void build_run(const Geometry &G, int cls, const QueryTile &qt, std::vector<int3
 
 // Packed keys: range list of rows [a, b), all inside image g (0-based span index), for a sparse
 // class.  Two parts, disjoint by construction:
+// [a, b) are the rows by the last key position they may see (Segment::ea, eb).
 //   own-image keys (classes with the intra bit): the prompt's own tiles over [start_g, b);
 //     a pair (i, j) counts there iff start_g <= j <= i;
 //   free keys: compact tiles; row i sees compact slot s iff s < free_before[i + 1] (the free
@@ -320,7 +331,7 @@ void build_class(const Geometry &G, int cls, const std::vector<int32_t> &row_ord
                 // (two images can be adjacent without a text token between them)
                 bool first_seg = true;
                 for (const Segment &sg : qt.segs) {
-                    build_run_packed(G, cls, sg.g, sg.a, sg.b, ragged, first_seg ? run : seg_run);
+                    build_run_packed(G, cls, sg.g, sg.ea, sg.eb, ragged, first_seg ? run : seg_run);
                     if (!first_seg) {
                         combine_runs(run, seg_run, tmp);
                         run.swap(tmp);
@@ -362,12 +373,13 @@ void count_pairs(const Geometry &G, const std::vector<uint32_t> &code, ClassList
             continue;
         }
         while (sp[g].end <= i) ++g;
-        const int64_t text = G.n_text[i + 1];
-        const int64_t sink_img = G.n_free_sink[i + 1] - text;  // image tokens that are sinks, <= i
-        const int64_t own = i - sp[g].start + 1;
-        const int64_t own_sink = (G.n_free_sink[i + 1] - G.n_free_sink[sp[g].start]) -
-                                 (G.n_text[i + 1] - G.n_text[sp[g].start]);
-        const int64_t row[4] = {i + 1, text + sink_img, text + own, text + sink_img + own - own_sink};
+        const int32_t e = G.bidir ? sp[g].end - 1 : i;   // last key position the row may see
+        const int64_t text = G.n_text[e + 1];
+        const int64_t sink_img = G.n_free_sink[e + 1] - text;  // image tokens that are sinks, <= e
+        const int64_t own = e - sp[g].start + 1;
+        const int64_t own_sink = (G.n_free_sink[e + 1] - G.n_free_sink[sp[g].start]) -
+                                 (G.n_text[e + 1] - G.n_text[sp[g].start]);
+        const int64_t row[4] = {e + 1, text + sink_img, text + own, text + sink_img + own - own_sink};
         for (int c = 0; c < 4; ++c) {
             pairs[c] += row[c];
             if (row[c] == 0) ++empty[c];
@@ -401,7 +413,19 @@ extern "C" int bs_build_tilemap_ex(const bs_span *spans, int32_t n_spans, int32_
                                    const uint8_t *head_class, int32_t n_q_heads, int32_t sink_len,
                                    int32_t block_m, int32_t block_n, uint32_t flags, bs_tilemap **out)
 {
-    if (flags & ~(uint32_t)(BS_MAP_REGROUP_ROWS | BS_MAP_PACK_KEYS)) return BS_EINVAL;
+    return bs_build_tilemap_model(spans, n_spans, seq_len, head_class, n_q_heads, sink_len, block_m, block_n, flags,
+                                  nullptr, 0, out);
+}
+
+extern "C" int bs_build_tilemap_model(const bs_span *spans, int32_t n_spans, int32_t seq_len,
+                                      const uint8_t *head_class, int32_t n_q_heads, int32_t sink_len,
+                                      int32_t block_m, int32_t block_n, uint32_t flags,
+                                      const int32_t *sink_offsets, int32_t n_sink_offsets, bs_tilemap **out)
+{
+    if (flags & ~(uint32_t)(BS_MAP_REGROUP_ROWS | BS_MAP_PACK_KEYS | BS_MAP_BIDIR_IMAGES)) return BS_EINVAL;
+    if (n_sink_offsets < 0 || (n_sink_offsets > 0 && !sink_offsets)) return BS_EINVAL;
+    for (int32_t o = 0; o < n_sink_offsets; ++o)
+        if (sink_offsets[o] < 0) return BS_EINVAL;
     if (flags & BS_MAP_PACK_KEYS) flags |= BS_MAP_REGROUP_ROWS;   // packed lists exist for image-only query tiles
     if (!out || !head_class || n_q_heads <= 0 || seq_len <= 0 || n_spans < 0) return BS_EINVAL;
     if (n_spans > 0 && !spans) return BS_EINVAL;
@@ -430,6 +454,10 @@ extern "C" int bs_build_tilemap_ex(const bs_span *spans, int32_t n_spans, int32_
                 if (t - spans[g].start < spans[g].sink || t < sink_len) c |= bs::kCodeSink;
                 tm->code[t] = c;
             }
+        for (int32_t g = 0; g < n_spans; ++g)   // sinks at fixed offsets inside every image
+            for (int32_t o = 0; o < n_sink_offsets; ++o)
+                if (sink_offsets[o] < spans[g].end - spans[g].start) tm->code[spans[g].start + sink_offsets[o]] |= bs::kCodeSink;
+        tm->bidir = (flags & BS_MAP_BIDIR_IMAGES) != 0 && n_spans > 0;
 
         // Key tiles: the prompt's keys in position order, then (packed) compact tiles with the
         // free keys -- text keys and sink keys, what an image query of a sparse class may see
@@ -492,6 +520,7 @@ extern "C" int bs_build_tilemap_ex(const bs_span *spans, int32_t n_spans, int32_
 
         Geometry G;
         G.L = L; G.bm = block_m; G.bn = block_n; G.M = tm->M; G.N = tm->N0; G.spans = &tm->spans;
+        G.bidir = tm->bidir;
         G.n_text.assign(L + 1, 0);
         G.n_free_sink.assign(L + 1, 0);
         G.last_text.assign(L, -1);

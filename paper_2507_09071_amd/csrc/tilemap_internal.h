@@ -65,6 +65,7 @@ struct bs_tilemap {
     // [N0, N) are compact tiles holding the free keys (text and sink keys) in position order.
     int32_t N0 = 0;
     bool packed = false;
+    bool bidir = false;                    // image tokens also attend to the later tokens of their own image
     bool intra_compact = false;            // packed: Intra-Image rows take their text keys from the compact tiles
     std::vector<int32_t> key_order;        // N * bn: position of each key-tile slot, -1 = none
     std::vector<int32_t> free_before;      // packed: L + 1, free keys at positions < t

@@ -1,0 +1,82 @@
+"""GPU parity of the model variant with non-causal attention inside an image and sinks at fixed
+in-image offsets (paper Sec. 6.1, App. "Attention Sink Positions in Gemma 3") against the oracle."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2507_09071_amd as bs
+import workloads as W
+from oracle import characterize as C
+from test_gpu_parity import RUNS_A, full_parity, sampled_parity
+
+pytestmark = pytest.mark.gpu
+D, S, I, IS = 0, 1, 2, 3
+DEV = "cuda:0"
+OFFSETS = (0, 3, 64, 65, 129, 299, 400)
+
+
+@pytest.mark.parametrize("dtype,d,flags", [("f32", 64, 0), ("f32", 128, bs.BS_MAP_REGROUP_ROWS), ("bf16", 128, 0),
+                                           ("bf16", 64, bs.BS_MAP_REGROUP_ROWS), ("bf16", 128, bs.BS_MAP_PACK_KEYS),
+                                           ("bf16", 64, bs.BS_MAP_PACK_KEYS)])
+def test_bidirectional_small_prompt_all_classes(dtype, d, flags):
+    p = W.custom_prompt(RUNS_A, [D, S, I, IS, IS, I, S, D], 4, d, dtype=dtype, sink_len=5, span_sink=0,
+                        name=f"bidir-{dtype}-d{d}-f{flags}", value_recipe={"std": 1.0, "first_key_scale": 4.0},
+                        img_bidir=True, sink_offsets=OFFSETS)
+    full_parity(p, seed=11, flags=flags)
+
+
+@pytest.mark.parametrize("flags", [0, bs.BS_MAP_PACK_KEYS])
+def test_offset_sinks_with_causal_images(flags):
+    p = W.custom_prompt(RUNS_A, [S, IS, I, D], 2, 128, dtype="bf16", sink_len=0, span_sink=0,
+                        name=f"offset-sinks-causal-f{flags}", sink_offsets=OFFSETS)
+    full_parity(p, seed=12, flags=flags)
+
+
+@pytest.mark.parametrize("flags", [0, bs.BS_MAP_PACK_KEYS])
+def test_bidirectional_equal_small_images(flags):
+    """Many images of one size with little text between them, image first, two adjacent images:
+    the layout of the Gemma-like workload in small."""
+    runs = []
+    for i in range(30):
+        runs += [("I", 96), ("T", 1 + (i % 4))]
+        if i % 9 == 4:
+            runs += [("I", 96)]
+    p = W.custom_prompt(runs, [S, I, IS, D, IS, S], 3, 128, dtype="bf16", sink_len=0, span_sink=0,
+                        name=f"bidir-equal-f{flags}", img_bidir=True, sink_offsets=(5, 17, 18, 70, 95))
+    full_parity(p, seed=13, flags=flags)
+
+
+def test_bidirectional_ragged_image_at_the_end():
+    p = W.custom_prompt([("T", 10), ("I", 500), ("T", 2), ("I", 333)], [D, IS, S, I], 2, 128, dtype="bf16",
+                        span_sink=0, name="bidir-tail", img_bidir=True, sink_offsets=(1, 2, 300))
+    assert p.seq_len % 128 != 0
+    full_parity(p, seed=14, flags=bs.BS_MAP_PACK_KEYS)
+    full_parity(p, seed=14, flags=0)
+
+
+def test_gemma_like_config_sampled_rows():
+    p = W.gemma3_bidir_config(0)
+    sampled_parity(p, 0, n_random=3, max_tiles=10, row_step=32, flags=bs.BS_MAP_PACK_KEYS)
+
+
+def test_characterisation_with_bidirectional_images():
+    kinds = ["dense", "sink", "intra", "intra_sink"] * 2
+    runs = [("T", 40), ("I", 256), ("T", 12), ("I", 256), ("T", 20), ("I", 256), ("T", 17)]
+    offs = (3, 50, 51, 200)
+    p = W.custom_prompt(runs, [0] * 8, 2, 64, dtype="bf16", span_sink=0, img_bidir=True, sink_offsets=offs)
+    q, k, v = W.make_planted_qkv(p, kinds, seed=5, device=DEV)
+    got_type, got = bs.bs_characterize_prompt(q, k, v, p.spans, p.seq_len, p.sink_len, bs.BS_BF16, 8, 4, 64, p.scale,
+                                              0.1, bs.BS_MAP_PACK_KEYS | bs.BS_MAP_BIDIR_IMAGES,
+                                              torch.cuda.current_stream().cuda_stream, sink_offsets=offs)
+    imgid, issink = oracle.token_arrays(p.spans, p.seq_len, p.sink_len, offs)
+    f = lambda t: t.float().cpu().numpy()
+    _, want = C.characterize_prompt(f(q), f(k), f(v), imgid, issink, p.scale, 0.0, True)
+    want_type, _ = C.characterize_prompt(f(q), f(k), f(v), imgid, issink, p.scale, 0.1, True)
+    tol = 5e-3 * (2 + 2 * np.sqrt(want)) / (1 - 5e-3)
+    assert (np.abs(np.sqrt(got) - np.sqrt(want)) <= tol).all(), (got, want)
+    clear = np.abs(np.sqrt(want) - np.sqrt(0.1)) > tol
+    for h in range(8):
+        if clear[:, h].all():
+            assert got_type[h] == want_type[h], (h, got[:, h], want[:, h])
+    assert clear.all(axis=0).sum() >= 6

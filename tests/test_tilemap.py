@@ -17,15 +17,20 @@ from golden_masks import all_fixtures, load
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def check_against_oracle(spans, L, sink_len, bm, bn, q_tiles=None, pairs=True):
-    tm = bs.bs_build_tilemap(spans, L, np.zeros(1, np.uint8), sink_len, bm, bn)
-    imgid, issink = oracle.token_arrays(spans, L, sink_len)
+def model_flags(bidir):
+    return bs.BS_MAP_BIDIR_IMAGES if bidir else 0
+
+
+def check_against_oracle(spans, L, sink_len, bm, bn, q_tiles=None, pairs=True, bidir=False, offsets=None):
+    tm = bs.bs_build_tilemap(spans, L, np.zeros(1, np.uint8), sink_len, bm, bn, flags=model_flags(bidir),
+                             sink_offsets=offsets)
+    imgid, issink = oracle.token_arrays(spans, L, sink_len, offsets)
     for c in range(4):
         if q_tiles is None:
-            want = oracle.tile_states(c, imgid, issink, bm, bn)
+            want = oracle.tile_states(c, imgid, issink, bm, bn, None, bidir)
             got = tm.tile_states(c)
         else:
-            want = oracle.tile_states(c, imgid, issink, bm, bn, q_tiles)
+            want = oracle.tile_states(c, imgid, issink, bm, bn, q_tiles, bidir)
             got = np.stack([tm.tile_states(c, int(m), 1)[0] for m in q_tiles])
         assert np.array_equal(got, want), (c, np.argwhere(got != want)[:5])
         st = tm.stats(c)
@@ -34,10 +39,10 @@ def check_against_oracle(spans, L, sink_len, bm, bn, q_tiles=None, pairs=True):
             assert st["full"] == int((want == 2).sum())
             assert st["partial"] == int((want == 1).sum())
         if pairs:
-            assert st["allowed_pairs"] == oracle.pair_count(c, imgid, issink)
+            assert st["allowed_pairs"] == oracle.pair_count(c, imgid, issink, bidir)
             m = None
             if L <= 2048:
-                m = oracle.mask(c, imgid, issink)
+                m = oracle.mask(c, imgid, issink, bidir)
                 assert st["empty_rows"] == int((~m.any(axis=1)).sum())
     return tm
 
@@ -107,11 +112,12 @@ def test_states_do_not_depend_on_head_classes():
 
 # ------------------------------------------------------------------------- regrouped query rows
 
-def check_regrouped(spans, L, sink_len, bm, bn, hc=None, q_tiles=None):
+def check_regrouped(spans, L, sink_len, bm, bn, hc=None, q_tiles=None, bidir=False, offsets=None):
     """Map built with BS_MAP_REGROUP_ROWS against the oracle's reduction over the map's own row lists."""
     hc = np.zeros(1, np.uint8) if hc is None else hc
-    tm = bs.bs_build_tilemap(spans, L, hc, sink_len, bm, bn, flags=bs.BS_MAP_REGROUP_ROWS)
-    imgid, issink = oracle.token_arrays(spans, L, sink_len)
+    tm = bs.bs_build_tilemap(spans, L, hc, sink_len, bm, bn, flags=bs.BS_MAP_REGROUP_ROWS | model_flags(bidir),
+                             sink_offsets=offsets)
+    imgid, issink = oracle.token_arrays(spans, L, sink_len, offsets)
     rows = tm.row_order(bm)
     # a permutation of the positions, image rows first, each group in position order
     flat = rows[rows >= 0]
@@ -128,13 +134,13 @@ def check_regrouped(spans, L, sink_len, bm, bn, hc=None, q_tiles=None):
         assert np.array_equal(rows.ravel()[:L], np.arange(L))
     sel = np.arange(tm.n_q_tiles) if q_tiles is None else np.asarray(q_tiles)
     for c in range(4):
-        want = oracle.tile_states_rows(c, imgid, issink, rows[sel], bn)
+        want = oracle.tile_states_rows(c, imgid, issink, rows[sel], bn, bidir)
         got = tm.tile_states(c) if q_tiles is None else np.stack([tm.tile_states(c, int(m), 1)[0] for m in sel])
         assert np.array_equal(got, want), (c, np.argwhere(got != want)[:5])
         st = tm.stats(c)
         if q_tiles is None:
             assert st["visited"] == int((want > 0).sum()) and st["full"] == int((want == 2).sum())
-        assert st["allowed_pairs"] == oracle.pair_count(c, imgid, issink)   # the grouping changes no pair
+        assert st["allowed_pairs"] == oracle.pair_count(c, imgid, issink, bidir)   # the grouping changes no pair
     return tm
 
 
@@ -194,7 +200,7 @@ def test_regroup_flag_without_effect_and_bad_flags():
     for c in range(4):
         assert np.array_equal(a.tile_states(c), b.tile_states(c))
     with pytest.raises(bs.BlindsightError):
-        bs.bs_build_tilemap(spans, L, np.zeros(2, np.uint8), 0, flags=4)
+        bs.bs_build_tilemap(spans, L, np.zeros(2, np.uint8), 0, flags=8)
 
 
 # ------------------------------------------------------------------------- packed keys
@@ -218,9 +224,10 @@ def packed_expectation(c, rows, keys, in_prompt_space, mask, imgid, packed=True,
     return np.where(plain, False, allowed & ~own)
 
 
-def check_packed(spans, L, sink_len, bm, bn):
-    tm = bs.bs_build_tilemap(spans, L, np.zeros(1, np.uint8), sink_len, bm, bn, flags=bs.BS_MAP_PACK_KEYS)
-    imgid, issink = oracle.token_arrays(spans, L, sink_len)
+def check_packed(spans, L, sink_len, bm, bn, bidir=False, offsets=None):
+    tm = bs.bs_build_tilemap(spans, L, np.zeros(1, np.uint8), sink_len, bm, bn,
+                             flags=bs.BS_MAP_PACK_KEYS | model_flags(bidir), sink_offsets=offsets)
+    imgid, issink = oracle.token_arrays(spans, L, sink_len, offsets)
     rows = tm.row_order(bm)
     keys, n0 = tm.key_order(bn)
     assert np.array_equal(keys[:n0].ravel()[:L], np.arange(L)) and (keys[:n0].ravel()[L:] < 0).all()
@@ -234,7 +241,7 @@ def check_packed(spans, L, sink_len, bm, bn):
     else:
         assert len(free) in (0, L) or (imgid == 0).all()
     for c in range(4):
-        mask = oracle.mask(c, imgid, issink)
+        mask = oracle.mask(c, imgid, issink, bidir)
         got = tm.tile_states(c)
         want = np.zeros_like(got)
         for m in range(tm.n_q_tiles):
@@ -247,7 +254,7 @@ def check_packed(spans, L, sink_len, bm, bn):
             valid = rows[m][rows[m] >= 0]
             assert total == int(mask[valid].sum()), (c, m)      # every allowed pair exactly once
         assert np.array_equal(got, want), (c, np.argwhere(got != want)[:5], got[got != want][:5], want[got != want][:5])
-        assert tm.stats(c)["allowed_pairs"] == oracle.pair_count(c, imgid, issink)
+        assert tm.stats(c)["allowed_pairs"] == oracle.pair_count(c, imgid, issink, bidir)
     return tm
 
 

@@ -330,6 +330,9 @@ def make_planted_qkv(p: Prompt, head_kinds, seed: int = 0, boost: float = 30.0, 
     for g, (s0, e0, sk) in enumerate(np.asarray(p.spans).reshape(-1, 3)):
         img[s0:e0] = g + 1
         sink[s0:s0 + sk] = True
+        for o in p.sink_offsets:
+            if o < e0 - s0:
+                sink[s0 + o] = True
     direction = np.zeros((L, d))
     in_img = img > 0
     direction[in_img] = basis[1 + (img[in_img] - 1) % (d - 1)]
