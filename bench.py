@@ -30,7 +30,9 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--config", type=int, default=2, help="workload family 1..5 (default: the 36K one)")
+    ap.add_argument("--config", type=int, default=2,
+                    help="workload family 1..5 (default: the 36K one); 6 = family 4 with non-causal attention "
+                         "inside an image and sinks at fixed in-image offsets")
     ap.add_argument("--target-len", type=int, default=None, help="config 5 prompt length")
     ap.add_argument("--map", choices=["packed", "regrouped", "natural"], default="packed",
                     help="tile map layout: natural = query rows and keys in position order; regrouped = text "
@@ -117,7 +119,8 @@ def timed_steps(bs, torch, p, q, k, v, out, steps, warmup, hev, flags):
 
     def step(record):
         t0 = time.perf_counter()
-        tm = bs.bs_build_tilemap(p.spans, p.seq_len, p.head_class, p.sink_len, 128, 64, flags=flags)
+        tm = bs.bs_build_tilemap(p.spans, p.seq_len, p.head_class, p.sink_len, 128, 64, flags=flags,
+                                 sink_offsets=p.sink_offsets or None)
         t1 = time.perf_counter()
         e0 = torch.cuda.Event(enable_timing=True)
         e1 = torch.cuda.Event(enable_timing=True)
@@ -149,21 +152,25 @@ def timed_steps(bs, torch, p, q, k, v, out, steps, warmup, hev, flags):
     return wall * 1e3, kern_ms, call_ms, 1e3 * sum(build_s) / len(build_s), 1e3 * sum(call_s) / len(call_s), keep[-1]
 
 
-def sampled_pairs(head_class, rows, imgid, issink):
+def sampled_pairs(head_class, rows, imgid, issink, img_bidir=False):
     """Allowed pairs of the given query rows summed over the heads (plain enumeration)."""
+    import numpy as np
     per_class_row = {}
     for c in set(int(x) for x in head_class):
         cnt = 0
         for i in rows:
             i = int(i)
+            e = i   # last key position the row may see
+            if img_bidir and imgid[i] != 0:
+                e = int(np.flatnonzero(imgid == imgid[i])[-1])
             if imgid[i] == 0 or c == 0:
-                cnt += i + 1
+                cnt += e + 1
             else:
-                ok = imgid[: i + 1] == 0
+                ok = imgid[: e + 1] == 0
                 if c & 1:
-                    ok |= issink[: i + 1] == 1
+                    ok |= issink[: e + 1] == 1
                 if c & 2:
-                    ok |= imgid[: i + 1] == imgid[i]
+                    ok |= imgid[: e + 1] == imgid[i]
                 cnt += int(ok.sum())
         per_class_row[c] = cnt
     return sum(per_class_row[int(c)] for c in head_class)
@@ -175,7 +182,7 @@ def cpu_baseline(p, q, k, v, target_seconds):
 
     import oracle
 
-    imgid, issink = oracle.token_arrays(p.spans, p.seq_len, p.sink_len)
+    imgid, issink = oracle.token_arrays(p.spans, p.seq_len, p.sink_len, p.sink_offsets)
     qn, kn, vn = (t.float().cpu().numpy() for t in (q, k, v))
     rng = np.random.default_rng(123)
     # pairs a row costs: count allowed keys per sampled row from the oracle's own predicate
@@ -183,15 +190,15 @@ def cpu_baseline(p, q, k, v, target_seconds):
     n_rows = 8
     rows = np.sort(rng.choice(p.seq_len, size=n_rows, replace=False)).astype(np.int32)
     t0 = time.perf_counter()
-    oracle.attention(qn, kn, vn, p.head_class, imgid, issink, p.scale, rows)
+    oracle.attention(qn, kn, vn, p.head_class, imgid, issink, p.scale, rows, p.img_bidir)
     t_probe = time.perf_counter() - t0
     n_rows = int(max(8, min(p.seq_len, n_rows * target_seconds / max(t_probe, 1e-3))))
     rows = np.sort(rng.choice(p.seq_len, size=n_rows, replace=False)).astype(np.int32)
     t0 = time.perf_counter()
-    oracle.attention(qn, kn, vn, p.head_class, imgid, issink, p.scale, rows)
+    oracle.attention(qn, kn, vn, p.head_class, imgid, issink, p.scale, rows, p.img_bidir)
     t = time.perf_counter() - t0
     # allowed pairs of the sampled rows, summed over heads (enumeration, outside the timed part)
-    pairs = sampled_pairs(p.head_class, rows, imgid, issink)
+    pairs = sampled_pairs(p.head_class, rows, imgid, issink, p.img_bidir)
     flops = 4.0 * p.head_dim * pairs
     return {"value": flops / t / 1e12, "unit": "TFLOP/s (useful, fp64 oracle)", "cores": oracle.num_threads(),
             "kind": "oracle", "seconds": round(t, 2),
@@ -207,7 +214,7 @@ def characterize_bench(args, bs, torch, p, q, k, v, flags):
     dt = bs.BS_BF16 if p.dtype == "bf16" else bs.BS_F32
     st = torch.cuda.current_stream().cuda_stream
     call = lambda: bs.bs_characterize_prompt(q, k, v, p.spans, p.seq_len, p.sink_len, dt, p.n_q_heads, p.gqa_group,
-                                              p.head_dim, p.scale, args.alpha, flags, st)
+                                              p.head_dim, p.scale, args.alpha, flags, st, p.sink_offsets or None)
     for _ in range(args.warmup):
         call()
     torch.cuda.synchronize()
@@ -234,7 +241,8 @@ def characterize_bench(args, bs, torch, p, q, k, v, flags):
     # attention work of the four runs
     pairs = []
     for c in range(4):
-        tm = bs.bs_build_tilemap(p.spans, p.seq_len, np.full(p.n_q_heads, c, np.uint8), p.sink_len, 128, 64, flags=flags)
+        tm = bs.bs_build_tilemap(p.spans, p.seq_len, np.full(p.n_q_heads, c, np.uint8), p.sink_len, 128, 64, flags=flags,
+                                 sink_offsets=p.sink_offsets or None)
         pairs.append(tm.stats(c)["allowed_pairs"] * p.n_q_heads)
     flop = 4.0 * p.head_dim * sum(pairs)
     res = {
@@ -264,7 +272,7 @@ def characterize_cpu_baseline(p, q, k, v, pairs_per_mask, target_seconds):
 
     import oracle
 
-    imgid, issink = oracle.token_arrays(p.spans, p.seq_len, p.sink_len)
+    imgid, issink = oracle.token_arrays(p.spans, p.seq_len, p.sink_len, p.sink_offsets)
     qn, kn, vn = (t.float().cpu().numpy() for t in (q, k, v))
     rng = np.random.default_rng(321)
     n_rows = 4
@@ -275,10 +283,10 @@ def characterize_cpu_baseline(p, q, k, v, pairs_per_mask, target_seconds):
         for c in range(4):
             hc = np.full(p.n_q_heads, c, np.uint8)
             t0 = time.perf_counter()
-            oracle.attention(qn, kn, vn, hc, imgid, issink, p.scale, rows)
+            oracle.attention(qn, kn, vn, hc, imgid, issink, p.scale, rows, p.img_bidir)
             t = time.perf_counter() - t0
             spent += t
-            total += t * pairs_per_mask[c] / max(1, sampled_pairs(hc, rows, imgid, issink))
+            total += t * pairs_per_mask[c] / max(1, sampled_pairs(hc, rows, imgid, issink, p.img_bidir))
         done = n_rows
         if attempt == 0:
             n_rows = int(max(4, min(p.seq_len, n_rows * target_seconds / max(spent, 1e-3))))
@@ -318,6 +326,8 @@ def main():
         del a, b
 
     flags = {"natural": 0, "regrouped": bs.BS_MAP_REGROUP_ROWS, "packed": bs.BS_MAP_PACK_KEYS}[args.map]
+    if p.img_bidir:
+        flags |= bs.BS_MAP_BIDIR_IMAGES
     order = args.map
     if args.characterize:
         del out
@@ -360,7 +370,9 @@ def main():
         "dtype": p.dtype, "data": "synthetic",
         "config": {"workload": p.name, "seq_len": p.seq_len, "n_q_heads": p.n_q_heads,
                    "n_kv_heads": p.n_kv_heads, "head_dim": d, "n_images": int(len(p.spans)),
-                   "sink_mode": args.sink_mode, "seed": args.seed, "map": order,
+                   "sink_mode": args.sink_mode if not p.sink_offsets else "%d in-image offsets" % len(p.sink_offsets),
+                   "image_attention": "bidirectional" if p.img_bidir else "causal",
+                   "seed": args.seed, "map": order,
                    "head_classes": {n: int((p.head_class == c).sum()) for c, n in enumerate(W.CLASS_NAMES)}},
         "kernel_ms": round(kern_ms, 4),
         "device_ms_per_call": round(call_ms, 4),

@@ -208,7 +208,8 @@ def stress_config(target_len: int, seed: int = 0, sink_mode: str = "paper10") ->
 
 
 def config(idx: int, seed: int = 0, sink_mode: str = "paper10", target_len: int | None = None) -> Prompt:
-    """The five workload families, numbered 1..5 in the order the baseline lists them."""
+    """The five workload families, numbered 1..5 in the order the baseline lists them; 6 is family 4
+    with the Gemma 3 attention rules (non-causal inside an image, sinks at fixed in-image offsets)."""
     if idx == 1:
         return tiny_config(sink_mode)
     if idx == 2:
@@ -219,6 +220,8 @@ def config(idx: int, seed: int = 0, sink_mode: str = "paper10", target_len: int 
         return gemma3_27b_config(seed, sink_mode)
     if idx == 5:
         return stress_config(target_len or STRESS_LENGTHS[0], seed, sink_mode)
+    if idx == 6:
+        return gemma3_bidir_config(seed)
     raise ValueError(idx)
 
 
