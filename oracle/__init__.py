@@ -40,17 +40,17 @@ def _load():
         f32p, f64p = ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_double)
         lib.bso_token_arrays.argtypes = [i32p, i32, i32, i32, i32p, i32, i32p, u8p]
         lib.bso_token_arrays.restype = ctypes.c_int
-        lib.bso_allowed.argtypes = [ctypes.c_int, i32, i32, i32p, u8p, ctypes.c_int]
+        lib.bso_allowed.argtypes = [ctypes.c_int, i32, i32, i32p, u8p, ctypes.c_int, i32]
         lib.bso_allowed.restype = ctypes.c_int
-        lib.bso_mask.argtypes = [ctypes.c_int, i32, i32p, u8p, ctypes.c_int, u8p]
+        lib.bso_mask.argtypes = [ctypes.c_int, i32, i32p, u8p, ctypes.c_int, i32, u8p]
         lib.bso_mask.restype = None
-        lib.bso_pair_count.argtypes = [ctypes.c_int, i32, i32p, u8p, ctypes.c_int]
+        lib.bso_pair_count.argtypes = [ctypes.c_int, i32, i32p, u8p, ctypes.c_int, i32]
         lib.bso_pair_count.restype = i64
-        lib.bso_tile_states.argtypes = [ctypes.c_int, i32, i32p, u8p, ctypes.c_int, i32, i32, i32p, i32, u8p]
+        lib.bso_tile_states.argtypes = [ctypes.c_int, i32, i32p, u8p, ctypes.c_int, i32, i32, i32, i32p, i32, u8p]
         lib.bso_tile_states.restype = None
-        lib.bso_tile_states_rows.argtypes = [ctypes.c_int, i32, i32p, u8p, ctypes.c_int, i32, i32, i32p, i32, u8p]
+        lib.bso_tile_states_rows.argtypes = [ctypes.c_int, i32, i32p, u8p, ctypes.c_int, i32, i32, i32, i32p, i32, u8p]
         lib.bso_tile_states_rows.restype = None
-        lib.bso_attention.argtypes = [f32p, f32p, f32p, i32, i32, i32, i32, u8p, i32p, u8p, ctypes.c_int,
+        lib.bso_attention.argtypes = [f32p, f32p, f32p, i32, i32, i32, i32, u8p, i32p, u8p, ctypes.c_int, i32,
                                       ctypes.c_double, i32p, i32, f64p]
         lib.bso_attention.restype = ctypes.c_int
         lib.bso_num_threads.argtypes = []
@@ -82,27 +82,28 @@ def token_arrays(spans, seq_len: int, sink_len: int = 0, sink_offsets=None):
     return imgid, issink
 
 
-def allowed(cls: int, i: int, j: int, imgid, issink, img_bidir: bool = False) -> bool:
-    """img_bidir: the model's dense mask also lets a token see the later tokens of its own image."""
+def allowed(cls: int, i: int, j: int, imgid, issink, img_bidir: bool = False, window: int = 0) -> bool:
+    """img_bidir: the model's dense mask also lets a token see the later tokens of its own image;
+    window > 0: the dense mask keeps only keys with i - j < window (sliding-window layers)."""
     return bool(_load().bso_allowed(int(cls), int(i), int(j), _p(imgid, ctypes.c_int32),
-                                    _p(issink, ctypes.c_uint8), int(bool(img_bidir))))
+                                    _p(issink, ctypes.c_uint8), int(bool(img_bidir)), int(window)))
 
 
-def mask(cls: int, imgid, issink, img_bidir: bool = False) -> np.ndarray:
+def mask(cls: int, imgid, issink, img_bidir: bool = False, window: int = 0) -> np.ndarray:
     L = len(imgid)
     out = np.empty((L, L), dtype=np.uint8)
     _load().bso_mask(int(cls), L, _p(imgid, ctypes.c_int32), _p(issink, ctypes.c_uint8),
-                     int(bool(img_bidir)), _p(out, ctypes.c_uint8))
+                     int(bool(img_bidir)), int(window), _p(out, ctypes.c_uint8))
     return out
 
 
-def pair_count(cls: int, imgid, issink, img_bidir: bool = False) -> int:
+def pair_count(cls: int, imgid, issink, img_bidir: bool = False, window: int = 0) -> int:
     return int(_load().bso_pair_count(int(cls), len(imgid), _p(imgid, ctypes.c_int32),
-                                      _p(issink, ctypes.c_uint8), int(bool(img_bidir))))
+                                      _p(issink, ctypes.c_uint8), int(bool(img_bidir)), int(window)))
 
 
 def tile_states(cls: int, imgid, issink, block_m: int, block_n: int, q_tiles=None,
-                img_bidir: bool = False) -> np.ndarray:
+                img_bidir: bool = False, window: int = 0) -> np.ndarray:
     """uint8 [len(q_tiles), N] of 0 skip / 1 partial / 2 full, by enumeration of the elements."""
     L = len(imgid)
     M = -(-L // block_m)
@@ -110,11 +111,12 @@ def tile_states(cls: int, imgid, issink, block_m: int, block_n: int, q_tiles=Non
     qt = np.arange(M, dtype=np.int32) if q_tiles is None else np.ascontiguousarray(q_tiles, dtype=np.int32)
     out = np.empty((len(qt), N), dtype=np.uint8)
     _load().bso_tile_states(int(cls), L, _p(imgid, ctypes.c_int32), _p(issink, ctypes.c_uint8),
-                            int(bool(img_bidir)), block_m, block_n, _p(qt, ctypes.c_int32), len(qt), _p(out, ctypes.c_uint8))
+                            int(bool(img_bidir)), int(window), block_m, block_n, _p(qt, ctypes.c_int32), len(qt), _p(out, ctypes.c_uint8))
     return out
 
 
-def tile_states_rows(cls: int, imgid, issink, rows, block_n: int, img_bidir: bool = False) -> np.ndarray:
+def tile_states_rows(cls: int, imgid, issink, rows, block_n: int, img_bidir: bool = False,
+                     window: int = 0) -> np.ndarray:
     """Tile states for query tiles given as row lists: rows int32 [n_tiles, block_m], -1 = no row."""
     L = len(imgid)
     rows = np.ascontiguousarray(rows, dtype=np.int32)
@@ -122,12 +124,13 @@ def tile_states_rows(cls: int, imgid, issink, rows, block_n: int, img_bidir: boo
     N = -(-L // block_n)
     out = np.empty((rows.shape[0], N), dtype=np.uint8)
     _load().bso_tile_states_rows(int(cls), L, _p(imgid, ctypes.c_int32), _p(issink, ctypes.c_uint8),
-                                 int(bool(img_bidir)), rows.shape[1], block_n, _p(rows, ctypes.c_int32), rows.shape[0],
+                                 int(bool(img_bidir)), int(window), rows.shape[1], block_n, _p(rows, ctypes.c_int32), rows.shape[0],
                                  _p(out, ctypes.c_uint8))
     return out
 
 
-def attention(q, k, v, head_class, imgid, issink, scale: float, rows=None, img_bidir: bool = False) -> np.ndarray:
+def attention(q, k, v, head_class, imgid, issink, scale: float, rows=None, img_bidir: bool = False,
+              window: int = 0) -> np.ndarray:
     """fp64 masked-softmax attention.  q [Hq,L,d], k/v [Hkv,L,d] as float32 numpy arrays
     (widen bf16 exactly before calling).  Returns [Hq, n_rows, d] float64."""
     q = np.ascontiguousarray(q, dtype=np.float32)
@@ -150,7 +153,7 @@ def attention(q, k, v, head_class, imgid, issink, scale: float, rows=None, img_b
     rc = _load().bso_attention(_p(q, ctypes.c_float), _p(k, ctypes.c_float), _p(v, ctypes.c_float),
                                Hq, Hq // Hkv, L, d, _p(hc, ctypes.c_uint8),
                                _p(imgid, ctypes.c_int32), _p(issink, ctypes.c_uint8), int(bool(img_bidir)),
-                               float(scale), rp, n_rows, _p(out, ctypes.c_double))
+                               int(window), float(scale), rp, n_rows, _p(out, ctypes.c_double))
     if rc != 0:
         raise RuntimeError(f"oracle attention failed (code {rc})")
     return out
@@ -165,4 +168,4 @@ def attention_for_prompt(p, q, k, v, rows=None) -> np.ndarray:
         return t
     imgid, issink = token_arrays(p.spans, p.seq_len, p.sink_len, getattr(p, "sink_offsets", None))
     return attention(to_np(q), to_np(k), to_np(v), p.head_class, imgid, issink, p.scale, rows,
-                     bool(getattr(p, "img_bidir", False)))
+                     bool(getattr(p, "img_bidir", False)), int(getattr(p, "window", 0)))

@@ -22,6 +22,11 @@
  *     sparse mask is its class pattern restricted to that dense mask; the sinks of such a model
  *     sit at a fixed list of offsets inside every image       [Sec. 6.1, App. "Attention Sink
  *     Positions in Gemma 3"].  Selected by img_bidir != 0 / a sink offset list.
+ *   - layers whose default mask is a sliding window: the dense mask keeps only the `window`
+ *     most recent keys of a query (i - j < window), for text queries too [App. kernel, "Dense
+ *     Attention Subroutine": text queries follow the dense mask, causal or sliding window as per
+ *     the original model]; the sparse masks live inside it.  With img_bidir the keys of the
+ *     query's own image stay visible at any distance.  window <= 0: no window.
  *
  * Readings taken where the paper's pseudo-code is loose (Alg. 3-7):
  *   - the running sum l divides the output once at the end (the SoftMax of Sec. 3.1);
@@ -75,9 +80,12 @@ int bso_token_arrays(const int32_t *spans, int32_t n_spans, int32_t L, int32_t s
 
 /* May query i attend to key j in a head of class cls?  [Sec. 3.2]
  * img_bidir: tokens of one image also see the later tokens of that image (the model's dense mask). */
-int bso_allowed(int cls, int32_t i, int32_t j, const int32_t *imgid, const uint8_t *issink, int img_bidir)
+int bso_allowed(int cls, int32_t i, int32_t j, const int32_t *imgid, const uint8_t *issink, int img_bidir,
+                int32_t window)
 {
-    if (j > i && !(img_bidir && imgid[i] != 0 && imgid[j] == imgid[i])) return 0;  /* the dense mask */
+    /* the dense mask: causal, optionally windowed, optionally the whole own image */
+    int causal = j <= i && (window <= 0 || i - j < window);
+    if (!causal && !(img_bidir && imgid[i] != 0 && imgid[j] == imgid[i])) return 0;
     if (imgid[i] == 0) return 1;         /* text queries see all earlier tokens */
     if (cls == BSO_DENSE) return 1;
     if (imgid[j] == 0) return 1;         /* text keys stay visible: the vertical bands */
@@ -87,21 +95,23 @@ int bso_allowed(int cls, int32_t i, int32_t j, const int32_t *imgid, const uint8
 }
 
 /* Dense L x L bitmap (row-major, 1 = allowed).  Small prompts only. */
-void bso_mask(int cls, int32_t L, const int32_t *imgid, const uint8_t *issink, int img_bidir, uint8_t *mask)
+void bso_mask(int cls, int32_t L, const int32_t *imgid, const uint8_t *issink, int img_bidir, int32_t window,
+              uint8_t *mask)
 {
     for (int32_t i = 0; i < L; ++i)
         for (int32_t j = 0; j < L; ++j)
-            mask[(size_t)i * L + j] = (uint8_t)bso_allowed(cls, i, j, imgid, issink, img_bidir);
+            mask[(size_t)i * L + j] = (uint8_t)bso_allowed(cls, i, j, imgid, issink, img_bidir, window);
 }
 
 /* Number of allowed (i, j) pairs, by enumeration. */
-int64_t bso_pair_count(int cls, int32_t L, const int32_t *imgid, const uint8_t *issink, int img_bidir)
+int64_t bso_pair_count(int cls, int32_t L, const int32_t *imgid, const uint8_t *issink, int img_bidir,
+                       int32_t window)
 {
     int64_t total = 0;
 #pragma omp parallel for schedule(dynamic, 64) reduction(+ : total)
     for (int32_t i = 0; i < L; ++i) {
         int64_t c = 0;
-        for (int32_t j = 0; j < L; ++j) c += bso_allowed(cls, i, j, imgid, issink, img_bidir);
+        for (int32_t j = 0; j < L; ++j) c += bso_allowed(cls, i, j, imgid, issink, img_bidir, window);
         total += c;
     }
     return total;
@@ -112,7 +122,7 @@ int64_t bso_pair_count(int cls, int32_t L, const int32_t *imgid, const uint8_t *
  * not allowed.  state: 0 = no element allowed, 2 = all bm*bn allowed, 1 = otherwise.
  * states is [n_qtiles][N], N = ceil(L / bn). */
 void bso_tile_states(int cls, int32_t L, const int32_t *imgid, const uint8_t *issink, int img_bidir,
-                     int32_t bm, int32_t bn, const int32_t *qtiles, int32_t n_qtiles,
+                     int32_t window, int32_t bm, int32_t bn, const int32_t *qtiles, int32_t n_qtiles,
                      uint8_t *states)
 {
     int32_t N = (L + bn - 1) / bn;
@@ -125,7 +135,7 @@ void bso_tile_states(int cls, int32_t L, const int32_t *imgid, const uint8_t *is
                 if (i >= L) continue;
                 for (int32_t j = n * bn; j < n * bn + bn; ++j) {
                     if (j >= L) continue;
-                    cnt += bso_allowed(cls, i, j, imgid, issink, img_bidir);
+                    cnt += bso_allowed(cls, i, j, imgid, issink, img_bidir, window);
                 }
             }
             states[(size_t)t * N + n] = (uint8_t)(cnt == 0 ? 0 : (cnt == (int64_t)bm * bn ? 2 : 1));
@@ -137,7 +147,7 @@ void bso_tile_states(int cls, int32_t L, const int32_t *imgid, const uint8_t *is
  * query rows in another order than their positions): rows is [n_qtiles][bm], entries < 0 or
  * >= L are slots without a row and count as not allowed, like positions past the end above. */
 void bso_tile_states_rows(int cls, int32_t L, const int32_t *imgid, const uint8_t *issink, int img_bidir,
-                          int32_t bm, int32_t bn, const int32_t *rows, int32_t n_qtiles,
+                          int32_t window, int32_t bm, int32_t bn, const int32_t *rows, int32_t n_qtiles,
                           uint8_t *states)
 {
     int32_t N = (L + bn - 1) / bn;
@@ -150,7 +160,7 @@ void bso_tile_states_rows(int cls, int32_t L, const int32_t *imgid, const uint8_
                 if (i < 0 || i >= L) continue;
                 for (int32_t j = n * bn; j < n * bn + bn; ++j) {
                     if (j >= L) continue;
-                    cnt += bso_allowed(cls, i, j, imgid, issink, img_bidir);
+                    cnt += bso_allowed(cls, i, j, imgid, issink, img_bidir, window);
                 }
             }
             states[(size_t)t * N + n] = (uint8_t)(cnt == 0 ? 0 : (cnt == (int64_t)bm * bn ? 2 : 1));
@@ -166,7 +176,7 @@ void bso_tile_states_rows(int cls, int32_t L, const int32_t *imgid, const uint8_
  * out = sum_j exp(x_j - m) v_j / sum_j exp(x_j - m).  Empty allowed set -> zeros. */
 int bso_attention(const float *q, const float *k, const float *v, int32_t Hq, int32_t G,
                   int32_t L, int32_t d, const uint8_t *head_class, const int32_t *imgid,
-                  const uint8_t *issink, int img_bidir, double scale, const int32_t *rows, int32_t n_rows,
+                  const uint8_t *issink, int img_bidir, int32_t window, double scale, const int32_t *rows, int32_t n_rows,
                   double *out)
 {
     if (Hq <= 0 || G <= 0 || Hq % G || L <= 0 || d <= 0) return -1;
@@ -197,7 +207,7 @@ int bso_attention(const float *q, const float *k, const float *v, int32_t Hq, in
 
                 double mx = -INFINITY;
                 for (int32_t j = 0; j < L; ++j) {
-                    if (!bso_allowed(cls, i, j, imgid, issink, img_bidir)) continue;
+                    if (!bso_allowed(cls, i, j, imgid, issink, img_bidir, window)) continue;
                     const float *kj = kh + (size_t)j * d;
                     double acc = 0.0;
 #pragma omp simd reduction(+ : acc)
@@ -208,7 +218,7 @@ int bso_attention(const float *q, const float *k, const float *v, int32_t Hq, in
                 if (mx == -INFINITY) continue; /* empty allowed set: zeros */
                 double denom = 0.0;
                 for (int32_t j = 0; j < L; ++j) {
-                    if (!bso_allowed(cls, i, j, imgid, issink, img_bidir)) continue;
+                    if (!bso_allowed(cls, i, j, imgid, issink, img_bidir, window)) continue;
                     double p = exp(x[j] - mx);
                     denom += p;
                     const float *vj = vh + (size_t)j * d;

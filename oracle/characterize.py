@@ -38,7 +38,8 @@ def nmse(attn_mask: np.ndarray, attn_ref: np.ndarray) -> float:
     return num / den
 
 
-def characterize_prompt(q, k, v, imgid, issink, scale: float, alpha: float, img_bidir: bool = False):
+def characterize_prompt(q, k, v, imgid, issink, scale: float, alpha: float, img_bidir: bool = False,
+                        window: int = 0):
     """Alg. 1 for every query head of one layer.
 
     q [Hq, L, d], k / v [Hkv, L, d] float32 arrays.  Returns (head_type uint8 [Hq],
@@ -56,7 +57,7 @@ def characterize_prompt(q, k, v, imgid, issink, scale: float, alpha: float, img_
 
         def attn(cls):
             return attention(q[h:h + 1], k[kv:kv + 1], v[kv:kv + 1], np.array([cls], dtype=np.uint8),
-                             imgid, issink, scale, None, img_bidir)[0]
+                             imgid, issink, scale, None, img_bidir, window)[0]
 
         attn_ref = attn(DENSE)
         for m, cls in enumerate(MASK_ORDER):

@@ -53,9 +53,9 @@ def all_fixtures():
 
 
 def load_full(path):
-    """Fixtures with full-width rows, an `offsets:` line (sink offsets inside every image) and a
-    `mode:` line (bidir = non-causal attention inside an image)."""
-    runs, sink_len, offsets, mode, masks, cur = None, 0, [], "causal", {}, None
+    """Fixtures with full-width rows, an `offsets:` line (sink offsets inside every image), a
+    `mode:` line (bidir = non-causal attention inside an image) and an optional `window:` line."""
+    runs, sink_len, offsets, mode, masks, cur, window = None, 0, [], "causal", {}, None, 0
     with open(path) as f:
         for line in f:
             line = line.strip()
@@ -72,6 +72,8 @@ def load_full(path):
                 sink_len = int(line.split(":")[1])
             elif line.startswith("mode:"):
                 mode = line.split(":")[1].strip()
+            elif line.startswith("window:"):
+                window = int(line.split(":")[1])
             elif line.startswith("class"):
                 cur = CLASS_ID[line.split()[1]]
                 masks[cur] = []
@@ -86,7 +88,7 @@ def load_full(path):
     for c, rows in masks.items():
         assert len(rows) == pos and all(len(r) == pos for r in rows), (path, c)
         out[c] = np.array([[int(ch) for ch in r] for r in rows], dtype=np.uint8)
-    return pos, np.asarray(spans, dtype=np.int32).reshape(-1, 3), sink_len, offsets, mode == "bidir", out
+    return pos, np.asarray(spans, dtype=np.int32).reshape(-1, 3), sink_len, offsets, mode == "bidir", out, window
 
 
 def full_fixtures():

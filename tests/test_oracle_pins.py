@@ -403,11 +403,11 @@ def test_tile_size_independence(bm, bn):
 
 @pytest.mark.parametrize("path", full_fixtures())
 def test_bidirectional_and_offset_sink_masks_match_hand_derived_bitmaps(path):
-    L, spans, sink_len, offsets, bidir, expected = load_full(path)
+    L, spans, sink_len, offsets, bidir, expected, window = load_full(path)
     imgid, issink = oracle.token_arrays(spans, L, sink_len, offsets)
     assert len(expected) == 4
     for cls, want in expected.items():
-        got = oracle.mask(cls, imgid, issink, bidir)
+        got = oracle.mask(cls, imgid, issink, bidir, window)
         assert np.array_equal(got, want), f"{path} class {cls}\n{got}\n{want}"
 
 
@@ -467,3 +467,48 @@ def test_bidirectional_attention_equals_library_attention_with_explicit_mask():
     rows = np.array([0, 5, 6, 94, 95, 100, 217, L - 1], dtype=np.int32)
     sub = oracle.attention_for_prompt(p, q, k, v, rows)
     assert np.array_equal(sub, got[:, rows])
+
+
+# ----------------------------------------------------------------------------- sliding window
+
+def test_window_mask_is_the_plain_mask_inside_the_band():
+    for seed in range(6):
+        p = small_prompt(seed)
+        imgid, issink = oracle.token_arrays(p.spans, p.seq_len, p.sink_len, [2, 9])
+        L = p.seq_len
+        ii, jj = np.meshgrid(np.arange(L), np.arange(L), indexing="ij")
+        own = (imgid[ii] == imgid[jj]) & (imgid[ii] > 0)
+        for window in (1, 2, 7, 33, L, L + 5):
+            band = (ii - jj < window)
+            for bidir in (False, True):
+                keep = band | own if bidir else band
+                for cls in (D, S, I, IS):
+                    plain = oracle.mask(cls, imgid, issink, bidir, 0).astype(bool)
+                    got = oracle.mask(cls, imgid, issink, bidir, window).astype(bool)
+                    assert np.array_equal(got, plain & keep), (seed, window, bidir, cls)
+                    assert oracle.pair_count(cls, imgid, issink, bidir, window) == int((plain & keep).sum())
+            if window >= L:
+                assert np.array_equal(oracle.mask(IS, imgid, issink, False, window), oracle.mask(IS, imgid, issink))
+        # closed form, causal dense mask: row i keeps min(i + 1, window) keys
+        assert oracle.pair_count(D, imgid, issink, False, 7) == sum(min(i + 1, 7) for i in range(L))
+
+
+def test_window_attention_equals_library_attention_with_explicit_mask():
+    p = W.custom_prompt([("T", 5), ("I", 90), ("T", 3), ("I", 120), ("I", 40), ("T", 9)],
+                        [D, S, I, IS, IS, I, S, D], 4, 24, dtype="f32", sink_len=2, scale=0.4, window=50)
+    q, k, v = (t.numpy() for t in W.make_qkv(p, 1))
+    imgid, issink = oracle.token_arrays(p.spans, p.seq_len, p.sink_len)
+    got = oracle.attention_for_prompt(p, q, k, v)
+    L = p.seq_len
+    band = np.tril(np.ones((L, L), dtype=bool)) & ~np.tril(np.ones((L, L), dtype=bool), -50)   # the textbook band
+    want = sdpa_fp64(q[0:1], k[0:1], v[0:1], 1, p.scale, band[None])
+    assert np.abs(got[0] - want[0]).max() < 1e-12
+    empty = 0
+    for h, c in enumerate(p.head_class):
+        m = oracle.mask(int(c), imgid, issink, False, 50).astype(bool)
+        rows = np.flatnonzero(m.any(axis=1))
+        empty += L - len(rows)
+        want = sdpa_fp64(q[h:h + 1, rows], k[h // 2:h // 2 + 1], v[h // 2:h // 2 + 1], 1, p.scale, m[None, rows])
+        assert np.abs(got[h][rows] - want[0]).max() < 1e-12, h
+        assert (got[h][~m.any(axis=1)] == 0).all()
+    assert empty > 0   # Sink-class rows deep inside an image see nothing within the window

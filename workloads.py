@@ -38,6 +38,7 @@ class Prompt:
     value_recipe: dict = field(default_factory=dict)
     img_bidir: bool = False    # tokens of one image also attend to the later tokens of that image
     sink_offsets: tuple = ()   # offsets inside every image that are sink keys too
+    window: int = 0            # > 0: sliding-window layer, a query sees keys with i - j < window
 
     @property
     def gqa_group(self) -> int:
@@ -227,7 +228,7 @@ def config(idx: int, seed: int = 0, sink_mode: str = "paper10", target_len: int 
 
 def custom_prompt(runs, head_class, n_kv_heads, head_dim, dtype="bf16", sink_len=0,
                   sink_mode="paper10", span_sink=None, scale=None, name="custom",
-                  value_recipe=None, img_bidir=False, sink_offsets=()) -> Prompt:
+                  value_recipe=None, img_bidir=False, sink_offsets=(), window=0) -> Prompt:
     """Small hand-shaped prompts for tests."""
     L, spans = layout_from_runs(runs, sink_mode, span_sink)
     hc = np.asarray(head_class, dtype=np.uint8)
@@ -235,7 +236,7 @@ def custom_prompt(runs, head_class, n_kv_heads, head_dim, dtype="bf16", sink_len
                   n_q_heads=len(hc), n_kv_heads=n_kv_heads, head_dim=head_dim, dtype=dtype,
                   scale=(1.0 / math.sqrt(head_dim)) if scale is None else scale,
                   value_recipe=value_recipe or {"std": 1.0}, img_bidir=bool(img_bidir),
-                  sink_offsets=tuple(int(o) for o in sink_offsets))
+                  sink_offsets=tuple(int(o) for o in sink_offsets), window=int(window))
 
 
 def make_qkv(p: Prompt, seed: int = 0, device: str = "cpu"):
