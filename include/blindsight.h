@@ -123,12 +123,21 @@ int bs_build_tilemap_ex(const bs_span *spans, int32_t n_spans, int32_t seq_len,
  * Paper Sec. 6.1 and App. "Attention Sink Positions in Gemma 3": that model tokenises every image to
  * the same length and its sinks sit at fixed locations inside every image (the paper keeps the 10 % most
  * frequent locations found on its characterisation set; the list itself is the caller's input).
- * Errors: as bs_build_tilemap_ex; BS_EINVAL for a negative offset or count.
+ * window > 0 makes the map one of a sliding-window layer: the layer's dense mask keeps, for every query
+ * (text queries too) and every class, only the keys with i - j < window (paper App. kernel, "Dense
+ * Attention Subroutine": text queries follow the model's dense mask, "causal or sliding window as per the
+ * original model"; the sparse masks live inside the dense mask).  0 = no window; a window of seq_len or
+ * more is no window.  With a window BS_MAP_PACK_KEYS acts as BS_MAP_REGROUP_ROWS (a windowed query tile
+ * visits a handful of key tiles: there is nothing to pack).  Together with BS_MAP_BIDIR_IMAGES the keys of
+ * the query's own image stay visible at any distance; the map supports that for images of at most
+ * `window` tokens (where the window alone already implies it) and returns BS_EUNSUPPORTED otherwise.
+ * Errors: as bs_build_tilemap_ex; BS_EINVAL for a negative offset, count or window.
  */
 int bs_build_tilemap_model(const bs_span *spans, int32_t n_spans, int32_t seq_len,
                            const uint8_t *head_class, int32_t n_q_heads, int32_t sink_len,
                            int32_t block_m, int32_t block_n, uint32_t flags,
-                           const int32_t *sink_offsets, int32_t n_sink_offsets, bs_tilemap **out);
+                           const int32_t *sink_offsets, int32_t n_sink_offsets, int32_t window,
+                           bs_tilemap **out);
 
 /* Frees the host arrays; device buffers (if any) go back to a per-process cache of the library
  * and are handed to a later map only after the work queued with this map has finished (the
@@ -238,7 +247,8 @@ int bs_attn_prefill_ex(const void *q, const void *k, const void *v, void *out, b
  *                bs_build_tilemap (host)
  *   alpha        the layer's threshold alpha_layer (the paper recommends 0.1 for Qwen-type models)
  *   map_flags    options for the four tile maps the call builds (BS_MAP_*; dtype BS_F32 needs a map
- *                without packed keys); sink_offsets / n_sink_offsets as for bs_build_tilemap_model
+ *                without packed keys); sink_offsets / n_sink_offsets / window as for
+ *                bs_build_tilemap_model
  *   head_type    host, n_q_heads values out (bs_head_class)
  *   nmse         host, [3][n_q_heads] out, row m = mask m + 1; may be NULL.  All three masks are
  *                evaluated for every head (Alg. 1 stops at the first that passes, which only saves
@@ -255,7 +265,8 @@ int bs_characterize_prompt(const void *q, const void *k, const void *v, const bs
                            int32_t n_spans, int32_t seq_len, int32_t sink_len, int32_t dtype,
                            int32_t n_q_heads, int32_t gqa_group, int32_t head_dim, float scale,
                            double alpha, uint32_t map_flags, const int32_t *sink_offsets,
-                           int32_t n_sink_offsets, uint8_t *head_type, double *nmse, void *stream);
+                           int32_t n_sink_offsets, int32_t window, uint8_t *head_type, double *nmse,
+                           void *stream);
 
 /*
  * The error measure of Alg. 1 on its own: for each of n_heads contiguous blocks of elems_per_head

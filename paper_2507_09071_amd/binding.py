@@ -72,7 +72,7 @@ def load_library():
                                         ctypes.POINTER(ctypes.c_void_p)]
     lib.bs_build_tilemap_ex.restype = ctypes.c_int
     lib.bs_build_tilemap_model.argtypes = [ctypes.POINTER(_Span), i32, i32, u8p, i32, i32, i32, i32, ctypes.c_uint32,
-                                           i32p, i32, ctypes.POINTER(ctypes.c_void_p)]
+                                           i32p, i32, i32, ctypes.POINTER(ctypes.c_void_p)]
     lib.bs_build_tilemap_model.restype = ctypes.c_int
     lib.bs_tilemap_row_order.argtypes = [vp, i32p]
     lib.bs_tilemap_row_order.restype = ctypes.c_int
@@ -98,7 +98,7 @@ def load_library():
     lib.bs_attn_prefill_ex.restype = ctypes.c_int
     f64, f64p = ctypes.c_double, ctypes.POINTER(ctypes.c_double)
     lib.bs_characterize_prompt.argtypes = [vp, vp, vp, ctypes.POINTER(_Span), i32, i32, i32, i32, i32, i32, i32,
-                                           ctypes.c_float, f64, ctypes.c_uint32, i32p, i32, u8p, f64p, vp]
+                                           ctypes.c_float, f64, ctypes.c_uint32, i32p, i32, i32, u8p, f64p, vp]
     lib.bs_characterize_prompt.restype = ctypes.c_int
     lib.bs_head_sq_error.argtypes = [vp, vp, i32, i32, ctypes.c_int64, vp, vp]
     lib.bs_head_sq_error.restype = ctypes.c_int
@@ -200,21 +200,24 @@ BS_MAP_BIDIR_IMAGES = 4
 
 
 def bs_build_tilemap(spans, seq_len: int, head_class, sink_len: int = 0,
-                     block_m: int = 128, block_n: int = 64, flags: int = 0, sink_offsets=None) -> TileMap:
+                     block_m: int = 128, block_n: int = 64, flags: int = 0, sink_offsets=None,
+                     window: int = 0) -> TileMap:
     """spans: int array [G,3] of (start, end, sink); head_class: uint8 [n_q_heads];
     flags: 0 or BS_MAP_* bits (goes through bs_build_tilemap_ex); sink_offsets: in-image offsets that
-    are sink keys in every image (goes through bs_build_tilemap_model)."""
+    are sink keys in every image, window: sliding window of the layer (both go through
+    bs_build_tilemap_model)."""
     lib = load_library()
     sp = np.ascontiguousarray(np.asarray(spans, dtype=np.int32).reshape(-1, 3))
     hc = np.ascontiguousarray(head_class, dtype=np.uint8)
     handle = ctypes.c_void_p()
     sp_ptr = sp.ctypes.data_as(ctypes.POINTER(_Span)) if len(sp) else None
     hc_ptr = hc.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8))
-    if sink_offsets is not None and len(sink_offsets):
-        so = np.ascontiguousarray(sink_offsets, dtype=np.int32).reshape(-1)
+    if (sink_offsets is not None and len(sink_offsets)) or window:
+        so = np.ascontiguousarray([] if sink_offsets is None else sink_offsets, dtype=np.int32).reshape(-1)
         rc = lib.bs_build_tilemap_model(sp_ptr, len(sp), int(seq_len), hc_ptr, len(hc), int(sink_len),
                                         int(block_m), int(block_n), int(flags),
-                                        so.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)), len(so), ctypes.byref(handle))
+                                        so.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)) if len(so) else None, len(so),
+                                        int(window), ctypes.byref(handle))
         _check(rc, "bs_build_tilemap_model")
     elif flags:
         rc = lib.bs_build_tilemap_ex(sp_ptr, len(sp), int(seq_len), hc_ptr, len(hc), int(sink_len),
@@ -256,7 +259,7 @@ def bs_attn_prefill(q, k, v, out, tilemap: TileMap, dtype: int, n_q_heads: int, 
 
 def bs_characterize_prompt(q, k, v, spans, seq_len: int, sink_len: int, dtype: int, n_q_heads: int,
                            gqa_group: int, head_dim: int, scale: float, alpha: float, map_flags: int = 0,
-                           stream=None, sink_offsets=None):
+                           stream=None, sink_offsets=None, window: int = 0):
     """Alg. 1 for every query head of one layer.  Returns (head_type uint8 [Hq], nmse float64 [3, Hq]);
     waits for the stream."""
     sp = np.ascontiguousarray(np.asarray(spans, dtype=np.int32).reshape(-1, 3))
@@ -267,7 +270,7 @@ def bs_characterize_prompt(q, k, v, spans, seq_len: int, sink_len: int, dtype: i
     so_ptr = so.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)) if len(so) else None
     rc = load_library().bs_characterize_prompt(
         _ptr(q), _ptr(k), _ptr(v), sp_ptr, len(sp), int(seq_len), int(sink_len), int(dtype), int(n_q_heads),
-        int(gqa_group), int(head_dim), float(scale), float(alpha), int(map_flags), so_ptr, len(so),
+        int(gqa_group), int(head_dim), float(scale), float(alpha), int(map_flags), so_ptr, len(so), int(window),
         head_type.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8)),
         nmse.ctypes.data_as(ctypes.POINTER(ctypes.c_double)), ctypes.c_void_p(int(stream) if stream else 0))
     _check(rc, "bs_characterize_prompt")

@@ -93,6 +93,7 @@ struct KernelArgs {
     int32_t n_prompt_tiles;   // key tiles that are the prompt in position order (compact tiles follow)
     int32_t packed, intra_compact;
     int32_t bidir;            // tokens of one image also see the later tokens of that image
+    int32_t window;           // > 0: keys more than window - 1 positions before the query are masked
 };
 #define BS_MAP_PARAMS                                                                              \
     const uint32_t *__restrict__ map_code, const uint64_t *__restrict__ map_text_bits,             \
@@ -146,6 +147,7 @@ struct TileWalker {
 // tiles, so that every allowed pair is counted once.
 struct QueryView {
     int32_t row;       // last visible position: the query's own (causal), the end of its image (bidirectional images)
+    int32_t first;     // first visible position: 0, or the start of the query's sliding window
     int32_t own_lo;    // own image [own_lo, own_hi) if the class attends inside images, else empty
     int32_t own_hi;
     int32_t free_bound;  // packed: free keys at positions <= i (the visible compact slots are [0, free_bound))
@@ -155,9 +157,10 @@ struct QueryView {
     bool own_only;     // packed: in the prompt's tiles only own-image keys count for this query
     __device__ void init(const uint32_t *__restrict__ code, const int2 *__restrict__ span_range,
                          const int32_t *__restrict__ free_before, const int2 *__restrict__ span_free,
-                         int L, int cls, int32_t i, bool packed, bool intra_compact, bool bidir)
+                         int L, int cls, int32_t i, bool packed, bool intra_compact, bool bidir, int32_t window)
     {
         row = i;
+        first = window > 0 ? max(0, i - window + 1) : 0;
         const uint32_t qcode = i < L ? code[i] : kCodeText;
         sees_all = (qcode & kCodeText) || cls == BS_DENSE;
         own_lo = own_hi = 0;
@@ -199,7 +202,7 @@ __device__ inline uint64_t allowed_keys(const QueryView &qv, int cls, uint64_t t
         const int n0 = n * kBlockN;
         const uint64_t base = qv.sees_all ? ~0ull : (qv.own_only ? 0ull : (tbits | ((cls & 1) ? sbits : 0ull)));
         const uint64_t own = bits_between(qv.own_lo - n0, qv.own_hi - n0);
-        return (base | own) & bits_below(min(max(qv.row - n0 + 1, 0), 64));   // causal: keys n0 .. row
+        return (base | own) & bits_between(qv.first - n0, qv.row - n0 + 1);   // keys first .. row
     }
     // compact tile: slots are free keys in position order, visible up to the row's bound
     const int s0 = (n - n_prompt) * kBlockN;
@@ -572,7 +575,7 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(
             qreg[t] = *reinterpret_cast<const bf16x8 *>(qh + (size_t)qrow * D + 16 * t + 8 * hl);
     }
     QueryView qv;
-    qv.init(map_code, map_span_range, map_free_before, map_span_free, L, cls, row, a.packed != 0, a.intra_compact != 0, a.bidir != 0);
+    qv.init(map_code, map_span_range, map_free_before, map_span_free, L, cls, row, a.packed != 0, a.intra_compact != 0, a.bidir != 0, a.window);
 
     // LDS byte address of this lane's MFMA operand fragments inside a K / V^T tile (see the
     // tile layouts above): key or channel `col`, half hl; slices, blocks and groups are
@@ -923,7 +926,7 @@ __global__ __launch_bounds__(kThreads, 1) void attn_prefill_f32(KernelArgs a, BS
         for (int t = 0; t < D / 2; ++t) qreg[t] = qh[(size_t)qrow * D + 2 * t + hl];
     }
     QueryView qv;
-    qv.init(map_code, map_span_range, nullptr, nullptr, a.L, cls, row, false, false, a.bidir != 0);
+    qv.init(map_code, map_span_range, nullptr, nullptr, a.L, cls, row, false, false, a.bidir != 0, a.window);
 
     floatx16 o[D / 32];
 #pragma unroll
@@ -1290,6 +1293,7 @@ extern "C" int bs_attn_prefill_ex(const void *q, const void *k, const void *v, v
     a.packed = tm->packed;
     a.intra_compact = tm->intra_compact;
     a.bidir = tm->bidir;
+    a.window = tm->window;
     if (tm->packed && dtype != BS_BF16) return BS_EUNSUPPORTED;   // the fp32 kernel reads K / V in place
 
     const dim3 grid((unsigned)d->n_work), block(bs::kThreads);

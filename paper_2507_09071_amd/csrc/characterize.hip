@@ -186,7 +186,8 @@ extern "C" int bs_characterize_prompt(const void *q, const void *k, const void *
                                       int32_t n_spans, int32_t seq_len, int32_t sink_len, int32_t dtype,
                                       int32_t n_q_heads, int32_t gqa_group, int32_t head_dim, float scale,
                                       double alpha, uint32_t map_flags, const int32_t *sink_offsets,
-                                      int32_t n_sink_offsets, uint8_t *head_type, double *nmse, void *stream)
+                                      int32_t n_sink_offsets, int32_t window, uint8_t *head_type, double *nmse,
+                                      void *stream)
 {
     using namespace bs;
     if (!q || !k || !v || !head_type || n_q_heads <= 0 || seq_len <= 0 || head_dim <= 0 || !(alpha == alpha))
@@ -210,7 +211,7 @@ extern "C" int bs_characterize_prompt(const void *q, const void *k, const void *
         std::fill(cls.begin(), cls.end(), (uint8_t)c);
         bs_tilemap *tm = nullptr;
         rc = bs_build_tilemap_model(spans, n_spans, seq_len, cls.data(), n_q_heads, sink_len, 128, 64, map_flags,
-                                    sink_offsets, n_sink_offsets, &tm);
+                                    sink_offsets, n_sink_offsets, window, &tm);
         if (rc != BS_OK) break;
         rc = bs_attn_prefill(q, k, v, c == 0 ? b.ref : b.cand, tm, dtype, n_q_heads, gqa_group, head_dim, scale, st);
         bs_tilemap_destroy(tm);

@@ -38,7 +38,10 @@ struct Geometry {
     // packed keys: compact tiles N .. N + Nc - 1 hold the free keys (text or sink) in position order
     bool packed = false, intra_compact = false;
     bool bidir = false;                // tokens of one image also see the later tokens of that image
+    int32_t window = 0;                // > 0: a query at position i sees no key before i - window + 1
     int32_t Nc = 0, n_free = 0;
+    // first key position a query at position i may see
+    int32_t lo(int32_t i) const { return window > 0 ? std::max(0, i - window + 1) : 0; }
     std::vector<int32_t> ctext;        // n_free + 1: text keys among compact slots [0, s)
 
     const std::vector<int32_t> &free_count(int cls) const { return (cls & 1) ? n_free_sink : n_text; }
@@ -83,19 +86,26 @@ int tile_state(const Geometry &G, const QueryTile &qt, int cls, int32_t n)
 {
     const int32_t c0 = n * G.bn, c1 = std::min(c0 + G.bn, G.L);
     if (c0 > qt.e1 - 1) return 0;  // beyond what the last row sees
+    if (c1 - 1 < G.lo(qt.r0)) return 0;  // before the first row's window (and every later row's)
     const auto &sp = *G.spans;
     const auto &freec = G.free_count(cls);
 
+    // Every row i sees the keys of its class pattern inside [lo(i), e(i)]; both ends grow with i, so
+    // the rows of a run together see [lo(first), e(last)] and share [lo(last), e(first)].
     bool any = false;
-    if (cls == BS_DENSE || qt.last_text >= c0) {
+    if (cls == BS_DENSE || qt.segs.empty()) {
         any = true;
     } else {
+        // a text row at or after the tile's first key, close enough to see the tile's last key
+        const int32_t t = G.next_text[std::max(qt.r0, c0)];
+        if (t < qt.r1 && G.lo(t) <= c1 - 1) any = true;
         for (const Segment &s : qt.segs) {
-            int32_t hi = std::min(c1, s.eb);  // keys the segment's last row may see
-            if (hi <= c0) continue;
-            if (freec[hi] - freec[c0] > 0) { any = true; break; }
+            if (any) break;
+            const int32_t lo = std::max(c0, G.lo(s.a)), hi = std::min(c1, s.eb);  // keys the segment's rows may see
+            if (hi <= lo) continue;
+            if (freec[hi] - freec[lo] > 0) { any = true; break; }
             if (cls & 2) {
-                int32_t lo2 = std::max(c0, sp[s.g].start), hi2 = std::min(hi, sp[s.g].end);
+                int32_t lo2 = std::max(lo, sp[s.g].start), hi2 = std::min(hi, sp[s.g].end);
                 if (hi2 > lo2) { any = true; break; }
             }
         }
@@ -103,8 +113,8 @@ int tile_state(const Geometry &G, const QueryTile &qt, int cls, int32_t n)
     if (!any) return 0;
 
     bool all;
-    if (qt.ragged || (c1 - c0) < G.bn || c1 - 1 > qt.e0) {
-        all = false;  // masked out-of-range positions, or the diagonal cuts through
+    if (qt.ragged || (c1 - c0) < G.bn || c1 - 1 > qt.e0 || c0 < G.lo(qt.r1 - 1)) {
+        all = false;  // masked out-of-range positions, or the diagonal / the window's edge cuts through
     } else if (cls == BS_DENSE || qt.segs.empty()) {
         all = true;
     } else {
@@ -177,7 +187,13 @@ void build_run(const Geometry &G, int cls, const QueryTile &qt, std::vector<int3
     // key tiles wholly within what the first row of a complete query tile sees can be FULL
     const int32_t n_full_limit = qt.ragged ? 0 : (qt.e0 + 1) / G.bn;
 
-    if (cls == BS_DENSE || qt.segs.empty()) {
+    if (G.window > 0) {
+        // sliding window: few key tiles per query tile, each classified exactly
+        for (int32_t n = G.lo(qt.r0) / G.bn; n <= n_last; ++n) {
+            const int st = tile_state(G, qt, cls, n);
+            if (st) emit(n, n + 1, st);
+        }
+    } else if (cls == BS_DENSE || qt.segs.empty()) {
         // every earlier key is visible: FULL below the diagonal, PARTIAL on it
         emit(0, n_full_limit, 2);
         emit(n_full_limit, n_last + 1, 1);
@@ -368,18 +384,19 @@ void count_pairs(const Geometry &G, const std::vector<uint32_t> &code, ClassList
     int64_t pairs[4] = {0, 0, 0, 0}, empty[4] = {0, 0, 0, 0};
     size_t g = 0;
     for (int32_t i = 0; i < G.L; ++i) {
+        const int32_t lo = G.lo(i);   // first key position the row may see
         if (code[i] & bs::kCodeText) {
-            for (int c = 0; c < 4; ++c) pairs[c] += i + 1;
+            for (int c = 0; c < 4; ++c) pairs[c] += i + 1 - lo;
             continue;
         }
         while (sp[g].end <= i) ++g;
         const int32_t e = G.bidir ? sp[g].end - 1 : i;   // last key position the row may see
-        const int64_t text = G.n_text[e + 1];
-        const int64_t sink_img = G.n_free_sink[e + 1] - text;  // image tokens that are sinks, <= e
-        const int64_t own = e - sp[g].start + 1;
-        const int64_t own_sink = (G.n_free_sink[e + 1] - G.n_free_sink[sp[g].start]) -
-                                 (G.n_text[e + 1] - G.n_text[sp[g].start]);
-        const int64_t row[4] = {e + 1, text + sink_img, text + own, text + sink_img + own - own_sink};
+        const int32_t s0 = std::max(sp[g].start, lo);    // first own-image key it may see
+        const int64_t text = G.n_text[e + 1] - G.n_text[lo];
+        const int64_t sink_img = G.n_free_sink[e + 1] - G.n_free_sink[lo] - text;  // image tokens that are sinks, in [lo, e]
+        const int64_t own = e - s0 + 1;
+        const int64_t own_sink = (G.n_free_sink[e + 1] - G.n_free_sink[s0]) - (G.n_text[e + 1] - G.n_text[s0]);
+        const int64_t row[4] = {e + 1 - lo, text + sink_img, text + own, text + sink_img + own - own_sink};
         for (int c = 0; c < 4; ++c) {
             pairs[c] += row[c];
             if (row[c] == 0) ++empty[c];
@@ -414,15 +431,28 @@ extern "C" int bs_build_tilemap_ex(const bs_span *spans, int32_t n_spans, int32_
                                    int32_t block_m, int32_t block_n, uint32_t flags, bs_tilemap **out)
 {
     return bs_build_tilemap_model(spans, n_spans, seq_len, head_class, n_q_heads, sink_len, block_m, block_n, flags,
-                                  nullptr, 0, out);
+                                  nullptr, 0, 0, out);
 }
 
 extern "C" int bs_build_tilemap_model(const bs_span *spans, int32_t n_spans, int32_t seq_len,
                                       const uint8_t *head_class, int32_t n_q_heads, int32_t sink_len,
                                       int32_t block_m, int32_t block_n, uint32_t flags,
-                                      const int32_t *sink_offsets, int32_t n_sink_offsets, bs_tilemap **out)
+                                      const int32_t *sink_offsets, int32_t n_sink_offsets, int32_t window,
+                                      bs_tilemap **out)
 {
     if (flags & ~(uint32_t)(BS_MAP_REGROUP_ROWS | BS_MAP_PACK_KEYS | BS_MAP_BIDIR_IMAGES)) return BS_EINVAL;
+    if (window < 0) return BS_EINVAL;
+    if (window >= seq_len) window = 0;   // every earlier key is inside the window
+    if (window > 0 && (flags & BS_MAP_PACK_KEYS)) {
+        // a windowed query tile visits a few key tiles only: nothing to pack; the rows stay regrouped
+        flags = (flags & ~(uint32_t)BS_MAP_PACK_KEYS) | BS_MAP_REGROUP_ROWS;
+    }
+    if (window > 0 && (flags & BS_MAP_BIDIR_IMAGES)) {
+        // the own image stays visible at any distance; with images no longer than the window that
+        // is implied by the window itself, which is the case the map handles
+        for (int32_t g = 0; g < n_spans; ++g)
+            if (spans && spans[g].end - spans[g].start > window) return BS_EUNSUPPORTED;
+    }
     if (n_sink_offsets < 0 || (n_sink_offsets > 0 && !sink_offsets)) return BS_EINVAL;
     for (int32_t o = 0; o < n_sink_offsets; ++o)
         if (sink_offsets[o] < 0) return BS_EINVAL;
@@ -521,6 +551,7 @@ extern "C" int bs_build_tilemap_model(const bs_span *spans, int32_t n_spans, int
         Geometry G;
         G.L = L; G.bm = block_m; G.bn = block_n; G.M = tm->M; G.N = tm->N0; G.spans = &tm->spans;
         G.bidir = tm->bidir;
+        G.window = tm->window = window;
         G.n_text.assign(L + 1, 0);
         G.n_free_sink.assign(L + 1, 0);
         G.last_text.assign(L, -1);

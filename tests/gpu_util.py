@@ -16,7 +16,8 @@ def run_prefill(p, q, k, v, tm=None, stream=None, flags=0):
         if getattr(p, "img_bidir", False):
             flags |= bs.BS_MAP_BIDIR_IMAGES
         tm = bs.bs_build_tilemap(p.spans, p.seq_len, p.head_class, p.sink_len, 128, 64, flags=flags,
-                                 sink_offsets=getattr(p, "sink_offsets", None) or None)
+                                 sink_offsets=getattr(p, "sink_offsets", None) or None,
+                                 window=int(getattr(p, "window", 0)))
     out = torch.full_like(q, float("nan"))
     dt = bs.BS_BF16 if q.dtype == torch.bfloat16 else bs.BS_F32
     st = torch.cuda.current_stream().cuda_stream if stream is None else stream

@@ -37,8 +37,8 @@ def test_characterize_rejects_bad_arguments_before_touching_the_device():
     one = ctypes.c_void_p(256)
     ht = (ctypes.c_uint8 * 4)()
     f = lambda *a: lib.bs_characterize_prompt(*a)
-    ok = (one, one, one, None, 0, 300, 0, 0, 4, 2, 128, 0.1, 0.1, 0, None, 0, ht, None, None)
-    for pos, bad, want in ((0, None, -1), (1, None, -1), (2, None, -1), (16, None, -1), (5, 0, -1),
+    ok = (one, one, one, None, 0, 300, 0, 0, 4, 2, 128, 0.1, 0.1, 0, None, 0, 0, ht, None, None)
+    for pos, bad, want in ((0, None, -1), (1, None, -1), (2, None, -1), (17, None, -1), (5, 0, -1),
                            (8, 0, -1), (10, 0, -1), (12, float("nan"), -1), (7, 5, -2)):
         args = list(ok)
         args[pos] = bad

@@ -8,6 +8,8 @@ import oracle
 import paper_2507_09071_amd as bs
 import workloads as W
 from oracle import characterize as C
+from dataclasses import replace
+
 from test_gpu_parity import RUNS_A, full_parity, sampled_parity
 
 pytestmark = pytest.mark.gpu
@@ -80,3 +82,37 @@ def test_characterisation_with_bidirectional_images():
         if clear[:, h].all():
             assert got_type[h] == want_type[h], (h, got[:, h], want[:, h])
     assert clear.all(axis=0).sum() >= 6
+
+
+# --- sliding-window layers
+
+@pytest.mark.parametrize("dtype,d,flags,window", [("f32", 64, 0, 100), ("bf16", 128, 0, 100), ("bf16", 64, bs.BS_MAP_REGROUP_ROWS, 37),
+                                                  ("bf16", 128, bs.BS_MAP_PACK_KEYS, 200), ("bf16", 128, 0, 1),
+                                                  ("f32", 128, bs.BS_MAP_REGROUP_ROWS, 64)])
+def test_window_small_prompt_all_classes(dtype, d, flags, window):
+    p = W.custom_prompt(RUNS_A, [D, S, I, IS, IS, I, S, D], 4, d, dtype=dtype, sink_len=5,
+                        name=f"window{window}-{dtype}-d{d}-f{flags}", value_recipe={"std": 1.0, "first_key_scale": 4.0},
+                        window=window)
+    if dtype == "f32" and flags == bs.BS_MAP_PACK_KEYS:
+        pytest.skip("no packed maps for fp32")
+    full_parity(p, seed=21, flags=flags)
+
+
+def test_window_with_bidirectional_images():
+    runs = []
+    for i in range(24):
+        runs += [("I", 96), ("T", 1 + (i % 4))]
+    for window in (96, 250):
+        p = W.custom_prompt(runs, [S, I, IS, D, IS, S], 3, 128, dtype="bf16", sink_len=0, span_sink=0,
+                            name=f"bidir-window{window}", img_bidir=True, sink_offsets=(5, 17, 18, 70, 95), window=window)
+        full_parity(p, seed=22, flags=bs.BS_MAP_REGROUP_ROWS)
+
+
+def test_window_1024_on_the_gemma_like_config_sampled_rows():
+    p = replace(W.gemma3_bidir_config(0), window=1024, name="cfg6-window1024")
+    sampled_parity(p, 0, n_random=3, max_tiles=10, row_step=8, flags=bs.BS_MAP_REGROUP_ROWS)
+
+
+def test_window_4096_on_config2_sampled_rows():
+    p = replace(W.config(2), window=4096, name="cfg2-window4096")
+    sampled_parity(p, 0, n_random=3, max_tiles=10, row_step=4, flags=bs.BS_MAP_PACK_KEYS)

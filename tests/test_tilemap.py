@@ -21,16 +21,16 @@ def model_flags(bidir):
     return bs.BS_MAP_BIDIR_IMAGES if bidir else 0
 
 
-def check_against_oracle(spans, L, sink_len, bm, bn, q_tiles=None, pairs=True, bidir=False, offsets=None):
+def check_against_oracle(spans, L, sink_len, bm, bn, q_tiles=None, pairs=True, bidir=False, offsets=None, window=0):
     tm = bs.bs_build_tilemap(spans, L, np.zeros(1, np.uint8), sink_len, bm, bn, flags=model_flags(bidir),
-                             sink_offsets=offsets)
+                             sink_offsets=offsets, window=window)
     imgid, issink = oracle.token_arrays(spans, L, sink_len, offsets)
     for c in range(4):
         if q_tiles is None:
-            want = oracle.tile_states(c, imgid, issink, bm, bn, None, bidir)
+            want = oracle.tile_states(c, imgid, issink, bm, bn, None, bidir, window)
             got = tm.tile_states(c)
         else:
-            want = oracle.tile_states(c, imgid, issink, bm, bn, q_tiles, bidir)
+            want = oracle.tile_states(c, imgid, issink, bm, bn, q_tiles, bidir, window)
             got = np.stack([tm.tile_states(c, int(m), 1)[0] for m in q_tiles])
         assert np.array_equal(got, want), (c, np.argwhere(got != want)[:5])
         st = tm.stats(c)
@@ -39,10 +39,10 @@ def check_against_oracle(spans, L, sink_len, bm, bn, q_tiles=None, pairs=True, b
             assert st["full"] == int((want == 2).sum())
             assert st["partial"] == int((want == 1).sum())
         if pairs:
-            assert st["allowed_pairs"] == oracle.pair_count(c, imgid, issink, bidir)
+            assert st["allowed_pairs"] == oracle.pair_count(c, imgid, issink, bidir, window)
             m = None
             if L <= 2048:
-                m = oracle.mask(c, imgid, issink, bidir)
+                m = oracle.mask(c, imgid, issink, bidir, window)
                 assert st["empty_rows"] == int((~m.any(axis=1)).sum())
     return tm
 
@@ -112,11 +112,13 @@ def test_states_do_not_depend_on_head_classes():
 
 # ------------------------------------------------------------------------- regrouped query rows
 
-def check_regrouped(spans, L, sink_len, bm, bn, hc=None, q_tiles=None, bidir=False, offsets=None):
+def check_regrouped(spans, L, sink_len, bm, bn, hc=None, q_tiles=None, bidir=False, offsets=None, window=0,
+                    flags=None):
     """Map built with BS_MAP_REGROUP_ROWS against the oracle's reduction over the map's own row lists."""
     hc = np.zeros(1, np.uint8) if hc is None else hc
-    tm = bs.bs_build_tilemap(spans, L, hc, sink_len, bm, bn, flags=bs.BS_MAP_REGROUP_ROWS | model_flags(bidir),
-                             sink_offsets=offsets)
+    tm = bs.bs_build_tilemap(spans, L, hc, sink_len, bm, bn,
+                             flags=(bs.BS_MAP_REGROUP_ROWS if flags is None else flags) | model_flags(bidir),
+                             sink_offsets=offsets, window=window)
     imgid, issink = oracle.token_arrays(spans, L, sink_len, offsets)
     rows = tm.row_order(bm)
     # a permutation of the positions, image rows first, each group in position order
@@ -134,13 +136,13 @@ def check_regrouped(spans, L, sink_len, bm, bn, hc=None, q_tiles=None, bidir=Fal
         assert np.array_equal(rows.ravel()[:L], np.arange(L))
     sel = np.arange(tm.n_q_tiles) if q_tiles is None else np.asarray(q_tiles)
     for c in range(4):
-        want = oracle.tile_states_rows(c, imgid, issink, rows[sel], bn, bidir)
+        want = oracle.tile_states_rows(c, imgid, issink, rows[sel], bn, bidir, window)
         got = tm.tile_states(c) if q_tiles is None else np.stack([tm.tile_states(c, int(m), 1)[0] for m in sel])
         assert np.array_equal(got, want), (c, np.argwhere(got != want)[:5])
         st = tm.stats(c)
         if q_tiles is None:
             assert st["visited"] == int((want > 0).sum()) and st["full"] == int((want == 2).sum())
-        assert st["allowed_pairs"] == oracle.pair_count(c, imgid, issink, bidir)   # the grouping changes no pair
+        assert st["allowed_pairs"] == oracle.pair_count(c, imgid, issink, bidir, window)   # the grouping changes no pair
     return tm
 
 

@@ -95,7 +95,7 @@ def test_model_entry_point_rejects_bad_arguments():
     hc = (ctypes.c_uint8 * 1)(0)
     out = ctypes.c_void_p()
     off = (ctypes.c_int32 * 2)(1, -3)
-    f = lambda flags, o, n: lib.bs_build_tilemap_model(sp, 1, 20, hc, 1, 0, 4, 4, flags, o, n, ctypes.byref(out))
+    f = lambda flags, o, n: lib.bs_build_tilemap_model(sp, 1, 20, hc, 1, 0, 4, 4, flags, o, n, 0, ctypes.byref(out))
     assert f(0, off, 2) == -1          # negative offset
     assert f(0, None, 1) == -1         # count without a list
     assert f(0, off, -1) == -1
