@@ -38,6 +38,7 @@ def parse_args():
                     help="tile map layout: natural = query rows and keys in position order; regrouped = text "
                          "rows in query tiles of their own (BS_MAP_REGROUP_ROWS); packed = that plus compact "
                          "key tiles of text and sink keys for the sparse classes (BS_MAP_PACK_KEYS)")
+    ap.add_argument("--window", type=int, default=0, help="sliding window of the layer (0 = none)")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--sink-mode", default="paper10", choices=["paper10", "prefix"])
     ap.add_argument("--all-dense", action="store_true", help="run the same prompt with every head Dense")
@@ -120,7 +121,7 @@ def timed_steps(bs, torch, p, q, k, v, out, steps, warmup, hev, flags):
     def step(record):
         t0 = time.perf_counter()
         tm = bs.bs_build_tilemap(p.spans, p.seq_len, p.head_class, p.sink_len, 128, 64, flags=flags,
-                                 sink_offsets=p.sink_offsets or None)
+                                 sink_offsets=p.sink_offsets or None, window=p.window)
         t1 = time.perf_counter()
         e0 = torch.cuda.Event(enable_timing=True)
         e1 = torch.cuda.Event(enable_timing=True)
@@ -152,7 +153,7 @@ def timed_steps(bs, torch, p, q, k, v, out, steps, warmup, hev, flags):
     return wall * 1e3, kern_ms, call_ms, 1e3 * sum(build_s) / len(build_s), 1e3 * sum(call_s) / len(call_s), keep[-1]
 
 
-def sampled_pairs(head_class, rows, imgid, issink, img_bidir=False):
+def sampled_pairs(head_class, rows, imgid, issink, img_bidir=False, window=0):
     """Allowed pairs of the given query rows summed over the heads (plain enumeration)."""
     import numpy as np
     per_class_row = {}
@@ -163,14 +164,15 @@ def sampled_pairs(head_class, rows, imgid, issink, img_bidir=False):
             e = i   # last key position the row may see
             if img_bidir and imgid[i] != 0:
                 e = int(np.flatnonzero(imgid == imgid[i])[-1])
+            lo = max(0, i - window + 1) if window > 0 else 0   # first key position the row may see
             if imgid[i] == 0 or c == 0:
-                cnt += e + 1
+                cnt += e + 1 - lo
             else:
-                ok = imgid[: e + 1] == 0
+                ok = imgid[lo: e + 1] == 0
                 if c & 1:
-                    ok |= issink[: e + 1] == 1
+                    ok |= issink[lo: e + 1] == 1
                 if c & 2:
-                    ok |= imgid[: e + 1] == imgid[i]
+                    ok |= imgid[lo: e + 1] == imgid[i]
                 cnt += int(ok.sum())
         per_class_row[c] = cnt
     return sum(per_class_row[int(c)] for c in head_class)
@@ -190,15 +192,15 @@ def cpu_baseline(p, q, k, v, target_seconds):
     n_rows = 8
     rows = np.sort(rng.choice(p.seq_len, size=n_rows, replace=False)).astype(np.int32)
     t0 = time.perf_counter()
-    oracle.attention(qn, kn, vn, p.head_class, imgid, issink, p.scale, rows, p.img_bidir)
+    oracle.attention(qn, kn, vn, p.head_class, imgid, issink, p.scale, rows, p.img_bidir, p.window)
     t_probe = time.perf_counter() - t0
     n_rows = int(max(8, min(p.seq_len, n_rows * target_seconds / max(t_probe, 1e-3))))
     rows = np.sort(rng.choice(p.seq_len, size=n_rows, replace=False)).astype(np.int32)
     t0 = time.perf_counter()
-    oracle.attention(qn, kn, vn, p.head_class, imgid, issink, p.scale, rows, p.img_bidir)
+    oracle.attention(qn, kn, vn, p.head_class, imgid, issink, p.scale, rows, p.img_bidir, p.window)
     t = time.perf_counter() - t0
     # allowed pairs of the sampled rows, summed over heads (enumeration, outside the timed part)
-    pairs = sampled_pairs(p.head_class, rows, imgid, issink, p.img_bidir)
+    pairs = sampled_pairs(p.head_class, rows, imgid, issink, p.img_bidir, p.window)
     flops = 4.0 * p.head_dim * pairs
     return {"value": flops / t / 1e12, "unit": "TFLOP/s (useful, fp64 oracle)", "cores": oracle.num_threads(),
             "kind": "oracle", "seconds": round(t, 2),
@@ -214,7 +216,7 @@ def characterize_bench(args, bs, torch, p, q, k, v, flags):
     dt = bs.BS_BF16 if p.dtype == "bf16" else bs.BS_F32
     st = torch.cuda.current_stream().cuda_stream
     call = lambda: bs.bs_characterize_prompt(q, k, v, p.spans, p.seq_len, p.sink_len, dt, p.n_q_heads, p.gqa_group,
-                                              p.head_dim, p.scale, args.alpha, flags, st, p.sink_offsets or None)
+                                              p.head_dim, p.scale, args.alpha, flags, st, p.sink_offsets or None, p.window)
     for _ in range(args.warmup):
         call()
     torch.cuda.synchronize()
@@ -242,7 +244,7 @@ def characterize_bench(args, bs, torch, p, q, k, v, flags):
     pairs = []
     for c in range(4):
         tm = bs.bs_build_tilemap(p.spans, p.seq_len, np.full(p.n_q_heads, c, np.uint8), p.sink_len, 128, 64, flags=flags,
-                                 sink_offsets=p.sink_offsets or None)
+                                 sink_offsets=p.sink_offsets or None, window=p.window)
         pairs.append(tm.stats(c)["allowed_pairs"] * p.n_q_heads)
     flop = 4.0 * p.head_dim * sum(pairs)
     res = {
@@ -283,10 +285,10 @@ def characterize_cpu_baseline(p, q, k, v, pairs_per_mask, target_seconds):
         for c in range(4):
             hc = np.full(p.n_q_heads, c, np.uint8)
             t0 = time.perf_counter()
-            oracle.attention(qn, kn, vn, hc, imgid, issink, p.scale, rows, p.img_bidir)
+            oracle.attention(qn, kn, vn, hc, imgid, issink, p.scale, rows, p.img_bidir, p.window)
             t = time.perf_counter() - t0
             spent += t
-            total += t * pairs_per_mask[c] / max(1, sampled_pairs(hc, rows, imgid, issink, p.img_bidir))
+            total += t * pairs_per_mask[c] / max(1, sampled_pairs(hc, rows, imgid, issink, p.img_bidir, p.window))
         done = n_rows
         if attempt == 0:
             n_rows = int(max(4, min(p.seq_len, n_rows * target_seconds / max(spent, 1e-3))))
@@ -315,6 +317,9 @@ def main():
     p = W.config(args.config, args.seed, args.sink_mode, args.target_len)
     if args.all_dense:
         p = p.all_dense()
+    if args.window:
+        from dataclasses import replace
+        p = replace(p, window=args.window, name=p.name + "/window%d" % args.window)
     q, k, v = W.make_qkv(p, args.seed, "cuda:0")
     out = torch.empty_like(q)
     hev = HipEvents()
@@ -371,7 +376,7 @@ def main():
         "config": {"workload": p.name, "seq_len": p.seq_len, "n_q_heads": p.n_q_heads,
                    "n_kv_heads": p.n_kv_heads, "head_dim": d, "n_images": int(len(p.spans)),
                    "sink_mode": args.sink_mode if not p.sink_offsets else "%d in-image offsets" % len(p.sink_offsets),
-                   "image_attention": "bidirectional" if p.img_bidir else "causal",
+                   "image_attention": "bidirectional" if p.img_bidir else "causal", "window": p.window,
                    "seed": args.seed, "map": order,
                    "head_classes": {n: int((p.head_class == c).sum()) for c, n in enumerate(W.CLASS_NAMES)}},
         "kernel_ms": round(kern_ms, 4),
