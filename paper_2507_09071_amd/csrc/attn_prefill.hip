@@ -229,7 +229,7 @@ __device__ inline void apply_mask(floatx16 (&s)[2], uint64_t allowed, int hl)
 // hoist the 32 bit tests in front of the 32 selects (32 registers of pressure in a kernel that
 // has none to spare): the allowed bit is spread over a word (0 / all ones) and a bit-field
 // insert then keeps the score or takes -inf.
-__device__ inline void apply_mask_tight(floatx16 (&s)[2], uint64_t allowed, int hl)
+__device__ inline void apply_mask_tight(const floatx16 (&s)[2], floatx16 (&ms)[2], uint64_t allowed, int hl)
 {
     const uint32_t w[2] = {(uint32_t)allowed >> (4 * hl), (uint32_t)(allowed >> 32) >> (4 * hl)};
     const float ninf = -INFINITY;
@@ -237,11 +237,15 @@ __device__ inline void apply_mask_tight(floatx16 (&s)[2], uint64_t allowed, int 
     for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
         for (int v = 0; v < 16; ++v) {
+            // out of place: the masked scores go to registers of their own, so the scores (in/out
+            // operands of the matrix phase) are not copied first
             uint32_t t;
+            float r;
             asm("v_bfe_i32 %1, %2, %3, 1\n\t"
-                "v_bfi_b32 %0, %1, %0, %4"
-                : "+v"(s[kb][v]), "=&v"(t)
-                : "v"(w[kb]), "n"(8 * (v / 4) + (v % 4)), "v"(ninf));
+                "v_bfi_b32 %0, %1, %4, %5"
+                : "=v"(r), "=&v"(t)
+                : "v"(w[kb]), "n"(8 * (v / 4) + (v % 4)), "v"(s[kb][v]), "v"(ninf));
+            ms[kb][v] = r;
         }
 }
 
@@ -790,8 +794,9 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(
                     // image row over keys of another image): no per-score work
                     softmax_pack<1>(s, pf, m_run, l_run, alpha, a.scale_log2e, allowed == 0ull);
                 } else {
-                    apply_mask_tight(s, allowed, hl);
-                    softmax_pack<2>(s, pf, m_run, l_run, alpha, a.scale_log2e, false);
+                    floatx16 ms[2];
+                    apply_mask_tight(s, ms, allowed, hl);
+                    softmax_pack<2>(ms, pf, m_run, l_run, alpha, a.scale_log2e, false);
                 }
             }
             if (__any(alpha != 1.f)) {
