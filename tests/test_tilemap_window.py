@@ -10,7 +10,7 @@ import paper_2507_09071_amd as bs
 import workloads as W
 from golden_masks import full_fixtures, load_full
 from paper_2507_09071_amd import binding
-from test_tilemap import check_against_oracle, check_regrouped
+from test_tilemap import check_against_oracle, check_packed, check_regrouped
 from test_tilemap_model import random_layout
 
 
@@ -90,3 +90,23 @@ def test_negative_window_is_rejected():
     assert lib.bs_build_tilemap_model(sp, 1, 20, hc, 1, 0, 4, 4, 4, None, 0, 6, ctypes.byref(out)) == -2   # image of 7 > window
     assert lib.bs_build_tilemap_model(sp, 1, 20, hc, 1, 0, 4, 4, 4, None, 0, 7, ctypes.byref(out)) == 0
     lib.bs_tilemap_destroy(out)
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_all_options_together_on_random_prompts(seed):
+    """Every combination of map layout, image attention rule, offset sinks and window on one random
+    prompt each: the maps stay bit-exact against the oracle."""
+    rng = np.random.default_rng(7000 + seed)
+    L, spans, offsets, sink_len, bm, bn = random_layout(500 + seed, equal_images=seed % 3 == 0)
+    if not L:
+        return
+    longest = int((spans[:, 1] - spans[:, 0]).max()) if len(spans) else 1
+    for bidir in (False, True):
+        for window in (0, max(longest, int(rng.integers(1, 50)))):
+            if window >= L:
+                window = 0
+            check_against_oracle(spans, L, sink_len, bm, bn, bidir=bidir, offsets=offsets, window=window)
+            check_regrouped(spans, L, sink_len, bm, bn, bidir=bidir, offsets=offsets, window=window,
+                            flags=bs.BS_MAP_PACK_KEYS if window else None)
+            if not window:
+                check_packed(spans, L, sink_len, bm, bn, bidir=bidir, offsets=offsets)
