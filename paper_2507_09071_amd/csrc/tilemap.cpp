@@ -596,18 +596,43 @@ extern "C" int bs_build_tilemap_model(const bs_span *spans, int32_t n_spans, int
                 tm->span_free_range[2 * (g + 1) + 1] = G.n_free_sink[spans[g].end];
             }
         }
-        for (int c = 0; c < 4; ++c) build_class(G, c, tm->row_order, tm->cls[c]);
+        bool intra_close_call = false;
         if (tm->packed) {
             // Intra-Image rows need the text keys only.  Among the compact tiles they are mixed
             // with the sink keys; where text is rare (a few long images) the prompt's own tiles
-            // hold it in fewer tiles.  Both lists are exact: keep the shorter one.
-            G.intra_compact = true;
+            // hold it in fewer tiles.  Both lists are exact, so the choice is a matter of cost
+            // only: count, for the last row of every image, the tiles with a text key either
+            // way (prefix counts over the two tile spaces) and take the smaller total; a close
+            // call is settled below by building both.
+            std::vector<int32_t> prompt_tiles(tm->N0 + 1, 0), compact_tiles(G.Nc + 1, 0);
+            for (int32_t n = 0; n < tm->N0; ++n) {
+                const int32_t c0 = n * block_n, c1 = std::min(c0 + block_n, L);
+                prompt_tiles[n + 1] = prompt_tiles[n] + (G.n_text[c1] - G.n_text[c0] > 0);
+            }
+            for (int32_t c = 0; c < G.Nc; ++c) {
+                const int32_t s0 = c * block_n, s1 = std::min(s0 + block_n, G.n_free);
+                compact_tiles[c + 1] = compact_tiles[c] + (G.ctext[s1] - G.ctext[s0] > 0);
+            }
+            int64_t cost_prompt = 0, cost_compact = 0;
+            for (int32_t g = 0; g < n_spans; ++g) {
+                const int64_t rows = spans[g].end - spans[g].start;
+                cost_prompt += rows * prompt_tiles[(spans[g].end - 1) / block_n + 1];
+                cost_compact += rows * compact_tiles[(G.n_free_sink[spans[g].end] + block_n - 1) / block_n];
+            }
+            G.intra_compact = tm->intra_compact = cost_compact < cost_prompt;
+            intra_close_call = cost_compact * 4 >= cost_prompt * 3 && cost_prompt * 4 >= cost_compact * 3;
+        }
+        for (int c = 0; c < 4; ++c) build_class(G, c, tm->row_order, tm->cls[c]);
+        if (intra_close_call) {
+            // the estimate is within a quarter: build the other variant as well and keep the shorter list
             ClassLists alt;
+            G.intra_compact = !G.intra_compact;
             build_class(G, BS_INTRA, tm->row_order, alt);
             if (alt.visited < tm->cls[BS_INTRA].visited) {
                 tm->cls[BS_INTRA] = std::move(alt);
-                tm->intra_compact = true;
+                tm->intra_compact = G.intra_compact;
             }
+            G.intra_compact = tm->intra_compact;
         }
         count_pairs(G, tm->code, tm->cls);
 
