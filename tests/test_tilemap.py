@@ -113,7 +113,7 @@ def test_states_do_not_depend_on_head_classes():
 # ------------------------------------------------------------------------- regrouped query rows
 
 def check_regrouped(spans, L, sink_len, bm, bn, hc=None, q_tiles=None, bidir=False, offsets=None, window=0,
-                    flags=None):
+                    flags=None, pairs=True):
     """Map built with BS_MAP_REGROUP_ROWS against the oracle's reduction over the map's own row lists."""
     hc = np.zeros(1, np.uint8) if hc is None else hc
     tm = bs.bs_build_tilemap(spans, L, hc, sink_len, bm, bn,
@@ -142,7 +142,8 @@ def check_regrouped(spans, L, sink_len, bm, bn, hc=None, q_tiles=None, bidir=Fal
         st = tm.stats(c)
         if q_tiles is None:
             assert st["visited"] == int((want > 0).sum()) and st["full"] == int((want == 2).sum())
-        assert st["allowed_pairs"] == oracle.pair_count(c, imgid, issink, bidir, window)   # the grouping changes no pair
+        if pairs:   # by enumeration: quadratic in the prompt length
+            assert st["allowed_pairs"] == oracle.pair_count(c, imgid, issink, bidir, window)   # the grouping changes no pair
     return tm
 
 
@@ -186,12 +187,13 @@ def test_regrouped_large_configs_sampled(cfg):
     M = probe.n_q_tiles
     n_img_tiles = -(-int(sum(e - s for s, e, _ in p.spans)) // 128)
     sel = sorted({0, 1, n_img_tiles // 2, n_img_tiles - 1, n_img_tiles, M - 1})   # both groups and their ragged ends
-    tm = check_regrouped(p.spans, p.seq_len, p.sink_len, 128, 64, p.head_class, sel)
+    tm = check_regrouped(p.spans, p.seq_len, p.sink_len, 128, 64, p.head_class, sel, pairs=(cfg == 2))
     tm.pair_plan(p.gqa_group)   # validates every unit against the per-class lists
     # the point of the grouping: the sparse classes visit fewer key tiles than in the natural order
     nat = bs.bs_build_tilemap(p.spans, p.seq_len, p.head_class, p.sink_len)
     for c in (1, 2, 3):
         assert tm.stats(c)["visited"] < nat.stats(c)["visited"]
+        assert tm.stats(c)["allowed_pairs"] == nat.stats(c)["allowed_pairs"]   # the grouping changes no pair
 
 
 def test_regroup_flag_without_effect_and_bad_flags():
