@@ -460,6 +460,16 @@ __device__ inline unsigned long long bs_now(floatx16 &a, floatx16 &b, floatx16 &
     asm volatile("s_memtime %0\n\ts_waitcnt lgkmcnt(0)" : "=s"(t));
     return t;
 }
+// per work unit: kernel entry -> query metadata loaded -> first loop barrier, the loop, loop -> stores done
+__device__ unsigned long long g_unit_cycles[4];
+__device__ inline unsigned long long bs_stamp()
+{
+    unsigned long long t;
+    asm volatile("s_memtime %0\n\ts_waitcnt lgkmcnt(0)" : "=s"(t)::"memory");
+    return t;
+}
+#define BS_U(i) do { const unsigned long long t_ = bs_stamp(); bs_u[i] = t_ - bs_ut; bs_ut = t_; } while (0)
+#define BS_UFLUSH() do { if (tid == 0) for (int i = 0; i < 4; ++i) atomicAdd(&g_unit_cycles[i], bs_u[i]); } while (0)
 #define BS_T0() unsigned long long bs_acc[4] = {0, 0, 0, 0}; unsigned long long bs_t0 = bs_now(s[0], s[1], o[0])
 #define BS_TICK(slot)                                                                  \
     do {                                                                               \
@@ -473,6 +483,8 @@ __device__ inline unsigned long long bs_now(floatx16 &a, floatx16 &b, floatx16 &
             for (int i = 0; i < 4; ++i) atomicAdd(&g_phase_cycles[i + 4 * (tid >> 8)], bs_acc[i]); \
     } while (0)
 #else
+#define BS_U(i) do {} while (0)
+#define BS_UFLUSH() do {} while (0)
 #define BS_T0() do {} while (0)
 #define BS_TICK(slot) do {} while (0)
 #define BS_TFLUSH() do {} while (0)
@@ -545,6 +557,9 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(
     extern __shared__ __align__(1024) unsigned char lds[];   // K slots 0..3, then V^T slots 0..3
 
     const int tid = threadIdx.x, lane = tid & 63, hl = lane >> 5, col = lane & 31;
+#ifdef BS_PHASE_TIMING
+    unsigned long long bs_u[4] = {0, 0, 0, 0}, bs_ut = bs_stamp();
+#endif
     const int grp = __builtin_amdgcn_readfirstlane(tid >> 8);          // wave group 0 / 1
     const int wave = __builtin_amdgcn_readfirstlane((tid >> 6) & 3);   // wave within the group
     const int wave8 = __builtin_amdgcn_readfirstlane(tid >> 6);        // wave within the workgroup
@@ -580,6 +595,10 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(
     }
     QueryView qv;
     qv.init(map_code, map_span_range, map_free_before, map_span_free, L, cls, row, a.packed != 0, a.intra_compact != 0, a.bidir != 0, a.window);
+#ifdef BS_PHASE_TIMING
+    asm volatile("" ::"v"(qreg[0]), "v"(qv.row), "v"(qv.own_hi), "v"(qv.free_bound), "v"(qv.cfree_hi));   // the metadata has arrived
+    BS_U(0);
+#endif
 
     // LDS byte address of this lane's MFMA operand fragments inside a K / V^T tile (see the
     // tile layouts above): key or channel `col`, half hl; slices, blocks and groups are
@@ -858,6 +877,7 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(
     // V^T(k) and written at K(k+3), V^T(k+2), whose slots (of K(k-1), V^T(k-2)) nobody reads
     // after barrier k; a tile written in one interval is waited for (vmcnt) in the next and
     // read in the one after: four slots each.
+    BS_U(1);
     BS_T0();
     if (grp == 0) {
         for (int k = 0, slot = 0; k < n_steps; ++k) {
@@ -881,6 +901,7 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(
         }
     }
     BS_TFLUSH();
+    BS_U(2);
 
     // epilogue: divide by the running sum, round, store.  Empty rows (l = 0) give zeros.
     const float l_tot = sum_across_halves(l_run);
@@ -897,6 +918,11 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(
                 *reinterpret_cast<bf16x4 *>(orow + 32 * db + 8 * g + 4 * hl) = w;
             }
     }
+#ifdef BS_PHASE_TIMING
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    BS_U(3);
+    BS_UFLUSH();
+#endif
 }
 
 // ------------------------------------------------------------------------------------ fp32
@@ -1387,12 +1413,14 @@ extern "C" int bs_attn_prefill_ex(const void *q, const void *k, const void *v, v
 extern "C" const char *bs_last_error(void) { return bs::g_last_error; }
 
 #ifdef BS_PHASE_TIMING
-extern "C" int bs_debug_phase_cycles(unsigned long long *out8, int reset)
+extern "C" int bs_debug_phase_cycles(unsigned long long *out8, int reset)   // out8: 12 values
 {
     if (hipMemcpyFromSymbol(out8, HIP_SYMBOL(bs::g_phase_cycles), 64) != hipSuccess) return BS_EHIP;
+    if (hipMemcpyFromSymbol(out8 + 8, HIP_SYMBOL(bs::g_unit_cycles), 32) != hipSuccess) return BS_EHIP;
     if (reset) {
         unsigned long long z[8] = {0, 0, 0, 0, 0, 0, 0, 0};
         if (hipMemcpyToSymbol(HIP_SYMBOL(bs::g_phase_cycles), z, 64) != hipSuccess) return BS_EHIP;
+        if (hipMemcpyToSymbol(HIP_SYMBOL(bs::g_unit_cycles), z, 32) != hipSuccess) return BS_EHIP;
     }
     return BS_OK;
 }
