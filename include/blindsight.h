@@ -100,7 +100,7 @@ int bs_build_tilemap(const bs_span *spans, int32_t n_spans, int32_t seq_len,
  *       the text slots; Intra-Image+Sink: the slots outside its own image) plus, for the classes
  *       with the intra bit, the prompt tiles of its own image, in which only own-image keys count.
  *       Every allowed pair is still counted exactly once.  bs_tilemap_key_order reports the key
- *       of every tile slot.  bf16 only (the fp32 kernel returns BS_EUNSUPPORTED for such a map).
+ *       of every tile slot.
  *       No effect on a prompt without images, without free keys, or made of free keys only. */
 #define BS_MAP_PACK_KEYS 2u
 /*   BS_MAP_BIDIR_IMAGES   model variant in which the tokens of one image attend to each other in
@@ -246,9 +246,8 @@ int bs_attn_prefill_ex(const void *q, const void *k, const void *v, void *out, b
  *   q, k, v      device pointers, layouts as for bs_attn_prefill; spans / seq_len / sink_len as for
  *                bs_build_tilemap (host)
  *   alpha        the layer's threshold alpha_layer (the paper recommends 0.1 for Qwen-type models)
- *   map_flags    options for the four tile maps the call builds (BS_MAP_*; dtype BS_F32 needs a map
- *                without packed keys); sink_offsets / n_sink_offsets / window as for
- *                bs_build_tilemap_model
+ *   map_flags    options for the four tile maps the call builds (BS_MAP_*); sink_offsets /
+ *                n_sink_offsets / window as for bs_build_tilemap_model
  *   head_type    host, n_q_heads values out (bs_head_class)
  *   nmse         host, [3][n_q_heads] out, row m = mask m + 1; may be NULL.  All three masks are
  *                evaluated for every head (Alg. 1 stops at the first that passes, which only saves

@@ -100,8 +100,9 @@ struct KernelArgs {
         const uint64_t *__restrict__ map_sink_bits, const int2 *__restrict__ map_span_range,       \
         const int32_t *__restrict__ map_row_ptr, const int2 *__restrict__ map_ranges,              \
         const int2 *__restrict__ map_work, const uint8_t *__restrict__ map_head_class,             \
-        const int32_t *__restrict__ map_row_order
-#define BS_MAP_ARGS(d) (d)->code, (d)->text_bits, (d)->sink_bits, (d)->span_range, (d)->row_ptr, (d)->ranges, (d)->work, (d)->head_class, (d)->row_order
+        const int32_t *__restrict__ map_row_order, const int32_t *__restrict__ map_key_order,      \
+        const int32_t *__restrict__ map_free_before, const int2 *__restrict__ map_span_free
+#define BS_MAP_ARGS(d) (d)->code, (d)->text_bits, (d)->sink_bits, (d)->span_range, (d)->row_ptr, (d)->ranges, (d)->work, (d)->head_class, (d)->row_order, (d)->key_order, (d)->free_before, (d)->span_free
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
@@ -927,7 +928,8 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(
 
 // ------------------------------------------------------------------------------------ fp32
 // Same structure with fp32 MFMA (32x32x2) end to end; P stays fp32.  Parity path for fp32
-// inputs, not tuned.  Dynamic LDS: K[64][D+1] floats, V[64][D+8] floats.
+// inputs, not tuned: K / V tiles are gathered from the caller's arrays through key_order (no
+// pre-pass).  Dynamic LDS: K[64][D+1] floats, V[64][D+8] floats.
 
 template <int D>
 __global__ __launch_bounds__(kThreads, 1) void attn_prefill_f32(KernelArgs a, BS_MAP_PARAMS)
@@ -957,7 +959,8 @@ __global__ __launch_bounds__(kThreads, 1) void attn_prefill_f32(KernelArgs a, BS
         for (int t = 0; t < D / 2; ++t) qreg[t] = qh[(size_t)qrow * D + 2 * t + hl];
     }
     QueryView qv;
-    qv.init(map_code, map_span_range, nullptr, nullptr, a.L, cls, row, false, false, a.bidir != 0, a.window);
+    qv.init(map_code, map_span_range, map_free_before, map_span_free, a.L, cls, row, a.packed != 0, a.intra_compact != 0,
+            a.bidir != 0, a.window);
 
     floatx16 o[D / 32];
 #pragma unroll
@@ -970,11 +973,12 @@ __global__ __launch_bounds__(kThreads, 1) void attn_prefill_f32(KernelArgs a, BS
     tw.init(map_ranges, map_row_ptr[cls * (a.M + 1) + m], map_row_ptr[cls * (a.M + 1) + m + 1]);
 
     for (; tw.valid(); tw.next()) {
-        const int n0 = tw.n * kBlockN;
         __syncthreads();
         for (int idx = tid; idx < kBlockN * (D / 4); idx += kThreads) {
             const int key = idx / (D / 4), ch = idx % (D / 4);
-            const int grow = min(n0 + key, L - 1);
+            // the key this slot of the tile holds (a compact tile of a packed map gathers free keys);
+            // a slot without a key is masked below, any finite values will do for it
+            const int grow = max(map_key_order[tw.n * kBlockN + key], 0);
             const floatx4 kk = *reinterpret_cast<const floatx4 *>(kh + (size_t)grow * D + ch * 4);
             const floatx4 vv = *reinterpret_cast<const floatx4 *>(vh + (size_t)grow * D + ch * 4);
 #pragma unroll
@@ -1325,7 +1329,6 @@ extern "C" int bs_attn_prefill_ex(const void *q, const void *k, const void *v, v
     a.intra_compact = tm->intra_compact;
     a.bidir = tm->bidir;
     a.window = tm->window;
-    if (tm->packed && dtype != BS_BF16) return BS_EUNSUPPORTED;   // the fp32 kernel reads K / V in place
 
     const dim3 grid((unsigned)d->n_work), block(bs::kThreads);
     if (dtype == BS_BF16) {

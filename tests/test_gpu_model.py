@@ -18,7 +18,7 @@ DEV = "cuda:0"
 OFFSETS = (0, 3, 64, 65, 129, 299, 400)
 
 
-@pytest.mark.parametrize("dtype,d,flags", [("f32", 64, 0), ("f32", 128, bs.BS_MAP_REGROUP_ROWS), ("bf16", 128, 0),
+@pytest.mark.parametrize("dtype,d,flags", [("f32", 64, 0), ("f32", 128, bs.BS_MAP_REGROUP_ROWS), ("f32", 64, bs.BS_MAP_PACK_KEYS), ("bf16", 128, 0),
                                            ("bf16", 64, bs.BS_MAP_REGROUP_ROWS), ("bf16", 128, bs.BS_MAP_PACK_KEYS),
                                            ("bf16", 64, bs.BS_MAP_PACK_KEYS)])
 def test_bidirectional_small_prompt_all_classes(dtype, d, flags):
@@ -93,8 +93,6 @@ def test_window_small_prompt_all_classes(dtype, d, flags, window):
     p = W.custom_prompt(RUNS_A, [D, S, I, IS, IS, I, S, D], 4, d, dtype=dtype, sink_len=5,
                         name=f"window{window}-{dtype}-d{d}-f{flags}", value_recipe={"std": 1.0, "first_key_scale": 4.0},
                         window=window)
-    if dtype == "f32" and flags == bs.BS_MAP_PACK_KEYS:
-        pytest.skip("no packed maps for fp32")
     full_parity(p, seed=21, flags=flags)
 
 

@@ -191,11 +191,11 @@ def test_packed_long_images_prefix_sinks():
     full_parity(p, seed=10, flags=bs.BS_MAP_PACK_KEYS)
 
 
-def test_packed_fp32_is_rejected():
-    p = W.custom_prompt(RUNS_A, [D, S, I, IS], 2, 64, dtype="f32")
-    q, k, v = W.make_qkv(p, 1, DEV)
-    with pytest.raises(bs.BlindsightError):
-        run_prefill(p, q, k, v, flags=bs.BS_MAP_PACK_KEYS)
+@pytest.mark.parametrize("d", [64, 128])
+def test_packed_fp32(d):
+    p = W.custom_prompt(RUNS_A, [D, S, I, IS, I, IS], 2, d, dtype="f32", sink_len=5, name=f"packed-f32-d{d}",
+                        value_recipe={"std": 1.0, "first_key_scale": 4.0})
+    full_parity(p, seed=1, flags=bs.BS_MAP_PACK_KEYS)
 
 
 @pytest.mark.parametrize("cfg", [2, 4])
