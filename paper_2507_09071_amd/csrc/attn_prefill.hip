@@ -480,6 +480,7 @@ __device__ inline unsigned long long bs_stamp()
     } while (0)
 #define BS_TFLUSH()                                                                    \
     do {                                                                               \
+        bs_acc[3] = bs_vm_wait;   /* slot 3: waiting for tile loads, part of slot 0 */ \
         if (tid == 0 || tid == 256)                                                    \
             for (int i = 0; i < 4; ++i) atomicAdd(&g_phase_cycles[i + 4 * (tid >> 8)], bs_acc[i]); \
     } while (0)
@@ -559,7 +560,7 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(
 
     const int tid = threadIdx.x, lane = tid & 63, hl = lane >> 5, col = lane & 31;
 #ifdef BS_PHASE_TIMING
-    unsigned long long bs_u[4] = {0, 0, 0, 0}, bs_ut = bs_stamp();
+    unsigned long long bs_u[4] = {0, 0, 0, 0}, bs_ut = bs_stamp(), bs_vm_wait = 0;
 #endif
     const int grp = __builtin_amdgcn_readfirstlane(tid >> 8);          // wave group 0 / 1
     const int wave = __builtin_amdgcn_readfirstlane((tid >> 6) & 3);   // wave within the group
@@ -780,7 +781,13 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(
         // Wait for the loads issued one step ago (only this step's may stay in flight): after
         // the next barrier every wave has passed this wait, and the tile is read in the interval
         // that follows it.
+#ifdef BS_PHASE_TIMING
+        const unsigned long long tw0 = bs_stamp();
+#endif
         asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * DMA_PER_WAVE));
+#ifdef BS_PHASE_TIMING
+        bs_vm_wait += bs_stamp() - tw0;   // time spent waiting for the tile loads of the previous step
+#endif
     };
 
     // text / sink key bits of the tile w0 names (scalar registers, fetched one step ahead)
