@@ -114,3 +114,36 @@ def test_window_1024_on_the_gemma_like_config_sampled_rows():
 def test_window_4096_on_config2_sampled_rows():
     p = replace(W.config(2), window=4096, name="cfg2-window4096")
     sampled_parity(p, 0, n_random=3, max_tiles=10, row_step=4, flags=bs.BS_MAP_PACK_KEYS)
+
+
+# --- every option combined, random small prompts
+
+@pytest.mark.parametrize("seed", range(16))
+def test_random_prompts_random_options(seed):
+    rng = np.random.default_rng(9100 + seed)
+    runs = [("T", int(rng.integers(0, 50)))]
+    size = int(rng.integers(40, 400))
+    equal = bool(rng.integers(0, 2))
+    for _ in range(int(rng.integers(1, 7))):
+        runs.append(("I", size if equal else int(rng.integers(20, 500))))
+        if rng.random() < 0.85:
+            runs.append(("T", int(rng.integers(1, 40))))
+    if sum(n for _, n in runs) == 0:
+        runs = [("T", 5)]
+    dtype = ["bf16", "bf16", "f32"][seed % 3]
+    d = [128, 64][(seed // 3) % 2]
+    n_kv = int(rng.integers(1, 3))
+    G = int(rng.integers(1, 4))
+    classes = rng.integers(0, 4, size=n_kv * G)
+    bidir = bool(rng.integers(0, 2))
+    longest = max(n for kind, n in runs if kind == "I")
+    window = [0, 0, int(rng.integers(longest, longest + 300)), int(rng.integers(1, 200))][int(rng.integers(0, 4))]
+    if bidir and 0 < window < longest:
+        window = longest
+    offsets = tuple(sorted(set(int(o) for o in rng.integers(0, 300, size=int(rng.integers(0, 8))))))
+    flags = [0, bs.BS_MAP_REGROUP_ROWS, bs.BS_MAP_PACK_KEYS][int(rng.integers(0, 3))]
+    p = W.custom_prompt(runs, classes, n_kv, d, dtype=dtype, sink_len=int(rng.integers(0, 8)),
+                        sink_mode=["paper10", "prefix"][int(rng.integers(0, 2))], span_sink=[None, 0, 7][int(rng.integers(0, 3))],
+                        name=f"rand{seed}-{dtype}-d{d}-f{flags}-w{window}-b{int(bidir)}",
+                        value_recipe={"std": 1.0, "first_key_scale": 3.0}, img_bidir=bidir, sink_offsets=offsets, window=window)
+    full_parity(p, seed=seed, flags=flags)
