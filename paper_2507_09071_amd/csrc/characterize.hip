@@ -16,6 +16,7 @@
 #include <cmath>
 #include <cstdint>
 #include <cstdio>
+#include <new>
 #include <vector>
 
 #include "blindsight.h"
@@ -206,7 +207,12 @@ extern "C" int bs_characterize_prompt(const void *q, const void *k, const void *
 
     int rc = BS_OK;
     hipLaunchKernelGGL(fill_zero, dim3((6 * n_q_heads + 255) / 256), dim3(256), 0, st, b.sums, 6 * n_q_heads);
-    std::vector<uint8_t> cls(n_q_heads);
+    std::vector<uint8_t> cls;
+    try {
+        cls.resize(n_q_heads);
+    } catch (const std::bad_alloc &) {
+        return BS_ENOMEM;   // nothing queued yet beyond the clearing kernel; the buffers are freed (hipFree waits)
+    }
     for (int c = 0; c < 4 && rc == BS_OK; ++c) {   // Dense reference, then Sink, Intra-Image, Intra-Image+Sink
         std::fill(cls.begin(), cls.end(), (uint8_t)c);
         bs_tilemap *tm = nullptr;
