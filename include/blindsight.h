@@ -289,6 +289,17 @@ int bs_head_sq_error(const void *attn_mask, const void *attn_ref, int32_t dtype,
  */
 int bs_aggregate_head_type(const double *fraction, double gamma_d, double gamma_s, double gamma_i);
 
+/*
+ * Alg. 2 for all heads of a layer, from the prompt-level results: head_types (host) is
+ * [n_prompts][n_q_heads], one row per characterised prompt as bs_characterize_prompt returned it.
+ * Counts, per head, the share of prompts that chose each class (the head_type_fraction of Alg. 2;
+ * written to fraction[n_q_heads][4] if non-NULL) and applies bs_aggregate_head_type to it:
+ * head_class[n_q_heads] (host) is the class vector to pass to bs_build_tilemap for this layer.
+ * Host only.  Errors: BS_EINVAL (null pointers, non-positive counts, a type above 3).
+ */
+int bs_aggregate_layer(const uint8_t *head_types, int32_t n_prompts, int32_t n_q_heads, double gamma_d,
+                       double gamma_s, double gamma_i, uint8_t *head_class, double *fraction);
+
 /* Static description of an error code. */
 const char *bs_strerror(int code);
 

@@ -19,7 +19,7 @@ DENSE, SINK, INTRA, INTRA_SINK = 0, 1, 2, 3
 
 EXPORTS = ("bs_build_tilemap", "bs_build_tilemap_ex", "bs_build_tilemap_model", "bs_tilemap_destroy", "bs_tilemap_dims", "bs_tilemap_row_order", "bs_tilemap_layout", "bs_tilemap_key_order", "bs_tilemap_tile_states",
            "bs_tilemap_stats", "bs_tilemap_pair_plan", "bs_tilemap_upload", "bs_attn_prefill", "bs_attn_prefill_ex",
-           "bs_characterize_prompt", "bs_head_sq_error", "bs_aggregate_head_type", "bs_strerror",
+           "bs_characterize_prompt", "bs_head_sq_error", "bs_aggregate_head_type", "bs_aggregate_layer", "bs_strerror",
            "bs_last_error")
 
 
@@ -104,6 +104,8 @@ def load_library():
     lib.bs_head_sq_error.restype = ctypes.c_int
     lib.bs_aggregate_head_type.argtypes = [f64p, f64, f64, f64]
     lib.bs_aggregate_head_type.restype = ctypes.c_int
+    lib.bs_aggregate_layer.argtypes = [u8p, i32, i32, f64, f64, f64, u8p, f64p]
+    lib.bs_aggregate_layer.restype = ctypes.c_int
     lib.bs_strerror.argtypes = [ctypes.c_int]
     lib.bs_strerror.restype = ctypes.c_char_p
     lib.bs_last_error.argtypes = []
@@ -295,3 +297,19 @@ def bs_aggregate_head_type(fraction, gamma_d: float, gamma_s: float, gamma_i: fl
     if rc < 0:
         _check(rc, "bs_aggregate_head_type")
     return rc
+
+
+def bs_aggregate_layer(head_types, gamma_d: float, gamma_s: float, gamma_i: float):
+    """Alg. 2 for a layer: head_types uint8 [n_prompts, n_q_heads] -> (head_class uint8 [n_q_heads],
+    fraction float64 [n_q_heads, 4])."""
+    t = np.ascontiguousarray(head_types, dtype=np.uint8)
+    if t.ndim != 2:
+        raise ValueError("head_types must be [n_prompts, n_q_heads]")
+    out = np.zeros(t.shape[1], dtype=np.uint8)
+    frac = np.zeros((t.shape[1], 4), dtype=np.float64)
+    rc = load_library().bs_aggregate_layer(t.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8)), t.shape[0], t.shape[1],
+                                           float(gamma_d), float(gamma_s), float(gamma_i),
+                                           out.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8)),
+                                           frac.ctypes.data_as(ctypes.POINTER(ctypes.c_double)))
+    _check(rc, "bs_aggregate_layer")
+    return out, frac

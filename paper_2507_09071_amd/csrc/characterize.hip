@@ -246,3 +246,21 @@ extern "C" int bs_aggregate_head_type(const double *fraction, double gamma_d, do
     if (fraction[BS_INTRA] > gamma_i) return BS_INTRA;
     return BS_INTRA_SINK;
 }
+
+extern "C" int bs_aggregate_layer(const uint8_t *head_types, int32_t n_prompts, int32_t n_q_heads, double gamma_d,
+                                  double gamma_s, double gamma_i, uint8_t *head_class, double *fraction)
+{
+    if (!head_types || !head_class || n_prompts <= 0 || n_q_heads <= 0) return BS_EINVAL;
+    for (int64_t i = 0; i < (int64_t)n_prompts * n_q_heads; ++i)
+        if (head_types[i] > 3) return BS_EINVAL;
+    for (int32_t h = 0; h < n_q_heads; ++h) {
+        int64_t count[4] = {0, 0, 0, 0};
+        for (int32_t p = 0; p < n_prompts; ++p) ++count[head_types[(int64_t)p * n_q_heads + h]];
+        double f[4];
+        for (int c = 0; c < 4; ++c) f[c] = (double)count[c] / (double)n_prompts;
+        if (fraction)
+            for (int c = 0; c < 4; ++c) fraction[4 * h + c] = f[c];
+        head_class[h] = (uint8_t)bs_aggregate_head_type(f, gamma_d, gamma_s, gamma_i);
+    }
+    return BS_OK;
+}

@@ -32,6 +32,22 @@ def test_aggregation_matches_oracle_on_a_grid_of_fractions():
     assert binding.load_library().bs_aggregate_head_type(None, 0.25, 0.6, 0.6) == -1
 
 
+def test_layer_aggregation_matches_oracle():
+    rng = np.random.default_rng(4)
+    for n_prompts, heads in ((1, 3), (7, 5), (40, 28), (100, 8)):
+        # skewed draws, so that every branch of Alg. 2 is taken by some head
+        weights = rng.dirichlet([0.4, 0.4, 0.4, 0.4], size=heads)
+        t = np.stack([rng.choice(4, size=n_prompts, p=w) for w in weights], axis=1).astype(np.uint8)
+        for g in ((0.25, 0.6, 0.6), (0.1, 0.3, 0.5)):
+            got, frac = bs.bs_aggregate_layer(t, *g)
+            want_frac = C.head_type_fraction(t)
+            assert np.array_equal(frac, want_frac)
+            assert list(got) == [C.aggregate(want_frac[h], *g) for h in range(heads)]
+    assert len(set(got)) >= 3
+    with pytest.raises(bs.BlindsightError):
+        bs.bs_aggregate_layer(np.full((2, 2), 4, np.uint8), 0.25, 0.6, 0.6)
+
+
 def test_characterize_rejects_bad_arguments_before_touching_the_device():
     lib = binding.load_library()
     one = ctypes.c_void_p(256)
