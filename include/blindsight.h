@@ -300,6 +300,15 @@ int bs_aggregate_head_type(const double *fraction, double gamma_d, double gamma_
 int bs_aggregate_layer(const uint8_t *head_types, int32_t n_prompts, int32_t n_q_heads, double gamma_d,
                        double gamma_s, double gamma_i, uint8_t *head_class, double *fraction);
 
+/*
+ * The layer threshold of Alg. 1 under the paper's linear schedule (App. "Impact of Linear alpha_layer
+ * for Gemma 3"): alpha_first + (alpha_last - alpha_first) * layer_idx / num_layers, which keeps the
+ * first layers denser.  The paper uses 0.005 .. 0.195 for Gemma 3 (12B), 0.001 .. 0.099 for Gemma 3 (4B)
+ * and a fixed 0.1 (alpha_first = alpha_last) for the Qwen-type models.  Host only.  NaN for
+ * num_layers <= 0 or layer_idx outside [0, num_layers].
+ */
+double bs_alpha_layer(double alpha_first, double alpha_last, int32_t layer_idx, int32_t num_layers);
+
 /* Static description of an error code. */
 const char *bs_strerror(int code);
 

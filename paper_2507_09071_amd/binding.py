@@ -19,7 +19,7 @@ DENSE, SINK, INTRA, INTRA_SINK = 0, 1, 2, 3
 
 EXPORTS = ("bs_build_tilemap", "bs_build_tilemap_ex", "bs_build_tilemap_model", "bs_tilemap_destroy", "bs_tilemap_dims", "bs_tilemap_row_order", "bs_tilemap_layout", "bs_tilemap_key_order", "bs_tilemap_tile_states",
            "bs_tilemap_stats", "bs_tilemap_pair_plan", "bs_tilemap_upload", "bs_attn_prefill", "bs_attn_prefill_ex",
-           "bs_characterize_prompt", "bs_head_sq_error", "bs_aggregate_head_type", "bs_aggregate_layer", "bs_strerror",
+           "bs_characterize_prompt", "bs_head_sq_error", "bs_aggregate_head_type", "bs_aggregate_layer", "bs_alpha_layer", "bs_strerror",
            "bs_last_error")
 
 
@@ -106,6 +106,8 @@ def load_library():
     lib.bs_aggregate_head_type.restype = ctypes.c_int
     lib.bs_aggregate_layer.argtypes = [u8p, i32, i32, f64, f64, f64, u8p, f64p]
     lib.bs_aggregate_layer.restype = ctypes.c_int
+    lib.bs_alpha_layer.argtypes = [f64, f64, i32, i32]
+    lib.bs_alpha_layer.restype = ctypes.c_double
     lib.bs_strerror.argtypes = [ctypes.c_int]
     lib.bs_strerror.restype = ctypes.c_char_p
     lib.bs_last_error.argtypes = []
@@ -313,3 +315,8 @@ def bs_aggregate_layer(head_types, gamma_d: float, gamma_s: float, gamma_i: floa
                                            frac.ctypes.data_as(ctypes.POINTER(ctypes.c_double)))
     _check(rc, "bs_aggregate_layer")
     return out, frac
+
+
+def bs_alpha_layer(alpha_first: float, alpha_last: float, layer_idx: int, num_layers: int) -> float:
+    """Linear alpha_layer schedule of the paper (fixed threshold when both ends are equal)."""
+    return float(load_library().bs_alpha_layer(float(alpha_first), float(alpha_last), int(layer_idx), int(num_layers)))

@@ -264,3 +264,9 @@ extern "C" int bs_aggregate_layer(const uint8_t *head_types, int32_t n_prompts, 
     }
     return BS_OK;
 }
+
+extern "C" double bs_alpha_layer(double alpha_first, double alpha_last, int32_t layer_idx, int32_t num_layers)
+{
+    if (num_layers <= 0 || layer_idx < 0 || layer_idx > num_layers) return NAN;
+    return alpha_first + (alpha_last - alpha_first) * (double)layer_idx / (double)num_layers;
+}

@@ -48,6 +48,19 @@ def test_layer_aggregation_matches_oracle():
         bs.bs_aggregate_layer(np.full((2, 2), 4, np.uint8), 0.25, 0.6, 0.6)
 
 
+def test_linear_alpha_schedule():
+    """End points and mid point of the schedules the paper prints for the two Gemma 3 sizes
+    (App. "Impact of Linear alpha_layer for Gemma 3"), and the fixed threshold of the Qwen-type models."""
+    assert bs.bs_alpha_layer(0.005, 0.195, 0, 48) == 0.005
+    assert bs.bs_alpha_layer(0.005, 0.195, 48, 48) == pytest.approx(0.195, rel=1e-15)
+    assert bs.bs_alpha_layer(0.005, 0.195, 24, 48) == pytest.approx(0.1, rel=1e-15)
+    assert bs.bs_alpha_layer(0.001, 0.099, 17, 34) == pytest.approx(0.05, rel=1e-15)
+    assert all(bs.bs_alpha_layer(0.1, 0.1, i, 28) == 0.1 for i in range(28))
+    a = [bs.bs_alpha_layer(0.001, 0.099, i, 34) for i in range(34)]
+    assert all(y > x for x, y in zip(a, a[1:]))
+    assert math.isnan(bs.bs_alpha_layer(0.1, 0.2, 3, 0)) and math.isnan(bs.bs_alpha_layer(0.1, 0.2, -1, 4))
+
+
 def test_characterize_rejects_bad_arguments_before_touching_the_device():
     lib = binding.load_library()
     one = ctypes.c_void_p(256)
