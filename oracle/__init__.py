@@ -46,6 +46,10 @@ def _load():
         lib.bso_mask.restype = None
         lib.bso_pair_count.argtypes = [ctypes.c_int, i32, i32p, u8p, ctypes.c_int, i32]
         lib.bso_pair_count.restype = i64
+        lib.bso_mask_rows.argtypes = [ctypes.c_int, i32, i32p, u8p, ctypes.c_int, i32, i32p, i32, u8p]
+        lib.bso_mask_rows.restype = None
+        lib.bso_pair_count_rows.argtypes = [ctypes.c_int, i32, i32p, u8p, ctypes.c_int, i32, i32p, i32]
+        lib.bso_pair_count_rows.restype = i64
         lib.bso_tile_states.argtypes = [ctypes.c_int, i32, i32p, u8p, ctypes.c_int, i32, i32, i32, i32p, i32, u8p]
         lib.bso_tile_states.restype = None
         lib.bso_tile_states_rows.argtypes = [ctypes.c_int, i32, i32p, u8p, ctypes.c_int, i32, i32, i32, i32p, i32, u8p]
@@ -100,6 +104,26 @@ def mask(cls: int, imgid, issink, img_bidir: bool = False, window: int = 0) -> n
 def pair_count(cls: int, imgid, issink, img_bidir: bool = False, window: int = 0) -> int:
     return int(_load().bso_pair_count(int(cls), len(imgid), _p(imgid, ctypes.c_int32),
                                       _p(issink, ctypes.c_uint8), int(bool(img_bidir)), int(window)))
+
+
+def mask_rows(cls: int, imgid, issink, rows, img_bidir: bool = False, window: int = 0) -> np.ndarray:
+    """uint8 [len(rows), L]: the listed rows of the bitmap (for prompts too long for mask())."""
+    L = len(imgid)
+    rows = np.ascontiguousarray(rows, dtype=np.int32).reshape(-1)
+    assert len(rows) == 0 or (rows.min() >= 0 and rows.max() < L)
+    out = np.empty((len(rows), L), dtype=np.uint8)
+    _load().bso_mask_rows(int(cls), L, _p(imgid, ctypes.c_int32), _p(issink, ctypes.c_uint8), int(bool(img_bidir)),
+                          int(window), _p(rows, ctypes.c_int32), len(rows), _p(out, ctypes.c_uint8))
+    return out
+
+
+def pair_count_rows(cls: int, imgid, issink, rows, img_bidir: bool = False, window: int = 0) -> int:
+    """Allowed pairs of the listed query rows, by enumeration."""
+    L = len(imgid)
+    rows = np.ascontiguousarray(rows, dtype=np.int32).reshape(-1)
+    assert len(rows) == 0 or (rows.min() >= 0 and rows.max() < L)
+    return int(_load().bso_pair_count_rows(int(cls), L, _p(imgid, ctypes.c_int32), _p(issink, ctypes.c_uint8),
+                                           int(bool(img_bidir)), int(window), _p(rows, ctypes.c_int32), len(rows)))
 
 
 def tile_states(cls: int, imgid, issink, block_m: int, block_n: int, q_tiles=None,

@@ -117,6 +117,30 @@ int64_t bso_pair_count(int cls, int32_t L, const int32_t *imgid, const uint8_t *
     return total;
 }
 
+/* The listed rows of the bitmap: mask is [n_rows][L].  For prompts too long for bso_mask. */
+void bso_mask_rows(int cls, int32_t L, const int32_t *imgid, const uint8_t *issink, int img_bidir, int32_t window,
+                   const int32_t *rows, int32_t n_rows, uint8_t *mask)
+{
+#pragma omp parallel for schedule(dynamic, 8)
+    for (int32_t r = 0; r < n_rows; ++r)
+        for (int32_t j = 0; j < L; ++j)
+            mask[(size_t)r * L + j] = (uint8_t)bso_allowed(cls, rows[r], j, imgid, issink, img_bidir, window);
+}
+
+/* Number of allowed (i, j) pairs of the listed rows, by enumeration. */
+int64_t bso_pair_count_rows(int cls, int32_t L, const int32_t *imgid, const uint8_t *issink, int img_bidir,
+                            int32_t window, const int32_t *rows, int32_t n_rows)
+{
+    int64_t total = 0;
+#pragma omp parallel for schedule(dynamic, 64) reduction(+ : total)
+    for (int32_t r = 0; r < n_rows; ++r) {
+        int64_t c = 0;
+        for (int32_t j = 0; j < L; ++j) c += bso_allowed(cls, rows[r], j, imgid, issink, img_bidir, window);
+        total += c;
+    }
+    return total;
+}
+
 /* Reduce the element mask to tile states for the listed query tiles.
  * Tile (m, n) covers rows [m*bm, m*bm+bm) x keys [n*bn, n*bn+bn); indices >= L count as
  * not allowed.  state: 0 = no element allowed, 2 = all bm*bn allowed, 1 = otherwise.

@@ -7,7 +7,7 @@ import torch
 import paper_2507_09071_amd as bs
 import workloads as W
 from gpu_util import assert_close, errors, oracle_rows, rows_of_tiles, run_prefill
-from test_oracle_pins import uniform_attention_closed_form
+from test_oracle_pins import uniform_attention_closed_form, uniform_attention_closed_form_heads
 
 pytestmark = pytest.mark.gpu
 D, S, I, IS = 0, 1, 2, 3
@@ -202,6 +202,49 @@ def test_packed_fp32(d):
 def test_packed_configs_sampled_rows(cfg):
     sampled_parity(W.config(cfg), 0, n_random=3, max_tiles=10, row_step=[0, 0, 4, 16, 32][cfg],
                    flags=bs.BS_MAP_PACK_KEYS)
+
+
+# --- the layout the bench times (packed keys) on the long prompts: sampled rows against the oracle, and the
+# --- two properties that hold at any size on EVERY row
+
+@pytest.mark.parametrize("cfg,target,row_step", [(3, None, 16), (5, 36864, 8), (5, 73728, 16), (5, 153600, 16),
+                                                  (5, 307200, 32), (6, None, 32)])
+def test_packed_long_configs_sampled_rows(cfg, target, row_step):
+    sampled_parity(W.config(cfg, target_len=target), 0, n_random=2, max_tiles=8, row_step=row_step,
+                   flags=bs.BS_MAP_PACK_KEYS)
+
+
+def all_rows_closed_forms(p, flags, seed=0, channel_step=1):
+    """V = 1 gives 1 on every row with a visible key (the weights of a row sum to one), and q = 0 gives the
+    mean of V over the row's allowed set, which a closed form from prefix sums states for every row in
+    O(L d): the mask of every row of every head, at any prompt length.  channel_step > 1 compares every
+    channel_step-th channel only (a wrong allowed set shows in every channel; the host side of this test is
+    a few fp64 passes over [L, d] per head)."""
+    q, k, v = W.make_qkv(p, seed, DEV)
+    ones = torch.ones_like(v)
+    out, tm = run_prefill(p, q, k, ones, flags=flags)
+    empty = sum(tm.stats(int(c))["empty_rows"] for c in p.head_class)
+    assert int((out == 0).all(dim=-1).sum()) == empty               # rows without a visible key give zeros
+    nonzero = out.float()[(out != 0).any(dim=-1)]
+    assert torch.all((nonzero - 1.0).abs() <= 2 ** -8), "rows do not sum to one"
+    del out, ones, nonzero
+    q.zero_()
+    out0, _ = run_prefill(p, q, k, v, tm)
+    vn = v[..., ::channel_step].float().cpu().numpy()
+    worst = (0.0, 0.0)
+    for h, want in uniform_attention_closed_form_heads(p, vn):
+        e = assert_close(out0[h][:, ::channel_step].float().cpu().numpy(), want, "bf16", f"{p.name} uniform head {h} class {p.head_class[h]}")
+        worst = (max(worst[0], e[0]), max(worst[1], e[1]))
+    print(p.name, "all rows: worst max_abs %.3e rel_l2 %.3e" % worst, flush=True)
+
+
+@pytest.mark.parametrize("cfg,target", [(2, None), (3, None), (4, None), (5, 307200), (6, None)])
+def test_packed_all_rows_sum_to_one_and_uniform_closed_form(cfg, target):
+    all_rows_closed_forms(W.config(cfg, target_len=target), bs.BS_MAP_PACK_KEYS, channel_step=1 if cfg == 2 else 4)
+
+
+def test_natural_map_all_rows_closed_forms_300k():
+    all_rows_closed_forms(W.config(5, target_len=307200), 0, channel_step=4)
 
 
 def test_config5_stress_72k_sampled_rows():

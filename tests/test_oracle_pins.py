@@ -16,14 +16,18 @@ from golden_masks import all_fixtures, full_fixtures, load, load_full
 D, S, I, IS = 0, 1, 2, 3
 
 
-def np_token_arrays(spans, L, sink_len):
-    """Independent (numpy slicing) construction of imgid / issink from the span table."""
+def np_token_arrays(spans, L, sink_len, offsets=()):
+    """Independent (numpy slicing) construction of imgid / issink from the span table;
+    offsets: in-image offsets that are sink keys in every image as well."""
     imgid = np.zeros(L, dtype=np.int32)
     issink = np.zeros(L, dtype=np.uint8)
     issink[:sink_len] = 1
     for g, (s, e, k) in enumerate(np.asarray(spans).reshape(-1, 3)):
         imgid[s:e] = g + 1
         issink[s:s + k] = 1
+        for o in offsets or ():
+            if o < e - s:
+                issink[s + o] = 1
     return imgid, issink
 
 
@@ -88,25 +92,27 @@ def test_mask_set_identities():
         assert not bad.any()
 
 
-def closed_form_pair_counts(spans, L, sink_len):
-    """Pair counts per class from prefix sums over the span table (no per-pair enumeration)."""
-    imgid, issink = np_token_arrays(spans, L, sink_len)
+def closed_form_pair_counts(spans, L, sink_len, offsets=(), bidir=False):
+    """Pair counts per class from prefix sums over the span table (no per-pair enumeration).
+    bidir: an image row sees up to the last token of its image (non-causal attention inside an image)."""
+    imgid, issink = np_token_arrays(spans, L, sink_len, offsets)
     text = imgid == 0
     text_cum = np.cumsum(text)                       # text keys in [0..i]
     snt = (issink == 1) & ~text
     snt_cum = np.cumsum(snt)                         # sink-and-image keys in [0..i]
     idx = np.arange(L)
     start = np.zeros(L, dtype=np.int64)
+    last = idx.copy()                                # last key position a row may see
     for s, e, _ in np.asarray(spans).reshape(-1, 3):
         start[s:e] = s
-    own = idx - start + 1                            # own-image keys in [start..i]
+        if bidir:
+            last[s:e] = e - 1
+    own = last - start + 1                           # own-image keys in [start..last]
     snt_before = np.where(start > 0, snt_cum[np.maximum(start - 1, 0)], 0)
-    own_sink = snt_cum - snt_before                  # of which sinks
-    counts = {D: L * (L + 1) // 2}
-    per_row = {S: text_cum + snt_cum, I: text_cum + own, IS: text_cum + snt_cum + own - own_sink}
-    for c, r in per_row.items():
-        counts[c] = int(np.where(text, idx + 1, r).sum())
-    return counts
+    own_sink = snt_cum[last] - snt_before            # of which sinks
+    per_row = {D: last + 1, S: text_cum[last] + snt_cum[last], I: text_cum[last] + own,
+               IS: text_cum[last] + snt_cum[last] + own - own_sink}
+    return {c: int(np.where(text, idx + 1, r).sum()) for c, r in per_row.items()}
 
 
 def test_pair_counts_match_closed_form():
@@ -122,6 +128,31 @@ def test_pair_counts_match_closed_form():
     want = closed_form_pair_counts(p.spans, p.seq_len, p.sink_len)
     for c in range(4):
         assert oracle.pair_count(c, imgid, issink) == want[c]
+    # images that attend in both directions, sinks at in-image offsets
+    for seed in range(6):
+        p = small_prompt(seed + 20, sink_len=seed % 3)
+        offsets = [0, 4, 11, 40][: 1 + seed % 4]
+        imgid, issink = oracle.token_arrays(p.spans, p.seq_len, p.sink_len, offsets)
+        for bidir in (False, True):
+            want = closed_form_pair_counts(p.spans, p.seq_len, p.sink_len, offsets, bidir)
+            for c in range(4):
+                assert oracle.pair_count(c, imgid, issink, bidir) == want[c]
+                assert int(oracle.mask(c, imgid, issink, bidir).sum()) == want[c]
+
+
+def test_row_subsets_of_the_bitmap_and_of_the_pair_count():
+    """mask_rows / pair_count_rows are the listed rows of the full bitmap (itself pinned to the hand-derived ones)."""
+    for seed in range(4):
+        p = small_prompt(seed + 30, sink_len=seed)
+        offsets = [2, 9] if seed % 2 else None
+        imgid, issink = oracle.token_arrays(p.spans, p.seq_len, p.sink_len, offsets)
+        rows = np.random.default_rng(seed).permutation(p.seq_len)[: max(1, p.seq_len // 3)].astype(np.int32)
+        for c in range(4):
+            for bidir, window in ((False, 0), (True, 0), (False, 7), (True, 5)):
+                full = oracle.mask(c, imgid, issink, bidir, window)
+                assert np.array_equal(oracle.mask_rows(c, imgid, issink, rows, bidir, window), full[rows])
+                assert oracle.pair_count_rows(c, imgid, issink, rows, bidir, window) == int(full[rows].sum())
+                assert oracle.pair_count_rows(c, imgid, issink, np.arange(p.seq_len), bidir, window) == int(full.sum())
 
 
 def test_tile_states_from_bitmap():
@@ -295,51 +326,64 @@ def test_perturbation_invariances():
         assert np.array_equal(o[h][: e2], base[h][: e2])
 
 
-def uniform_attention_closed_form(p, v):
-    """With q = 0 every allowed key gets the same weight: out[i] = mean of v over the allowed
-    set, from per-category prefix sums of v (O(L d), no pair enumeration)."""
+def uniform_attention_closed_form_heads(p, v):
+    """With q = 0 every allowed key gets the same weight: out[h, i] = mean of v over the allowed
+    set of row i, from per-category prefix sums of v (O(L d) per head, no pair enumeration).
+    Yields (h, out[h]) head by head, so that a 300K-token prompt needs one head's array at a time.
+    Covers the model variant with non-causal images (a row then sees up to the last token of its
+    image) and sinks at in-image offsets; no sliding window."""
+    assert not p.window
     L = p.seq_len
-    imgid, issink = np_token_arrays(p.spans, L, p.sink_len)
+    imgid, issink = np_token_arrays(p.spans, L, p.sink_len, p.sink_offsets)
     text = imgid == 0
     snt = (issink == 1) & ~text
     start = np.zeros(L, dtype=np.int64)
+    idx = np.arange(L)
+    last = idx.copy()                # last key position a row may see
     for s, e, _ in p.spans:
         start[s:e] = s
-    idx = np.arange(L)
+        if p.img_bidir:
+            last[s:e] = e - 1
 
     def csum(w):  # inclusive prefix sums with a leading zero row
-        return np.concatenate([np.zeros((1,) + w.shape[1:]), np.cumsum(w, axis=0)])
+        out = np.zeros((L + 1,) + w.shape[1:])
+        np.cumsum(w, axis=0, out=out[1:])
+        return out
 
-    out = np.zeros((p.n_q_heads, L, v.shape[-1]))
+    # three disjoint key categories: text, image sinks, other image tokens
+    cats = (text, snt, ~text & ~snt)
+    cnt = [csum(sel.astype(np.float64)[:, None]) for sel in cats]
+    acc, acc_kv = None, -1
+    img_rows = np.flatnonzero(~text)
+    hi_t, hi_i, lo_i = idx[text] + 1, last[img_rows] + 1, start[img_rows]
     for h, c in enumerate(p.head_class):
-        vh = v[h // p.gqa_group].astype(np.float64)
-        ones = np.ones((L, 1))
-        acc, cnt = {}, {}
-        for name, sel in (("all", np.ones(L, bool)), ("text", text), ("snt", snt), ("img", ~text),
-                          ("img_nonsink", ~text & ~snt)):
-            acc[name] = csum(vh * sel[:, None])
-            cnt[name] = csum(ones * sel[:, None])
-
-        def rng_sum(tab, lo, hi):   # keys in [lo, hi]
-            return tab[hi + 1] - tab[lo]
-
-        num = rng_sum(acc["all"], 0 * idx, idx)
-        den = rng_sum(cnt["all"], 0 * idx, idx)
-        if c != D:
-            n2 = rng_sum(acc["text"], 0 * idx, idx)
-            d2 = rng_sum(cnt["text"], 0 * idx, idx)
+        if h // p.gqa_group != acc_kv:   # prefix sums of this KV head's values, shared by its query heads
+            acc_kv = h // p.gqa_group
+            vh = np.asarray(v[acc_kv], dtype=np.float64)
+            acc = [csum(np.where(sel[:, None], vh, 0.0)) for sel in cats]
+        num = np.empty((L, vh.shape[1]))
+        den = np.empty((L, 1))
+        for tab, dst in ((acc, num), (cnt, den)):
+            dst[text] = tab[0][hi_t] + tab[1][hi_t] + tab[2][hi_t]          # text rows: every key up to the row
+            if c == D:
+                dst[img_rows] = tab[0][hi_i] + tab[1][hi_i] + tab[2][hi_i]
+                continue
+            r = tab[0][hi_i].copy()                                          # text keys up to the last visible position
             if c in (S, IS):
-                n2 = n2 + rng_sum(acc["snt"], 0 * idx, idx)
-                d2 = d2 + rng_sum(cnt["snt"], 0 * idx, idx)
+                r += tab[1][hi_i]                                            # image sinks anywhere before it
             if c == I:
-                n2 = n2 + rng_sum(acc["img"], start, idx)
-                d2 = d2 + rng_sum(cnt["img"], start, idx)
-            if c == IS:
-                n2 = n2 + rng_sum(acc["img_nonsink"], start, idx)
-                d2 = d2 + rng_sum(cnt["img_nonsink"], start, idx)
-            num = np.where(text[:, None], num, n2)
-            den = np.where(text[:, None], den, d2)
-        out[h] = np.where(den > 0, num / np.maximum(den, 1), 0.0)
+                r += tab[1][hi_i] - tab[1][lo_i]                             # own image: its sinks ...
+            if c in (I, IS):
+                r += tab[2][hi_i] - tab[2][lo_i]                             # ... and its other tokens
+            dst[img_rows] = r
+        yield h, np.where(den > 0, num / np.maximum(den, 1), 0.0)
+
+
+def uniform_attention_closed_form(p, v):
+    """All heads of uniform_attention_closed_form_heads at once: [n_q_heads, L, d]."""
+    out = np.zeros((p.n_q_heads, p.seq_len, v.shape[-1]))
+    for h, o in uniform_attention_closed_form_heads(p, v):
+        out[h] = o
     return out
 
 
@@ -352,6 +396,12 @@ def test_uniform_attention_closed_form():
         assert np.abs(got - want).max() < 1e-12
     p = W.tiny_config("paper10").with_classes([S, I])
     q, k, v = (t.numpy() for t in W.make_qkv(p, 0))
+    got = oracle.attention_for_prompt(p, np.zeros_like(q), k, v)
+    assert np.abs(got - uniform_attention_closed_form(p, v)).max() < 1e-12
+    # non-causal images and sinks at in-image offsets
+    p = W.custom_prompt([("T", 5), ("I", 40), ("T", 3), ("I", 61), ("I", 17), ("T", 9)], [D, S, I, IS], 2, 16,
+                        dtype="f32", sink_len=2, img_bidir=True, sink_offsets=(0, 7, 33))
+    q, k, v = (t.numpy() for t in W.make_qkv(p, 3))
     got = oracle.attention_for_prompt(p, np.zeros_like(q), k, v)
     assert np.abs(got - uniform_attention_closed_form(p, v)).max() < 1e-12
 

@@ -238,7 +238,7 @@ def check_packed(spans, L, sink_len, bm, bn, bidir=False, offsets=None):
     free = np.flatnonzero((imgid == 0) | (issink == 1))
     packed = n0 < tm.n_k_tiles
     lay = tm.layout()
-    assert lay["packed"] == packed and (lay["regrouped"] or not packed)
+    assert lay["packed"] == packed and (lay["regrouped"] or not packed or (imgid > 0).all())   # regrouped, or no text rows
     if packed:
         comp = keys[n0:].ravel()
         assert np.array_equal(comp[comp >= 0], free) and (comp[:len(free)] >= 0).all()
@@ -298,6 +298,84 @@ def test_packed_kernel_tile_size_and_plan():
     reg = bs.bs_build_tilemap(spans, L, hc, 9, flags=bs.BS_MAP_REGROUP_ROWS)
     for c in (1, 3):
         assert tm2.stats(c)["visited"] <= reg.stats(c)["visited"]
+
+
+def check_packed_sampled(p, q_tiles, bm=128, bn=64):
+    """Packed map of a long prompt at the kernel's tile size against the oracle, on sampled query tiles of the
+    map's own row order: every (query tile, key tile) state from the oracle's bitmap rows, and every allowed
+    pair of those rows counted exactly once over the two key-tile spaces."""
+    from test_oracle_pins import closed_form_pair_counts
+    flags = bs.BS_MAP_PACK_KEYS | model_flags(p.img_bidir)
+    tm = bs.bs_build_tilemap(p.spans, p.seq_len, p.head_class, p.sink_len, bm, bn, flags=flags,
+                             sink_offsets=p.sink_offsets or None)
+    L = p.seq_len
+    imgid, issink = oracle.token_arrays(p.spans, L, p.sink_len, p.sink_offsets or None)
+    rows_all = tm.row_order(bm)
+    keys, n0 = tm.key_order(bn)
+    lay = tm.layout()
+    assert lay["packed"] and lay["regrouped"] and n0 == -(-L // bn)
+    free = np.flatnonzero((imgid == 0) | (issink == 1))
+    comp = keys[n0:].ravel()
+    assert np.array_equal(comp[comp >= 0], free) and (comp[:len(free)] >= 0).all()
+    nc = tm.n_k_tiles - n0
+    for c in range(4):
+        plain_class = c == 0 or (c == 2 and not lay["intra_compact"])
+        for m in q_tiles:
+            rows = rows_all[int(m)]
+            valid = rows[rows >= 0]
+            allowed = oracle.mask_rows(c, imgid, issink, valid, p.img_bidir).astype(bool)      # [rows, L]
+            plain = (imgid[valid] == 0) | plain_class
+            own = (imgid[valid][:, None] == imgid[None, :]) & bool(c & 2)
+            in_prompt = np.where(plain[:, None], allowed, allowed & own)
+            in_compact = np.where(plain[:, None], False, allowed & ~own)[:, free]
+            assert int(in_prompt.sum()) + int(in_compact.sum()) == int(allowed.sum()), (c, m)   # each pair once
+            cnt_p = np.pad(in_prompt, ((0, 0), (0, n0 * bn - L))).reshape(len(valid), n0, bn).sum(axis=(0, 2))
+            cnt_c = np.pad(in_compact, ((0, 0), (0, nc * bn - len(free)))).reshape(len(valid), nc, bn).sum(axis=(0, 2))
+            cnt = np.concatenate([cnt_p, cnt_c])
+            want = np.where(cnt == 0, 0, np.where(cnt == bm * bn, 2, 1)).astype(np.uint8)
+            got = tm.tile_states(c, int(m), 1)[0]
+            assert np.array_equal(got, want), (p.name, c, int(m), np.flatnonzero(got != want)[:5])
+    # the numerator of every TFLOP/s figure: allowed pairs per class against the test-side closed form
+    want = closed_form_pair_counts(p.spans, L, p.sink_len, p.sink_offsets, p.img_bidir)
+    for c in range(4):
+        assert tm.stats(c)["allowed_pairs"] == want[c], (p.name, c)
+    tm.pair_plan(p.gqa_group)   # validates every work unit against the per-class lists
+    return tm
+
+
+def packed_sample_tiles(tm, p, n_random, seed):
+    """Query tiles of a packed map worth checking: the ends of the image group and of the text group, tiles
+    around the start / end of a few images (in the image group rows are image tokens in position order), random."""
+    rng = np.random.default_rng([17, seed])
+    n_img = int(sum(e - s for s, e, _ in p.spans))
+    m_img = -(-n_img // 128)
+    picks = {0, m_img - 1, m_img, tm.n_q_tiles - 1}
+    lens = np.cumsum([0] + [int(e - s) for s, e, _ in p.spans])
+    for g in rng.choice(len(p.spans), size=min(3, len(p.spans)), replace=False):
+        picks.update({int(lens[g]) // 128, max(0, int(lens[g + 1]) - 1) // 128})
+    picks.update(int(t) for t in rng.integers(0, tm.n_q_tiles, size=n_random))
+    return sorted(picks)
+
+
+@pytest.mark.parametrize("cfg,target", [(2, None), (3, None), (4, None), (6, None), (5, 36864), (5, 153600), (5, 307200)])
+def test_packed_large_configs_states_and_pair_counts(cfg, target):
+    p = W.config(cfg, target_len=target)
+    probe = bs.bs_build_tilemap(p.spans, p.seq_len, p.head_class, p.sink_len, flags=bs.BS_MAP_PACK_KEYS | model_flags(p.img_bidir),
+                                sink_offsets=p.sink_offsets or None)
+    check_packed_sampled(p, packed_sample_tiles(probe, p, n_random=2, seed=cfg))
+
+
+@pytest.mark.parametrize("cfg,target", [(3, None), (4, None), (6, None), (5, 153600), (5, 307200)])
+def test_natural_map_pair_counts_long_configs(cfg, target):
+    """allowed_pairs of the long prompts, where enumeration is out of reach: against the test-side closed form
+    (itself pinned to the oracle's enumeration on small prompts)."""
+    from test_oracle_pins import closed_form_pair_counts
+    p = W.config(cfg, target_len=target)
+    tm = bs.bs_build_tilemap(p.spans, p.seq_len, p.head_class, p.sink_len, flags=model_flags(p.img_bidir),
+                             sink_offsets=p.sink_offsets or None)
+    want = closed_form_pair_counts(p.spans, p.seq_len, p.sink_len, p.sink_offsets, p.img_bidir)
+    for c in range(4):
+        assert tm.stats(c)["allowed_pairs"] == want[c]
 
 
 @pytest.mark.parametrize("cfg", [2, 4])
