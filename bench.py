@@ -44,6 +44,10 @@ def parse_args():
     ap.add_argument("--all-dense", action="store_true", help="run the same prompt with every head Dense")
     ap.add_argument("--no-dense-leg", action="store_true", help="skip the all-Dense comparison run")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-sweep", action="store_true",
+                    help="skip the 36K-300K sweep (class map and all-Dense on the stress prompts at four lengths and "
+                         "on the 128K and 300K model-shaped prompts) that the default run adds to its JSON line")
+    ap.add_argument("--sweep-steps", type=int, default=3, help="timed launches per sweep entry and leg")
     ap.add_argument("--cpu-seconds", type=float, default=40.0, help="target CPU time of the oracle sample")
     ap.add_argument("--characterize", action="store_true",
                     help="time the offline prompt-level characterisation (Alg. 1: the kernel under the dense "
@@ -87,7 +91,9 @@ class HipEvents:
 
 
 # HBM traffic per launch of the attention kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
-# runs, scaled by the same counters' reading for a 1 GiB copy (see profiles/).  Bytes.
+# runs, scaled by the same counters' reading for a 1 GiB copy (see profiles/).  Bytes.  These are
+# figures from earlier profiled runs of the same command, NOT read in this run; the JSON says so.
+TRAFFIC_SOURCE = "profiles/attn_prefill_bf16_d128_cfg2_36k.md (rocprofv3 --pmc FETCH_SIZE, WRITE_SIZE; not measured in this run)"
 MEASURED_TRAFFIC = {
     # profiles/attn_prefill_bf16_d128_cfg2_36k.md (measured where L2 meets the fabric: the 256 MB
     # memory-side cache sits behind that point); keyed by workload and row order of the tile map
@@ -154,28 +160,10 @@ def timed_steps(bs, torch, p, q, k, v, out, steps, warmup, hev, flags):
 
 
 def sampled_pairs(head_class, rows, imgid, issink, img_bidir=False, window=0):
-    """Allowed pairs of the given query rows summed over the heads (plain enumeration)."""
-    import numpy as np
-    per_class_row = {}
-    for c in set(int(x) for x in head_class):
-        cnt = 0
-        for i in rows:
-            i = int(i)
-            e = i   # last key position the row may see
-            if img_bidir and imgid[i] != 0:
-                e = int(np.flatnonzero(imgid == imgid[i])[-1])
-            lo = max(0, i - window + 1) if window > 0 else 0   # first key position the row may see
-            if imgid[i] == 0 or c == 0:
-                cnt += e + 1 - lo
-            else:
-                ok = imgid[lo: e + 1] == 0
-                if c & 1:
-                    ok |= issink[lo: e + 1] == 1
-                if c & 2:
-                    ok |= imgid[lo: e + 1] == imgid[i]
-                cnt += int(ok.sum())
-        per_class_row[c] = cnt
-    return sum(per_class_row[int(c)] for c in head_class)
+    """Allowed pairs of the given query rows summed over the heads (the oracle's own enumeration)."""
+    import oracle
+    per_class = {c: oracle.pair_count_rows(c, imgid, issink, rows, img_bidir, window) for c in set(int(x) for x in head_class)}
+    return sum(per_class[int(c)] for c in head_class)
 
 
 def cpu_baseline(p, q, k, v, target_seconds):
@@ -297,6 +285,62 @@ def characterize_cpu_baseline(p, q, k, v, pairs_per_mask, target_seconds):
             "sample": f"{done} random query rows x all {p.n_q_heads} heads x 4 masks, scaled by unmasked pairs"}
 
 
+def reused_map_steps(bs, torch, p, q, k, v, out, steps, flags):
+    """A model's prefill reuses ONE tile map of the prompt for all its layers and binds it to each layer's
+    class vector (bs_tilemap_rebind).  Times `steps` such layer calls queued back to back, alternating between
+    the workload's class vector and a rotated copy (so that every call plans and uploads new work units).
+    Returns (wall ms per layer, host ms per layer spent in rebind + bs_attn_prefill)."""
+    import numpy as np
+    dt = bs.BS_BF16 if p.dtype == "bf16" else bs.BS_F32
+    st = torch.cuda.current_stream().cuda_stream
+    tm = bs.bs_build_tilemap(p.spans, p.seq_len, p.head_class, p.sink_len, 128, 64, flags=flags,
+                             sink_offsets=p.sink_offsets or None, window=p.window)
+    vecs = [p.head_class, np.roll(p.head_class, p.gqa_group)]   # same classes per KV group count, other heads
+    for i in range(2):
+        tm.rebind(vecs[i % 2])
+        bs.bs_attn_prefill(q, k, v, out, tm, dt, p.n_q_heads, p.gqa_group, p.head_dim, p.scale, st)
+    torch.cuda.synchronize()
+    host = 0.0
+    t0 = time.perf_counter()
+    for i in range(steps):
+        h0 = time.perf_counter()
+        tm.rebind(vecs[i % 2])
+        bs.bs_attn_prefill(q, k, v, out, tm, dt, p.n_q_heads, p.gqa_group, p.head_dim, p.scale, st)
+        host += time.perf_counter() - h0
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    return 1e3 * wall / steps, 1e3 * host / steps
+
+
+def measure_workload(bs, torch, W, p, seed, steps, warmup, hev, flags):
+    """Class map and all-Dense on one prompt: kernel ms of both, speed-up, the skipped-tile prediction,
+    useful TFLOP/s and the fraction of the bf16 MFMA peak (attention kernel alone, HIP events)."""
+    q, k, v = W.make_qkv(p, seed, "cuda:0")
+    out = torch.empty_like(q)
+    wall, kern, call, build, host_call, tm = timed_steps(bs, torch, p, q, k, v, out, steps, warmup, hev, flags)
+    tot, _ = class_totals(tm, p.head_class)
+    pd = p.all_dense()
+    d_wall, d_kern, d_call, _, _, d_tm = timed_steps(bs, torch, pd, q, k, v, out, steps, 1, hev, flags)
+    d_tot, _ = class_totals(d_tm, pd.head_class)
+    useful = 4.0 * p.head_dim * tot["allowed_pairs"]
+    d_useful = 4.0 * p.head_dim * d_tot["allowed_pairs"]
+    tf = useful / (kern * 1e-3) / 1e12
+    res = {"workload": p.name, "seq_len": p.seq_len, "n_images": int(len(p.spans)),
+           "heads": "%d/%d" % (p.n_q_heads, p.n_kv_heads), "steps": steps,
+           "kernel_ms": round(kern, 3), "device_ms_per_call": round(call, 3), "ms_per_step": round(wall, 3),
+           "all_dense_kernel_ms": round(d_kern, 3), "speedup_kernel": round(d_kern / kern, 3),
+           "predicted_speedup_from_tiles": round(d_tot["visited"] / tot["visited"], 3),
+           "skipped_tile_fraction": round(1.0 - tot["visited"] / d_tot["visited"], 4),
+           "useful_tflops": round(tf, 1), "frac": round(tf / PEAK_BF16_TFLOPS, 4),
+           "frac_with_prepass": round(useful / (call * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
+           "all_dense_tflops": round(d_useful / (d_kern * 1e-3) / 1e12, 1),
+           "all_dense_frac": round(d_useful / (d_kern * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
+           "tilemap_build_host_ms": round(build, 3), "attn_call_host_ms": round(host_call, 3)}
+    del q, k, v, out
+    torch.cuda.empty_cache()
+    return res
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -355,16 +399,19 @@ def main():
     if not args.all_dense and not args.no_dense_leg:
         pd = p.all_dense()
         dsteps = max(3, min(args.steps, 10))
-        d_wall, d_kern, _, _, _, d_tm = timed_steps(bs, torch, pd, q, k, v, out, dsteps, 1, hev, flags)
+        d_wall, d_kern, d_call, _, _, d_tm = timed_steps(bs, torch, pd, q, k, v, out, dsteps, 1, hev, flags)
         d_tot, _ = class_totals(d_tm, pd.head_class)
         dense = {"ms_per_step": round(d_wall, 4), "kernel_ms": round(d_kern, 4), "steps": dsteps,
                  "visited_tiles": d_tot["visited"],
                  "useful_tflops": round(4.0 * d * d_tot["allowed_pairs"] / (d_kern * 1e-3) / 1e12, 2),
                  "speedup_kernel": round(d_kern / kern_ms, 3),
+                 "speedup_device_call": round(d_call / call_ms, 3),     # pre-pass included on both sides
                  "speedup_step": round(d_wall / wall_ms, 3),
                  "predicted_speedup_from_tiles": round(d_tot["visited"] / tot["visited"], 3)}
+    reuse_wall, reuse_host = reused_map_steps(bs, torch, p, q, k, v, out, args.steps, flags)
 
     achieved = useful_flop / (kern_ms * 1e-3) / 1e12
+    traffic = MEASURED_TRAFFIC.get((p.name, order))
     res = {
         "metric": "attn prefill ms + useful TFLOP/s (MFMA util), speedup vs all-Dense @36K-300K",
         "value": round(useful_flop / (wall_ms * 1e-3) / 1e12, 3),
@@ -383,6 +430,10 @@ def main():
         "device_ms_per_call": round(call_ms, 4),
         "tilemap_build_host_ms": round(build_ms, 4),
         "attn_call_host_ms": round(host_call_ms, 4),
+        "reused_map": {"what": "one tile map of the prompt, re-bound to another class vector before every call (a layer of "
+                               "a model): no map build, the work units are planned and uploaded per call",
+                       "ms_per_layer": round(reuse_wall, 4), "host_ms_per_layer": round(reuse_host, 4),
+                       "useful_tflops": round(useful_flop / (reuse_wall * 1e-3) / 1e12, 2)},
         "executed_tflops": round(executed_flop / (kern_ms * 1e-3) / 1e12, 2),
         "kv_stream_gbs": round(kv_stream_bytes / (kern_ms * 1e-3) / 1e9, 1),
         "min_hbm_gbs": round(min_bytes / (kern_ms * 1e-3) / 1e9, 1),
@@ -392,11 +443,28 @@ def main():
                   "useful_over_executed": round(useful_flop / executed_flop, 4)},
         "all_dense": dense,
         "roofline": {"bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS,
-                     "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": MEASURED_TRAFFIC.get((p.name, order)),
+                     "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": traffic,
+                     "traffic_source": TRAFFIC_SOURCE if traffic is not None else None,
                      "kernel": "attn_prefill_%s<%d>" % (p.dtype, d),
-                     "flop_per_launch": useful_flop, "avg_launch_ms": round(kern_ms, 4)},
+                     "flop_per_launch": useful_flop, "avg_launch_ms": round(kern_ms, 4),
+                     # the same useful FLOP over the device time of the whole call: the K / V^T tile-pack
+                     # pre-pass that every bf16 call runs (two HBM-bound kernels) counted in
+                     "frac_with_prepass": round(useful_flop / (call_ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 4),
+                     "device_ms_per_call": round(call_ms, 4)},
     }
+    del q, k, v, out
+    torch.cuda.empty_cache()
+    if not args.no_sweep and args.config == 2 and not args.all_dense and not args.window and p.dtype == "bf16":
+        # the 36K-300K range of the metric: the stress prompts at their four lengths, then the
+        # 128K and 300K model-shaped prompts; same kernel, same map layout, few launches each
+        sweep = []
+        for cfg, target in [(5, L) for L in W.STRESS_LENGTHS] + [(3, None), (4, None)]:
+            ps = W.config(cfg, args.seed, args.sink_mode, target)
+            sweep.append(measure_workload(bs, torch, W, ps, args.seed, args.sweep_steps, 1, hev, flags))
+            print("sweep", json.dumps(sweep[-1]), file=sys.stderr, flush=True)
+        res["sweep"] = sweep
     if not args.no_cpu_baseline:
+        q, k, v = W.make_qkv(p, args.seed, "cuda:0")
         res["cpu_baseline"] = cpu_baseline(p, q, k, v, args.cpu_seconds)
     print(json.dumps(res))
 

@@ -104,8 +104,8 @@ int bs_build_tilemap(const bs_span *spans, int32_t n_spans, int32_t seq_len,
  *       No effect on a prompt without images, without free keys, or made of free keys only. */
 #define BS_MAP_PACK_KEYS 2u
 /*   BS_MAP_BIDIR_IMAGES   model variant in which the tokens of one image attend to each other in
- *       both directions (Gemma 3; paper Sec. 2: the dense mask is the model's default mask, Sec. 6.1:
- *       "non-causal attention mechanism within an image").  The causal condition j <= i of the pair
+ *       both directions (Gemma 3; paper Sec. 2: the dense mask is the model's default mask; Sec. 6.1
+ *       states that this model does not attend causally inside an image).  The causal condition j <= i of the pair
  *       rule above becomes "j <= i, or i and j belong to the same image", for every class: a sparse
  *       mask is its class pattern inside the model's dense mask.  An image query then sees exactly
  *       what the last query of its image sees under the causal rule, which is how the map and the
@@ -125,8 +125,8 @@ int bs_build_tilemap_ex(const bs_span *spans, int32_t n_spans, int32_t seq_len,
  * frequent locations found on its characterisation set; the list itself is the caller's input).
  * window > 0 makes the map one of a sliding-window layer: the layer's dense mask keeps, for every query
  * (text queries too) and every class, only the keys with i - j < window (paper App. kernel, "Dense
- * Attention Subroutine": text queries follow the model's dense mask, "causal or sliding window as per the
- * original model"; the sparse masks live inside the dense mask).  0 = no window; a window of seq_len or
+ * Attention Subroutine": text queries follow the model's own dense mask, which is causal or a sliding
+ * window depending on the model; the sparse masks live inside the dense mask).  0 = no window; a window of seq_len or
  * more is no window.  With a window BS_MAP_PACK_KEYS acts as BS_MAP_REGROUP_ROWS (a windowed query tile
  * visits a handful of key tiles: there is nothing to pack).  Together with BS_MAP_BIDIR_IMAGES the keys of
  * the query's own image stay visible at any distance; the map supports that for images of at most
@@ -139,7 +139,9 @@ int bs_build_tilemap_model(const bs_span *spans, int32_t n_spans, int32_t seq_le
                            const int32_t *sink_offsets, int32_t n_sink_offsets, int32_t window,
                            bs_tilemap **out);
 
-/* Frees the host arrays; device buffers (if any) go back to a per-process cache of the library
+/* End of a map's life (the paper builds its mask metadata once per prompt, Sec. 5 "no runtime overhead";
+ * so does a caller here, and destroys the map when the prompt's prefill is over).
+ * Frees the host arrays; device buffers (if any) go back to a per-process cache of the library
  * and are handed to a later map only after the work queued with this map has finished (the
  * next owner's stream waits for an event recorded after this map's last call).  So a map may be
  * destroyed as soon as its last bs_attn_prefill has returned, without waiting for the stream,
@@ -147,7 +149,9 @@ int bs_build_tilemap_model(const bs_span *spans, int32_t n_spans, int32_t seq_le
  * blocks until the process ends.  NULL is allowed. */
 void bs_tilemap_destroy(bs_tilemap *tm);
 
-/* Geometry: any output pointer may be NULL. */
+/* Geometry of the map, in the paper's symbols (App. kernel, "Notation"): seq_len = L, n_q_tiles = M =
+ * number of block_m-row query tiles, n_k_tiles = N = number of block_n-key tiles (compact tiles included).
+ * Any output pointer may be NULL. */
 int bs_tilemap_dims(const bs_tilemap *tm, int32_t *seq_len, int32_t *n_q_tiles,
                     int32_t *n_k_tiles, int32_t *n_q_heads);
 
@@ -166,12 +170,15 @@ int bs_tilemap_layout(const bs_tilemap *tm, int32_t *regrouped, int32_t *packed,
  * the prompt in position order (all of them unless the map was built with BS_MAP_PACK_KEYS). */
 int bs_tilemap_key_order(const bs_tilemap *tm, int32_t *keys, int32_t *n_prompt_tiles);
 
-/* Expand the range lists of class `cls` for query tiles [q_tile_begin, +q_tile_count) into
+/* The per-tile decision of the paper's kernel (App. kernel, Overview: fully masked tiles are skipped, tiles at
+ * a mask boundary are masked element-wise) made explicit for the bit-exact check against the element-wise mask
+ * of Sec. 3.2.  Expand the range lists of class `cls` for query tiles [q_tile_begin, +q_tile_count) into
  * states[q_tile_count][n_k_tiles] (host, row-major): 0 skip, 1 partial, 2 full. */
 int bs_tilemap_tile_states(const bs_tilemap *tm, int32_t cls, int32_t q_tile_begin,
                            int32_t q_tile_count, uint8_t *states);
 
-/* Per-class accounting (any output pointer may be NULL):
+/* Per-class accounting behind the FLOP figures (the paper counts attention FLOPs per unmasked pair, App.
+ * "FLOPs Reduction"; Sec. 3.2 defines which pairs a class keeps).  Any output pointer may be NULL:
  *   visited = full + partial tiles over all query tiles; allowed_pairs = number of allowed
  *   (i, j) pairs, from span geometry (the bench's "4 d FLOP per unmasked pair" counts these);
  *   empty_rows = query rows whose allowed set is empty (their output is zero);
@@ -191,6 +198,30 @@ int bs_tilemap_stats(const bs_tilemap *tm, int32_t cls, int64_t *visited, int64_
  */
 int bs_tilemap_pair_plan(bs_tilemap *tm, int32_t gqa_group, int64_t *n_units, int64_t *unit_tiles,
                          int64_t *skip_steps);
+
+/*
+ * Bind a built map to another class vector (paper Sec. 4: every layer of a model has its own offline-assigned
+ * head classes, while the mask metadata depends on the prompt alone, Sec. 5): the four per-class tile lists,
+ * token codes, row and key order -- everything bs_build_tilemap derived from the span table -- are kept,
+ * on the host and on the device; only the work list / work units are planned again by the next
+ * bs_attn_prefill (or bs_tilemap_prepare).  So a model builds ONE map per prompt and rebinds it per layer.
+ *   head_class   host, n_q_heads values in 0..3 (n_q_heads may differ from the count the map was built with)
+ * Host only, O(n_q_heads); binding the vector the map already has is free.  Stream order makes it safe to
+ * rebind while kernels of the previous binding are still queued on the stream of the next call.
+ * Errors: BS_EINVAL, BS_ENOMEM.
+ */
+int bs_tilemap_rebind(bs_tilemap *tm, const uint8_t *head_class, int32_t n_q_heads);
+
+/*
+ * Do, ahead of time, everything bs_attn_prefill would do on the first call with this map and these
+ * arguments except the kernels: upload the prompt part (once per map), plan and upload the work list
+ * (BS_F32) or the work units for `gqa_group` (BS_BF16) of the current class vector, raise the kernels'
+ * dynamic-LDS limits and look up the address of the static scratch on the current device.  Enqueues
+ * copies on `stream`, does not wait.  May allocate (block cache / hipMalloc, pinned staging).  After it,
+ * bs_attn_prefill_static with the same map, class vector and gqa_group allocates nothing.
+ * Errors: BS_EINVAL, BS_EUNSUPPORTED, BS_ENOMEM, BS_EHIP.
+ */
+int bs_tilemap_prepare(bs_tilemap *tm, int32_t dtype, int32_t gqa_group, void *stream);
 
 /* Copy the map to the current HIP device and wait until the copy is done (default stream,
  * then hipStreamSynchronize on it).  Optional: bs_attn_prefill uploads on first use, on its own
@@ -238,6 +269,29 @@ int bs_attn_prefill_ex(const void *q, const void *k, const void *v, void *out, b
                        float scale, void *stream, void *ev_main_start, void *ev_main_stop);
 
 /*
+ * bs_attn_prefill (bf16) for callers that cannot allocate: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Same kernels and same result as bs_attn_prefill with BS_BF16;
+ * the packed K / V^T tiles of the pre-pass go to a static device array of BS_STATIC_SCRATCH_MIB MiB
+ * inside the library (one copy per GPU, held until the process ends) instead of a workspace owned by the
+ * map.  Calls no hipMalloc / hipFree, creates no events, uploads nothing.
+ *   tm       must have been prepared: bs_tilemap_prepare(tm, BS_BF16, gqa_group, stream) after the build and
+ *            after every bs_tilemap_rebind; BS_EINVAL otherwise (bs_last_error says so)
+ *   limit    n_kv_heads * n_k_tiles * head_dim * 256 bytes (packed K plus packed V^T) must fit the scratch:
+ *            BS_EUNSUPPORTED otherwise, nothing launched (96 MiB hold 4 KV heads x 768 key tiles of d = 128:
+ *            a 40K-token prompt with its compact tiles)
+ * Every call on a GPU uses that GPU's one array: calls that overlap in time on one GPU (two streams, two
+ * threads) race on it; calls queued on one stream are safe.  The pre-pass rewrites every tile slot it
+ * uses, so nothing needs clearing between calls.
+ * Other arguments and errors as bs_attn_prefill.
+ */
+#define BS_STATIC_SCRATCH_MIB 96
+int bs_attn_prefill_static(const void *q, const void *k, const void *v, void *out, bs_tilemap *tm,
+                           int32_t n_q_heads, int32_t gqa_group, int32_t head_dim, float scale, void *stream);
+
+/* Size of that array in bytes. */
+int64_t bs_static_scratch_bytes(void);
+
+/*
  * Offline characterisation, prompt level (paper Sec. 4.1, Alg. 1), for all query heads of one layer:
  * the attention output under the dense causal mask is the reference; for the masks Sink,
  * Intra-Image, Intra-Image+Sink, in this order,
@@ -246,7 +300,7 @@ int bs_attn_prefill_ex(const void *q, const void *k, const void *v, void *out, b
  *   q, k, v      device pointers, layouts as for bs_attn_prefill; spans / seq_len / sink_len as for
  *                bs_build_tilemap (host)
  *   alpha        the layer's threshold alpha_layer (the paper recommends 0.1 for Qwen-type models)
- *   map_flags    options for the four tile maps the call builds (BS_MAP_*); sink_offsets /
+ *   map_flags    options for the tile map the call builds (BS_MAP_*); sink_offsets /
  *                n_sink_offsets / window as for bs_build_tilemap_model
  *   head_type    host, n_q_heads values out (bs_head_class)
  *   nmse         host, [3][n_q_heads] out, row m = mask m + 1; may be NULL.  All three masks are
@@ -256,8 +310,10 @@ int bs_attn_prefill_ex(const void *q, const void *k, const void *v, void *out, b
  * The four outputs come from bs_attn_prefill in `dtype` (bf16: the outputs are rounded to bf16 before
  * they are compared, which puts a floor of about 1e-5 under the NMSE), the squared errors are
  * accumulated in fp64 and the decision is taken in fp64.
- * Allocates two output-sized device buffers for the duration of the call and returns after `stream`
- * has drained (this is an offline routine).
+ * Builds ONE tile map of the prompt and binds it to the four class vectors in turn (bs_tilemap_rebind).  Takes
+ * two output-sized device buffers from the library's block cache for the duration of the call (hipMalloc only
+ * while the cache is cold; the blocks stay cached afterwards) and returns after `stream` has drained (this
+ * is an offline routine).
  * Errors: as bs_build_tilemap_ex and bs_attn_prefill; nothing is written to head_type / nmse on error.
  */
 int bs_characterize_prompt(const void *q, const void *k, const void *v, const bs_span *spans,
@@ -309,7 +365,7 @@ int bs_aggregate_layer(const uint8_t *head_types, int32_t n_prompts, int32_t n_q
  */
 double bs_alpha_layer(double alpha_first, double alpha_last, int32_t layer_idx, int32_t num_layers);
 
-/* Static description of an error code. */
+/* Static description of an error code (error behaviour of this boundary; no passage of the paper). */
 const char *bs_strerror(int code);
 
 /* Detail of the most recent BS_EHIP / BS_ENOMEM failure on the calling thread (the HIP call

@@ -18,7 +18,8 @@ BS_BF16, BS_F32 = 0, 1
 DENSE, SINK, INTRA, INTRA_SINK = 0, 1, 2, 3
 
 EXPORTS = ("bs_build_tilemap", "bs_build_tilemap_ex", "bs_build_tilemap_model", "bs_tilemap_destroy", "bs_tilemap_dims", "bs_tilemap_row_order", "bs_tilemap_layout", "bs_tilemap_key_order", "bs_tilemap_tile_states",
-           "bs_tilemap_stats", "bs_tilemap_pair_plan", "bs_tilemap_upload", "bs_attn_prefill", "bs_attn_prefill_ex",
+           "bs_tilemap_stats", "bs_tilemap_pair_plan", "bs_tilemap_upload", "bs_tilemap_rebind", "bs_tilemap_prepare",
+           "bs_attn_prefill", "bs_attn_prefill_ex", "bs_attn_prefill_static", "bs_static_scratch_bytes",
            "bs_characterize_prompt", "bs_head_sq_error", "bs_aggregate_head_type", "bs_aggregate_layer", "bs_alpha_layer", "bs_strerror",
            "bs_last_error")
 
@@ -26,7 +27,7 @@ EXPORTS = ("bs_build_tilemap", "bs_build_tilemap_ex", "bs_build_tilemap_model", 
 class BlindsightError(RuntimeError):
     def __init__(self, code: int, where: str):
         self.code = code
-        detail = load_library().bs_last_error().decode() if code in (-3, -4) else ""
+        detail = load_library().bs_last_error().decode() if code in (-3, -4) or "static" in where else ""
         super().__init__(f"{where}: {_strerror(code)} ({code})" + (f" [{detail}]" if detail else ""))
 
 
@@ -92,6 +93,14 @@ def load_library():
     lib.bs_tilemap_pair_plan.restype = ctypes.c_int
     lib.bs_tilemap_upload.argtypes = [vp]
     lib.bs_tilemap_upload.restype = ctypes.c_int
+    lib.bs_tilemap_rebind.argtypes = [vp, u8p, i32]
+    lib.bs_tilemap_rebind.restype = ctypes.c_int
+    lib.bs_tilemap_prepare.argtypes = [vp, i32, i32, vp]
+    lib.bs_tilemap_prepare.restype = ctypes.c_int
+    lib.bs_attn_prefill_static.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, ctypes.c_float, vp]
+    lib.bs_attn_prefill_static.restype = ctypes.c_int
+    lib.bs_static_scratch_bytes.argtypes = []
+    lib.bs_static_scratch_bytes.restype = ctypes.c_int64
     lib.bs_attn_prefill.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, ctypes.c_float, vp]
     lib.bs_attn_prefill.restype = ctypes.c_int
     lib.bs_attn_prefill_ex.argtypes = [vp, vp, vp, vp, vp, i32, i32, i32, i32, ctypes.c_float, vp, vp, vp]
@@ -186,6 +195,18 @@ class TileMap:
     def upload(self):
         _check(load_library().bs_tilemap_upload(self._h), "bs_tilemap_upload")
 
+    def rebind(self, head_class):
+        """Bind the map to another class vector (one per layer); the per-class lists are kept."""
+        hc = np.ascontiguousarray(head_class, dtype=np.uint8)
+        _check(load_library().bs_tilemap_rebind(self._h, hc.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8)), len(hc)),
+               "bs_tilemap_rebind")
+        self.n_q_heads = len(hc)
+
+    def prepare(self, dtype: int, gqa_group: int, stream=None):
+        """Upload and plan ahead of time, so that bs_attn_prefill_static allocates nothing."""
+        _check(load_library().bs_tilemap_prepare(self._h, int(dtype), int(gqa_group),
+                                                 ctypes.c_void_p(int(stream) if stream else 0)), "bs_tilemap_prepare")
+
     def close(self):
         if self._h is not None and self._h.value:
             load_library().bs_tilemap_destroy(self._h)
@@ -259,6 +280,20 @@ def bs_attn_prefill(q, k, v, out, tilemap: TileMap, dtype: int, n_q_heads: int, 
                                         int(dtype), int(n_q_heads), int(gqa_group), int(head_dim),
                                         float(scale), ctypes.c_void_p(int(stream) if stream else 0))
     _check(rc, "bs_attn_prefill")
+
+
+def bs_attn_prefill_static(q, k, v, out, tilemap: TileMap, n_q_heads: int, gqa_group: int, head_dim: int,
+                           scale: float, stream=None) -> None:
+    """bf16 prefill that allocates nothing (static scratch inside the library); the map must have been
+    prepared with TileMap.prepare(BS_BF16, gqa_group)."""
+    rc = load_library().bs_attn_prefill_static(_ptr(q), _ptr(k), _ptr(v), _ptr(out), tilemap.handle, int(n_q_heads),
+                                               int(gqa_group), int(head_dim), float(scale),
+                                               ctypes.c_void_p(int(stream) if stream else 0))
+    _check(rc, "bs_attn_prefill_static")
+
+
+def bs_static_scratch_bytes() -> int:
+    return int(load_library().bs_static_scratch_bytes())
 
 
 def bs_characterize_prompt(q, k, v, spans, seq_len: int, sink_len: int, dtype: int, n_q_heads: int,

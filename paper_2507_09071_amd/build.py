@@ -9,7 +9,7 @@ PKG = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 LIB = os.path.join(PKG, "libblindsight.so")
-SOURCES = ["tilemap.cpp", "attn_prefill.hip", "characterize.hip"]
+SOURCES = ["tilemap.cpp", "device_map.hip", "attn_prefill.hip", "characterize.hip"]
 
 
 def hipcc() -> str:

@@ -8,17 +8,18 @@
 // element predicate (PARTIAL) or not (FULL).  One softmax runs per row over the union of all
 // visited keys, and the output is divided by the running sum at the end.
 //
-// Mapping to CDNA4:
-//  * a workgroup of four 64-lane waves owns one 128-row query tile of one head; wave w owns
-//    rows 32w..32w+31 and keeps its Q rows in registers for the whole pass;
+// Mapping to CDNA4 (bf16 kernel):
+//  * a workgroup of eight 64-lane waves owns one work unit: two (head, query tile) items that
+//    read the same KV head, four waves each; wave w of a group owns rows 32w..32w+31 of its item
+//    and keeps its Q rows in registers for the whole pass;
 //  * scores are produced transposed, S^T = K Q^T, with 32x32x16 bf16 MFMA tiles, so every lane
 //    holds 16 keys of ONE query per 32-key block: row max / row sum are in-lane reductions plus
 //    one exchange with the lane 32 apart (v_permlane32_swap);
-//  * O^T = V^T P^T reuses the score registers, rounded to bf16, as the B operand;
-//  * K and V tiles travel global -> LDS with 16-byte LDS-direct loads (no VGPR staging) into a
-//    two-stage ring, one barrier per tile; rows are unpadded and XOR-swizzled so both the
-//    128-bit K fragment reads and the 64-bit transposing V reads (ds_read_b64_tr_b16) are free
-//    of bank conflicts;
+//  * O^T = V^T P^T reuses the probabilities, rounded to bf16, as the B operand; V^T comes from a
+//    pre-pass that writes K and V^T per key tile in exactly the layout the LDS reads want;
+//  * K and V^T tiles travel global -> LDS with 16-byte LDS-direct loads (no VGPR staging) into a
+//    ring of 4 K + 4 V^T slots shared by the two groups; ONE barrier per key tile, placed so that
+//    on every SIMD one wave runs its matrix phase while the other runs its vector phase;
 //  * PARTIAL tiles build one 64-bit allowed-key word per lane from per-tile text/sink bit
 //    masks, the query's own image range and the causal bound, then test one bit per score.
 #include <hip/hip_runtime.h>
@@ -33,54 +34,10 @@
 #include <type_traits>
 #include <vector>
 
-#include "hip_internal.h"
+#include "device_map.h"
 #include "tilemap_internal.h"
 
 namespace bs {
-
-thread_local char g_last_error[256] = "";
-
-int fail_hip(hipError_t e, const char *what)
-{
-    snprintf(g_last_error, sizeof g_last_error, "%s: %s (%d)", what, hipGetErrorString(e), (int)e);
-    (void)hipGetLastError();
-    return e == hipErrorOutOfMemory ? BS_ENOMEM : BS_EHIP;
-}
-
-struct DeviceMap {
-    int device = -1;
-    void *blob = nullptr;                 // one allocation holding everything below
-    size_t blob_cap = 0;
-    const uint32_t *code = nullptr;       // [L] per-token code
-    const int32_t *row_order = nullptr;   // [M * 128] position of each query-tile row, -1 = none
-    const int32_t *key_order = nullptr;   // [N * 64] position of each key-tile slot, -1 = none
-    const int32_t *free_before = nullptr; // packed: [L + 1]
-    const int2 *span_free = nullptr;      // packed: [G + 1] compact slots of the free keys inside each image
-    const uint64_t *text_bits = nullptr;  // [N] text keys of each key tile
-    const uint64_t *sink_bits = nullptr;  // [N] sink keys of each key tile
-    const int2 *span_range = nullptr;     // [G+1] (start, end) by imgid; entry 0 unused
-    const int32_t *row_ptr = nullptr;     // [4][M+1] offsets into ranges
-    const int32_t *row_tiles = nullptr;   // [4][M] visited key tiles per query tile
-    const int2 *ranges = nullptr;         // concatenated over classes
-    const int2 *work = nullptr;           // [n_work] (head, q_tile)
-    const uint8_t *head_class = nullptr;  // [Hq]
-    int32_t n_work = 0;
-    void *vt_buf = nullptr;               // workspace: packed K and V^T tiles of the last bf16 call
-    size_t vt_bytes = 0;
-    void *pair_blob = nullptr;            // bf16 work units for pair_G: items, then ranges
-    size_t pair_cap = 0;
-    const int4 *pair_items = nullptr;
-    const int2 *pair_ranges = nullptr;
-    int32_t n_pairs = 0, pair_G = 0;
-    hipStream_t last_stream = nullptr;    // stream of the most recent upload / launch (compared, never used)
-    std::shared_ptr<struct EventHolder> last_use;   // recorded after the most recent upload / launch
-};
-
-// An event that dies with its last owner (a map, or cached blocks that wait to be reused).
-struct EventHolder {
-    hipEvent_t ev = nullptr;
-    ~EventHolder() { if (ev) (void)hipEventDestroy(ev); }
-};
 
 // Read-only tile-map arrays; passed as separate __restrict__ kernel parameters so that loads
 // with wave-uniform addresses go through the scalar cache (they then never wait on the vector
@@ -444,54 +401,6 @@ __global__ __launch_bounds__(256) void pack_k_tiles(const __bf16 *__restrict__ k
 
 constexpr int kPingPongThreads = 512;
 
-// Optional phase timing (build with -DBS_PHASE_TIMING): wave 0 of every workgroup adds the
-// cycles it spent in phase X, the barrier after X, phase Y and the barrier after Y.
-#ifdef BS_PROBE_NO_BARRIER
-#define BS_LOOP_BARRIER() do {} while (0)
-#else
-#define BS_LOOP_BARRIER() __builtin_amdgcn_s_barrier()
-#endif
-#ifdef BS_PHASE_TIMING
-__device__ unsigned long long g_phase_cycles[8];
-__device__ inline unsigned long long bs_now(floatx16 &a, floatx16 &b, floatx16 &c)
-{
-    // the ties make the stamp wait for the MFMAs that produce these accumulators
-    asm volatile("" : "+v"(a), "+v"(b), "+v"(c));
-    unsigned long long t;
-    asm volatile("s_memtime %0\n\ts_waitcnt lgkmcnt(0)" : "=s"(t));
-    return t;
-}
-// per work unit: kernel entry -> query metadata loaded -> first loop barrier, the loop, loop -> stores done
-__device__ unsigned long long g_unit_cycles[4];
-__device__ inline unsigned long long bs_stamp()
-{
-    unsigned long long t;
-    asm volatile("s_memtime %0\n\ts_waitcnt lgkmcnt(0)" : "=s"(t)::"memory");
-    return t;
-}
-#define BS_U(i) do { const unsigned long long t_ = bs_stamp(); bs_u[i] = t_ - bs_ut; bs_ut = t_; } while (0)
-#define BS_UFLUSH() do { if (tid == 0) for (int i = 0; i < 4; ++i) atomicAdd(&g_unit_cycles[i], bs_u[i]); } while (0)
-#define BS_T0() unsigned long long bs_acc[4] = {0, 0, 0, 0}; unsigned long long bs_t0 = bs_now(s[0], s[1], o[0])
-#define BS_TICK(slot)                                                                  \
-    do {                                                                               \
-        const unsigned long long bs_t1 = bs_now(s[0], s[1], o[0]);                     \
-        bs_acc[slot] += bs_t1 - bs_t0;                                                 \
-        bs_t0 = bs_t1;                                                                 \
-    } while (0)
-#define BS_TFLUSH()                                                                    \
-    do {                                                                               \
-        bs_acc[3] = bs_vm_wait;   /* slot 3: waiting for tile loads, part of slot 0 */ \
-        if (tid == 0 || tid == 256)                                                    \
-            for (int i = 0; i < 4; ++i) atomicAdd(&g_phase_cycles[i + 4 * (tid >> 8)], bs_acc[i]); \
-    } while (0)
-#else
-#define BS_U(i) do {} while (0)
-#define BS_UFLUSH() do {} while (0)
-#define BS_T0() do {} while (0)
-#define BS_TICK(slot) do {} while (0)
-#define BS_TFLUSH() do {} while (0)
-#endif
-
 // Batch tags of the matrix phase: four operand reads + four MFMAs each.
 template <int G> struct PvBatch { static constexpr int kind = 1, idx = G; static constexpr bool first = false; };            // O^T += V^T(group G) P^T(group G)
 template <int B, bool FIRST> struct ScBatch { static constexpr int kind = 2, idx = B; static constexpr bool first = FIRST; }; // S += K(slices 2B, 2B+1) Q^T
@@ -545,7 +454,7 @@ template <int D>
 __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(
     KernelArgs a, const uint32_t *__restrict__ map_code, const uint64_t *__restrict__ map_text_bits,
     const uint64_t *__restrict__ map_sink_bits, const int2 *__restrict__ map_span_range,
-    const uint8_t *__restrict__ map_head_class, const int32_t *__restrict__ map_row_order,
+    const int32_t *__restrict__ map_row_order,
     const int32_t *__restrict__ map_free_before, const int2 *__restrict__ map_span_free,
     const int4 *__restrict__ pair_items,
     const int2 *__restrict__ pair_ranges, const __bf16 *__restrict__ kp, const __bf16 *__restrict__ vt,
@@ -559,9 +468,6 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(
     extern __shared__ __align__(1024) unsigned char lds[];   // K slots 0..3, then V^T slots 0..3
 
     const int tid = threadIdx.x, lane = tid & 63, hl = lane >> 5, col = lane & 31;
-#ifdef BS_PHASE_TIMING
-    unsigned long long bs_u[4] = {0, 0, 0, 0}, bs_ut = bs_stamp(), bs_vm_wait = 0;
-#endif
     const int grp = __builtin_amdgcn_readfirstlane(tid >> 8);          // wave group 0 / 1
     const int wave = __builtin_amdgcn_readfirstlane((tid >> 6) & 3);   // wave within the group
     const int wave8 = __builtin_amdgcn_readfirstlane(tid >> 6);        // wave within the workgroup
@@ -575,7 +481,7 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(
     const int T = __builtin_amdgcn_readfirstlane(it1.z);            // key tiles in the merged list
     const int n_steps = T + 1;                                      // the last step only adds P(T-1) V(T-1)
     const int hsafe = max(head, 0);
-    const int cls = __builtin_amdgcn_readfirstlane((int)map_head_class[hsafe]);
+    const int cls = __builtin_amdgcn_readfirstlane((grp ? it1.w >> 8 : it1.w) & 3);   // head classes travel with the unit
     const int kvh = __builtin_amdgcn_readfirstlane(it0.x / a.G);    // both items share it
     // the query position of this lane's row; a tile slot without a row behaves like a row past
     // the end of the prompt (computed on a copy of the last row, never stored)
@@ -597,10 +503,6 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(
     }
     QueryView qv;
     qv.init(map_code, map_span_range, map_free_before, map_span_free, L, cls, row, a.packed != 0, a.intra_compact != 0, a.bidir != 0, a.window);
-#ifdef BS_PHASE_TIMING
-    asm volatile("" ::"v"(qreg[0]), "v"(qv.row), "v"(qv.own_hi), "v"(qv.free_bound), "v"(qv.cfree_hi));   // the metadata has arrived
-    BS_U(0);
-#endif
 
     // LDS byte address of this lane's MFMA operand fragments inside a K / V^T tile (see the
     // tile layouts above): key or channel `col`, half hl; slices, blocks and groups are
@@ -647,9 +549,6 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(
         __builtin_amdgcn_global_load_lds((global_void_ptr)((tile + r * 8 * 1024) + dma_lane_off), (lds_void_ptr)dst, 16, 0, 0);
     };
     auto tile_ptr = [&](const char *base, int n) {
-#ifdef BS_PROBE_SAME_TILE
-        n = n & 7;
-#endif
         return base + (size_t)min(n, n_k_tiles - 1) * TILE;  // a walker past its end names no tile
     };
 
@@ -660,9 +559,6 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(
     uint32_t kbase = 0, vbase = 0;  // fragment base addresses inside the ring slots of this step
     // one operand read / one MFMA of a batch (element i = 0..3)
     auto read_one = [&](auto tag, auto ic, bf16x8 &dst) __attribute__((always_inline)) {
-#ifdef BS_PROBE_NO_LDSREAD
-        return;
-#endif
         using T = decltype(tag);
         constexpr int i = decltype(ic)::value;
         if constexpr (T::kind == 1) {
@@ -672,9 +568,6 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(
         }
     };
     auto mul_one = [&](auto tag, auto ic, const bf16x8 &f) __attribute__((always_inline)) {
-#ifdef BS_PROBE_NO_MFMA
-        return;
-#endif
         using T = decltype(tag);
         constexpr int i = decltype(ic)::value;
         if constexpr (T::kind == 1) {
@@ -726,16 +619,13 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(
         // Refill addresses: computed while the first operand reads are in flight.
         const char *ksrc = nullptr, *vsrc = nullptr;
         auto refill_prepare = [&]() __attribute__((always_inline)) {
-#ifndef BS_PROBE_NO_DMA
             __builtin_amdgcn_sched_barrier(0);
             ksrc = tile_ptr(kph, w2.n);
             vsrc = tile_ptr(vth, w1.n);
             w1.next();
             w2.next();
             __builtin_amdgcn_sched_barrier(0);
-#endif
         };
-#ifndef BS_PROBE_NO_X
         if constexpr (D == 128) {
             // batch order: PV0 S0 PV1 S1 PV2 S2 PV3 S3, four reads / MFMAs each
             read_batch(PvBatch<0>{}, fa); read_batch(ScBatch<0, true>{}, fb); read_batch(PvBatch<1>{}, fc);
@@ -761,33 +651,22 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(
             lds_wait<0>(fc); batch(PvBatch<3>{}, NoBatch{}, fc);
             mfma_drain(o[0], o[1]);   // the scores finished two MFMAs earlier
         }
-#else
-        refill_prepare();
-#endif
         // Refill: this wave's share of K(k+2+ahead) and V^T(k+1+ahead) into the slots of the tiles
         // four steps older, which nobody reads after the last barrier.  Unconditional: past the end of the
         // list a valid tile is fetched again and never used.  Issued after the last MFMA:
         // an LDS-direct load issued while the matrix pipe of the SIMD is being fed stalls the
         // wave several times longer (measured both between the MFMAs of this phase and from
         // the other group's vector phase).
-#ifndef BS_PROBE_NO_DMA
         __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int r = 0; r < DMA_PER_WAVE; ++r) dma(r, ksrc, Sk_dst * TILE);
 #pragma unroll
         for (int r = 0; r < DMA_PER_WAVE; ++r) dma(r, vsrc, (kRing + Sv_dst) * TILE);
         __builtin_amdgcn_sched_barrier(0);
-#endif
         // Wait for the loads issued one step ago (only this step's may stay in flight): after
         // the next barrier every wave has passed this wait, and the tile is read in the interval
         // that follows it.
-#ifdef BS_PHASE_TIMING
-        const unsigned long long tw0 = bs_stamp();
-#endif
         asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * DMA_PER_WAVE));
-#ifdef BS_PHASE_TIMING
-        bs_vm_wait += bs_stamp() - tw0;   // time spent waiting for the tile loads of the previous step
-#endif
     };
 
     // text / sink key bits of the tile w0 names (scalar registers, fetched one step ahead)
@@ -799,10 +678,6 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(
     }
     // Phase Y of step k: mask (PARTIAL tiles), online softmax, rescale O, round P to bf16.
     auto phase_y = [&](int k) __attribute__((always_inline)) {
-#ifdef BS_PROBE_NO_Y
-        if (k < T) w0.next();
-        return;
-#endif
         if (k < T) {
             // state of the tile for this group's item: 0 skip (only the other item wants the
             // tile), 1 partial, 2 full.  A skipped tile goes through the row-uniform path with
@@ -885,31 +760,21 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(
     // V^T(k) and written at K(k+3), V^T(k+2), whose slots (of K(k-1), V^T(k-2)) nobody reads
     // after barrier k; a tile written in one interval is waited for (vmcnt) in the next and
     // read in the one after: four slots each.
-    BS_U(1);
-    BS_T0();
     if (grp == 0) {
         for (int k = 0, slot = 0; k < n_steps; ++k) {
             phase_x(slot);
-            BS_TICK(0);
-            BS_LOOP_BARRIER();
-            BS_TICK(1);
+            __builtin_amdgcn_s_barrier();
             phase_y(k);
-            BS_TICK(2);
             slot = slot == kRing - 1 ? 0 : slot + 1;
         }
     } else {
         for (int k = 0, slot = 0; k < n_steps; ++k) {
-            BS_LOOP_BARRIER();
-            BS_TICK(1);
+            __builtin_amdgcn_s_barrier();
             phase_x(slot);
-            BS_TICK(0);
             phase_y(k);
-            BS_TICK(2);
             slot = slot == kRing - 1 ? 0 : slot + 1;
         }
     }
-    BS_TFLUSH();
-    BS_U(2);
 
     // epilogue: divide by the running sum, round, store.  Empty rows (l = 0) give zeros.
     const float l_tot = sum_across_halves(l_run);
@@ -926,11 +791,6 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(
                 *reinterpret_cast<bf16x4 *>(orow + 32 * db + 8 * g + 4 * hl) = w;
             }
     }
-#ifdef BS_PHASE_TIMING
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    BS_U(3);
-    BS_UFLUSH();
-#endif
 }
 
 // ------------------------------------------------------------------------------------ fp32
@@ -1050,246 +910,140 @@ __global__ __launch_bounds__(kThreads, 1) void attn_prefill_f32(KernelArgs a, BS
 template <int D>
 constexpr size_t f32_lds_bytes() { return (size_t)kBlockN * (D + 1) * 4 + (size_t)kBlockN * (D + 8) * 4; }
 
-// ---------------------------------------------------------------- device memory for tile maps
-//
-// A serving loop builds a tile map per prompt.  hipMalloc / hipFree per map would cost more than
-// the pre-pass kernels and hipFree would drain the device, so the blocks a destroyed map held go
-// back to a small per-process cache instead, tagged with an event recorded on the stream that
-// last used them; the next owner's stream waits for that event before touching the block.
-// Host-to-device copies are staged through a ring of pinned buffers and queued on the caller's
-// stream, so nothing here blocks the host or drains the device once the cache is warm.  Cached
-// blocks and pinned buffers are kept until the process ends.
-
-struct CachedBlock {
-    int device;
-    void *ptr;
-    size_t cap;
-    std::shared_ptr<EventHolder> released;   // last use of the block by its previous owner (may be null: never used)
-};
-struct StagingBuffer {
-    void *host = nullptr;
-    size_t cap = 0;
-    hipEvent_t done = nullptr;   // the copy out of this buffer
-    bool used = false;
-};
-constexpr size_t kCacheMaxBlocks = 24;
-constexpr int kStagingBuffers = 8;
-std::mutex g_mem_mutex;
-// never destroyed: at process exit the HIP runtime may already be gone
-std::vector<CachedBlock> &g_cache = *new std::vector<CachedBlock>();
-StagingBuffer g_staging[kStagingBuffers];
-int g_staging_next = 0;
-
-// A device block of at least `bytes`, safe to use in work queued on `st` after this call.
-hipError_t pool_acquire(int device, size_t bytes, hipStream_t st, void **out, size_t *cap_out)
-{
-    const size_t want = (bytes + ((size_t)1 << 20) - 1) & ~(((size_t)1 << 20) - 1);   // 1 MiB granules
-    {
-        std::lock_guard<std::mutex> lock(g_mem_mutex);
-        size_t best = g_cache.size();
-        for (size_t i = 0; i < g_cache.size(); ++i)
-            if (g_cache[i].device == device && g_cache[i].cap >= want && g_cache[i].cap <= 2 * want &&
-                (best == g_cache.size() || g_cache[i].cap < g_cache[best].cap))
-                best = i;
-        if (best < g_cache.size()) {
-            const CachedBlock b = g_cache[best];
-            g_cache.erase(g_cache.begin() + best);
-            const hipError_t e = b.released ? hipStreamWaitEvent(st, b.released->ev, 0) : hipSuccess;
-            if (e != hipSuccess) { (void)hipFree(b.ptr); return e; }
-            *out = b.ptr; *cap_out = b.cap;
-            return hipSuccess;
-        }
-    }
-    hipError_t e = hipMalloc(out, want);
-    if (e == hipSuccess) *cap_out = want;
-    return e;
-}
-
-// Hand a block back; `last_use` is the event after which nobody reads or writes it any more.
-void pool_release(int device, void *ptr, size_t cap, const std::shared_ptr<EventHolder> &last_use)
-{
-    if (!ptr) return;
-    std::lock_guard<std::mutex> lock(g_mem_mutex);
-    g_cache.push_back({device, ptr, cap, last_use});
-    if (g_cache.size() > kCacheMaxBlocks) {   // drop the oldest block (hipFree waits for its users)
-        const CachedBlock b = g_cache.front();
-        g_cache.erase(g_cache.begin());
-        (void)hipFree(b.ptr);
-    }
-}
-
-// Queue a host-to-device copy of `bytes` from pageable memory on `st` without blocking the host
-// on the device: the data is copied into a pinned buffer first.
-hipError_t staged_upload(void *dst, const void *src, size_t bytes, hipStream_t st)
-{
-    if (bytes == 0) return hipSuccess;
-    std::lock_guard<std::mutex> lock(g_mem_mutex);
-    StagingBuffer &sb = g_staging[g_staging_next];
-    g_staging_next = (g_staging_next + 1) % kStagingBuffers;
-    hipError_t e;
-    if (sb.used) {   // the copy that last read this buffer must be over (it was queued eight uploads ago)
-        e = hipEventSynchronize(sb.done);
-        if (e != hipSuccess) return e;
-    }
-    if (sb.cap < bytes) {
-        if (sb.host) (void)hipHostFree(sb.host);
-        sb.host = nullptr; sb.cap = 0;
-        const size_t cap = (bytes + ((size_t)1 << 20) - 1) & ~(((size_t)1 << 20) - 1);
-        e = hipHostMalloc(&sb.host, cap, hipHostMallocDefault);
-        if (e != hipSuccess) { sb.host = nullptr; return e; }
-        sb.cap = cap;
-    }
-    if (!sb.done) {
-        e = hipEventCreateWithFlags(&sb.done, hipEventDisableTiming);
-        if (e != hipSuccess) { sb.done = nullptr; return e; }
-    }
-    std::memcpy(sb.host, src, bytes);
-    e = hipMemcpyAsync(dst, sb.host, bytes, hipMemcpyHostToDevice, st);
-    if (e != hipSuccess) return e;
-    e = hipEventRecord(sb.done, st);
-    sb.used = (e == hipSuccess);
-    return e;
-}
-
-void free_device_map(DeviceMap *d)
-{
-    if (!d) return;
-    int cur = -1;
-    (void)hipGetDevice(&cur);
-    if (d->device >= 0 && cur != d->device) (void)hipSetDevice(d->device);
-    pool_release(d->device, d->blob, d->blob_cap, d->last_use);
-    pool_release(d->device, d->vt_buf, d->vt_bytes, d->last_use);
-    pool_release(d->device, d->pair_blob, d->pair_cap, d->last_use);
-    if (cur >= 0 && cur != d->device) (void)hipSetDevice(cur);
-    delete d;
-}
-
 }  // namespace bs
 
 using bs::DeviceMap;
 
-// Copies the arrays of the map to the current device with work queued on `st` (no host-side wait).
-static int upload_on_stream(bs_tilemap *tm, hipStream_t st)
+// ------------------------------------------------------------------------------------ launch
+
+// Scratch of the entry point that allocates nothing (bs_attn_prefill_static): packed K tiles, then
+// packed V^T tiles.  Every GPU the library runs on holds its own copy until the process ends.  In
+// host code the name below is only a handle for hipGetSymbolAddress; kernels get the per-device
+// address that call returns.
+constexpr size_t kStaticScratchBytes = (size_t)BS_STATIC_SCRATCH_MIB << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_device_mutex;
+void *g_scratch_ptr[kMaxDevices];       // device address of `scratch` on each device (looked up once)
+bool g_attr_set[kMaxDevices];           // dynamic-LDS limits of the kernels raised on this device
+
+// Once per device, with that device current: the address of its copy of `scratch`, and the
+// kernels' dynamic LDS limits.  Allocates nothing.
+int device_setup(int dev, void **scratch_out)
 {
-    if (!tm) return BS_EINVAL;
-    if (tm->dev) return BS_OK;
-    if (tm->bn > 64) return BS_EUNSUPPORTED;  // the per-tile key bit masks are 64 wide
-    int dev = -1;
-    hipError_t e = hipGetDevice(&dev);
-    if (e != hipSuccess) return bs::fail_hip(e, "hipGetDevice");
-
-    const int64_t M1 = (int64_t)tm->M + 1;
-    int64_t total_ranges = 0;
-    for (int c = 0; c < 4; ++c) total_ranges += (int64_t)tm->cls[c].ranges.size();
-    if (total_ranges >= INT32_MAX) return BS_EUNSUPPORTED;
-    const size_t G1 = tm->spans.size() + 1;
-
-    auto align = [](size_t x) { return (x + 255) & ~(size_t)255; };
-    const size_t off_code = 0;
-    const size_t off_rows = align(off_code + (size_t)tm->L * 4);
-    const size_t off_keys = align(off_rows + tm->row_order.size() * 4);
-    const size_t off_fbefore = align(off_keys + tm->key_order.size() * 4);
-    const size_t off_sfree = align(off_fbefore + std::max<size_t>(tm->free_before.size(), 1) * 4);
-    const size_t off_tbits = align(off_sfree + std::max<size_t>(tm->span_free_range.size(), 2) * 4);
-    const size_t off_sbits = align(off_tbits + (size_t)tm->N * 8);
-    const size_t off_spans = align(off_sbits + (size_t)tm->N * 8);
-    const size_t off_rowptr = align(off_spans + G1 * 8);
-    const size_t off_rowtiles = align(off_rowptr + (size_t)(4 * M1) * 4);
-    const size_t off_ranges = align(off_rowtiles + (size_t)(4 * tm->M) * 4);
-    const size_t off_work = align(off_ranges + (size_t)std::max<int64_t>(total_ranges, 1) * 8);
-    const size_t off_class = align(off_work + tm->work.size() * 8);
-    const size_t bytes = align(off_class + tm->head_class.size());
-
-    std::vector<unsigned char> host;
-    DeviceMap *d = nullptr;
-    try {
-        host.assign(bytes, 0);
-        d = new DeviceMap();
-    } catch (const std::bad_alloc &) {
-        return BS_ENOMEM;
+    if (dev < 0 || dev >= kMaxDevices) return bs::fail_msg(BS_EUNSUPPORTED, "device ordinal above 63");
+    std::lock_guard<std::mutex> lock(g_device_mutex);
+    hipError_t e;
+    if (!g_attr_set[dev]) {
+        e = hipFuncSetAttribute(reinterpret_cast<const void *>(bs::attn_prefill_bf16<128>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, bs::bf16_lds_bytes<128>());
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute(reinterpret_cast<const void *>(bs::attn_prefill_bf16<64>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, bs::bf16_lds_bytes<64>());
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute(reinterpret_cast<const void *>(bs::attn_prefill_f32<128>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)bs::f32_lds_bytes<128>());
+        if (e != hipSuccess) return bs::fail_hip(e, "hipFuncSetAttribute");
+        g_attr_set[dev] = true;
     }
-    std::memcpy(host.data() + off_code, tm->code.data(), (size_t)tm->L * 4);
-    std::memcpy(host.data() + off_rows, tm->row_order.data(), tm->row_order.size() * 4);
-    std::memcpy(host.data() + off_keys, tm->key_order.data(), tm->key_order.size() * 4);
-    if (!tm->free_before.empty()) std::memcpy(host.data() + off_fbefore, tm->free_before.data(), tm->free_before.size() * 4);
-    if (!tm->span_free_range.empty())
-        std::memcpy(host.data() + off_sfree, tm->span_free_range.data(), tm->span_free_range.size() * 4);
-    std::memcpy(host.data() + off_tbits, tm->text_bits.data(), (size_t)tm->N * 8);
-    std::memcpy(host.data() + off_sbits, tm->sink_bits.data(), (size_t)tm->N * 8);
-    int2 *sp = reinterpret_cast<int2 *>(host.data() + off_spans);
-    sp[0] = make_int2(0, 0);
-    for (size_t g = 0; g < tm->spans.size(); ++g) sp[g + 1] = make_int2(tm->spans[g].start, tm->spans[g].end);
-    int32_t *rp = reinterpret_cast<int32_t *>(host.data() + off_rowptr);
-    int32_t *rt = reinterpret_cast<int32_t *>(host.data() + off_rowtiles);
-    int2 *rg = reinterpret_cast<int2 *>(host.data() + off_ranges);
-    int64_t base = 0;
-    for (int c = 0; c < 4; ++c) {
-        const bs::ClassLists &cl = tm->cls[c];
-        for (int64_t m = 0; m < M1; ++m) rp[c * M1 + m] = (int32_t)(base + cl.row_ptr[m]);
-        for (int64_t m = 0; m < tm->M; ++m) rt[c * (int64_t)tm->M + m] = cl.row_tiles[m];
-        for (size_t i = 0; i < cl.ranges.size(); ++i) rg[base + i] = make_int2(cl.ranges[i].begin, cl.ranges[i].end_state);
-        base += (int64_t)cl.ranges.size();
-    }
-    int2 *wk = reinterpret_cast<int2 *>(host.data() + off_work);
-    for (size_t i = 0; i < tm->work.size(); ++i) wk[i] = make_int2(tm->work[i].head, tm->work[i].q_tile);
-    std::memcpy(host.data() + off_class, tm->head_class.data(), tm->head_class.size());
-
-    void *blob = nullptr;
-    size_t blob_cap = 0;
-    e = bs::pool_acquire(dev, bytes, st, &blob, &blob_cap);
-    if (e != hipSuccess) {
-        delete d;
-        return bs::fail_hip(e, "hipMalloc(tile map)");
-    }
-    e = bs::staged_upload(blob, host.data(), bytes, st);
-    std::shared_ptr<bs::EventHolder> holder;
-    if (e == hipSuccess) {
-        try {
-            holder = std::make_shared<bs::EventHolder>();
-        } catch (const std::bad_alloc &) {
-            e = hipErrorOutOfMemory;
+    if (scratch_out) {
+        if (!g_scratch_ptr[dev]) {
+            void *ptr = nullptr;
+            e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+            if (e != hipSuccess || !ptr) return bs::fail_hip(e, "hipGetSymbolAddress(scratch)");
+            g_scratch_ptr[dev] = ptr;
         }
+        *scratch_out = g_scratch_ptr[dev];
     }
-    if (e == hipSuccess) e = hipEventCreateWithFlags(&holder->ev, hipEventDisableTiming);
-    if (e == hipSuccess) e = hipEventRecord(holder->ev, st);
-    if (e != hipSuccess) {
-        (void)hipFree(blob);
-        delete d;
-        return bs::fail_hip(e, "hipMemcpyAsync(tile map)");
-    }
-    unsigned char *b = static_cast<unsigned char *>(blob);
-    d->device = dev;
-    d->blob = blob;
-    d->blob_cap = blob_cap;
-    d->last_stream = st;
-    d->last_use = holder;
-    d->code = reinterpret_cast<const uint32_t *>(b + off_code);
-    d->row_order = reinterpret_cast<const int32_t *>(b + off_rows);
-    d->key_order = reinterpret_cast<const int32_t *>(b + off_keys);
-    d->free_before = reinterpret_cast<const int32_t *>(b + off_fbefore);
-    d->span_free = reinterpret_cast<const int2 *>(b + off_sfree);
-    d->text_bits = reinterpret_cast<const uint64_t *>(b + off_tbits);
-    d->sink_bits = reinterpret_cast<const uint64_t *>(b + off_sbits);
-    d->span_range = reinterpret_cast<const int2 *>(b + off_spans);
-    d->row_ptr = reinterpret_cast<const int32_t *>(b + off_rowptr);
-    d->row_tiles = reinterpret_cast<const int32_t *>(b + off_rowtiles);
-    d->ranges = reinterpret_cast<const int2 *>(b + off_ranges);
-    d->work = reinterpret_cast<const int2 *>(b + off_work);
-    d->head_class = b + off_class;
-    d->n_work = (int32_t)tm->work.size();
-    tm->dev = d;
-    tm->dev_free = bs::free_device_map;
     return BS_OK;
 }
+
+int check_call(const void *q, const void *k, const void *v, void *out, const bs_tilemap *tm, int32_t dtype,
+               int32_t n_q_heads, int32_t gqa_group, int32_t head_dim, float scale)
+{
+    if (!q || !k || !v || !out || !tm) return BS_EINVAL;
+    if (n_q_heads <= 0 || gqa_group <= 0 || n_q_heads % gqa_group != 0) return BS_EINVAL;
+    if (n_q_heads != tm->n_q_heads) return BS_EINVAL;
+    if (!(scale > 0.f) || !(scale < INFINITY)) return BS_EINVAL;  // masking relies on -inf * scale = -inf
+    if (tm->bm != bs::kBlockM || tm->bn != bs::kBlockN) return BS_EUNSUPPORTED;
+    if (head_dim != 64 && head_dim != 128) return BS_EUNSUPPORTED;
+    if (dtype != BS_BF16 && dtype != BS_F32) return BS_EUNSUPPORTED;
+    if (((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)out) & 15) return BS_EINVAL;
+    return BS_OK;
+}
+
+bs::KernelArgs kernel_args(const void *q, const void *k, const void *v, void *out, const bs_tilemap *tm,
+                           int32_t gqa_group, float scale)
+{
+    bs::KernelArgs a;
+    a.q = q; a.k = k; a.v = v; a.out = out;
+    a.L = tm->L; a.M = tm->M; a.G = gqa_group;
+    a.scale_log2e = scale * 1.4426950408889634f;
+    a.n_prompt_tiles = tm->N0;
+    a.packed = tm->packed;
+    a.intra_compact = tm->intra_compact;
+    a.bidir = tm->bidir;
+    a.window = tm->window;
+    return a;
+}
+
+// Pre-pass (K and V^T into per-key-tile blocks of `workspace`) and the attention kernel.
+template <int D>
+void launch_bf16(const bs::KernelArgs &a, const bs_tilemap *tm, const DeviceMap *d, void *workspace, size_t pack_bytes,
+                 int n_kv_heads, hipStream_t st, void *ev_main_start)
+{
+    __bf16 *kp = static_cast<__bf16 *>(workspace);
+    __bf16 *vt = reinterpret_cast<__bf16 *>(static_cast<char *>(workspace) + pack_bytes);
+    const dim3 tgrid((unsigned)tm->N, (unsigned)n_kv_heads);
+    const dim3 pgrid((unsigned)d->n_pairs), pblock(bs::kPingPongThreads);
+    hipLaunchKernelGGL(bs::pack_k_tiles<D>, tgrid, dim3(256), 0, st, static_cast<const __bf16 *>(a.k), kp, d->key_order, tm->L, tm->N);
+    hipLaunchKernelGGL(bs::pack_vt_tiles<D>, tgrid, dim3(256), 0, st, static_cast<const __bf16 *>(a.v), vt, d->key_order, tm->L, tm->N);
+    if (ev_main_start) (void)hipEventRecord(static_cast<hipEvent_t>(ev_main_start), st);
+    hipLaunchKernelGGL(bs::attn_prefill_bf16<D>, pgrid, pblock, bs::bf16_lds_bytes<D>(), st, a, d->code, d->text_bits,
+                       d->sink_bits, d->span_range, d->row_order, d->free_before, d->span_free, d->pair_items,
+                       d->pair_ranges, kp, vt, tm->N);
+}
+
+size_t bf16_pack_bytes(const bs_tilemap *tm, int n_kv_heads, int head_dim)
+{
+    return (size_t)n_kv_heads * tm->N * (size_t)head_dim * bs::kBlockN * 2;   // one of the two halves (K, V^T)
+}
+
+}  // namespace
 
 extern "C" int bs_tilemap_upload(bs_tilemap *tm)
 {
     if (!tm) return BS_EINVAL;
     if (tm->dev) return BS_OK;
-    const int rc = upload_on_stream(tm, nullptr);
+    const int rc = bs::upload_prompt_part(tm, nullptr);
     if (rc != BS_OK) return rc;
     const hipError_t e = hipStreamSynchronize(nullptr);   // this entry point promises a finished upload
     return e == hipSuccess ? BS_OK : bs::fail_hip(e, "hipStreamSynchronize");
+}
+
+extern "C" int bs_tilemap_prepare(bs_tilemap *tm, int32_t dtype, int32_t gqa_group, void *stream)
+{
+    if (!tm || gqa_group <= 0 || tm->n_q_heads % gqa_group != 0) return BS_EINVAL;
+    if (dtype != BS_BF16 && dtype != BS_F32) return BS_EUNSUPPORTED;
+    if (tm->bm != bs::kBlockM || tm->bn != bs::kBlockN) return BS_EUNSUPPORTED;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    int rc = bs::upload_prompt_part(tm, st);
+    if (rc != BS_OK) return rc;
+    DeviceMap *d = tm->dev;
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return bs::fail_hip(e, "hipGetDevice");
+    if (dev != d->device) return BS_EINVAL;  // the map lives on another device
+    void *unused = nullptr;
+    if ((rc = device_setup(dev, &unused)) != BS_OK) return rc;
+    if ((rc = bs::order_after_last_use(d, st)) != BS_OK) return rc;
+    rc = bs::upload_binding(tm, dtype == BS_BF16 ? bs::kBindPairPlan : bs::kBindWorkList, gqa_group, st);
+    if (rc != BS_OK) return rc;
+    e = hipEventRecord(d->last_use->ev, st);
+    return e == hipSuccess ? BS_OK : bs::fail_hip(e, "hipEventRecord");
 }
 
 extern "C" int bs_attn_prefill(const void *q, const void *k, const void *v, void *out, bs_tilemap *tm,
@@ -1303,114 +1057,40 @@ extern "C" int bs_attn_prefill_ex(const void *q, const void *k, const void *v, v
                                   int32_t dtype, int32_t n_q_heads, int32_t gqa_group, int32_t head_dim,
                                   float scale, void *stream, void *ev_main_start, void *ev_main_stop)
 {
-    if (!q || !k || !v || !out || !tm) return BS_EINVAL;
-    if (n_q_heads <= 0 || gqa_group <= 0 || n_q_heads % gqa_group != 0) return BS_EINVAL;
-    if (n_q_heads != tm->n_q_heads) return BS_EINVAL;
-    if (!(scale > 0.f) || !(scale < INFINITY)) return BS_EINVAL;  // masking relies on -inf * scale = -inf
-    if (tm->bm != bs::kBlockM || tm->bn != bs::kBlockN) return BS_EUNSUPPORTED;
-    if (head_dim != 64 && head_dim != 128) return BS_EUNSUPPORTED;
-    if (dtype != BS_BF16 && dtype != BS_F32) return BS_EUNSUPPORTED;
-    if (((uintptr_t)q | (uintptr_t)k | (uintptr_t)v | (uintptr_t)out) & 15) return BS_EINVAL;
-
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    int rc = upload_on_stream(tm, st);
+    int rc = check_call(q, k, v, out, tm, dtype, n_q_heads, gqa_group, head_dim, scale);
     if (rc != BS_OK) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if ((rc = bs::upload_prompt_part(tm, st)) != BS_OK) return rc;
     DeviceMap *d = tm->dev;
     int dev = -1;
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return bs::fail_hip(e, "hipGetDevice");
     if (dev != d->device) return BS_EINVAL;  // the map lives on another device
-    if (d->last_stream != st) {
-        // the buffers of the map were last written or read on another stream: order this call after that
-        e = hipStreamWaitEvent(st, d->last_use->ev, 0);
-        if (e != hipSuccess) return bs::fail_hip(e, "hipStreamWaitEvent");
-        d->last_stream = st;
-    }
+    if ((rc = device_setup(dev, nullptr)) != BS_OK) return rc;
+    if ((rc = bs::order_after_last_use(d, st)) != BS_OK) return rc;
+    rc = bs::upload_binding(tm, dtype == BS_BF16 ? bs::kBindPairPlan : bs::kBindWorkList, gqa_group, st);
+    if (rc != BS_OK) return rc;
 
-    bs::KernelArgs a;
-    a.q = q; a.k = k; a.v = v; a.out = out;
-    a.L = tm->L; a.M = tm->M; a.G = gqa_group;
-    a.scale_log2e = scale * 1.4426950408889634f;
-    a.n_prompt_tiles = tm->N0;
-    a.packed = tm->packed;
-    a.intra_compact = tm->intra_compact;
-    a.bidir = tm->bidir;
-    a.window = tm->window;
-
-    const dim3 grid((unsigned)d->n_work), block(bs::kThreads);
+    const bs::KernelArgs a = kernel_args(q, k, v, out, tm, gqa_group, scale);
     if (dtype == BS_BF16) {
-        // pre-pass: pack V into transposed, swizzled key tiles (workspace owned by the map)
+        // workspace of the pre-pass: packed K tiles, then packed V^T tiles (owned by the map)
         const int n_kv_heads = n_q_heads / gqa_group;
-        const size_t pack_bytes = (size_t)n_kv_heads * tm->N * (size_t)head_dim * bs::kBlockN * 2;
-        const size_t vt_need = 2 * pack_bytes;  // packed K tiles, then packed V^T tiles
-        if (d->vt_bytes < vt_need) {
+        const size_t pack_bytes = bf16_pack_bytes(tm, n_kv_heads, head_dim);
+        if (d->vt_bytes < 2 * pack_bytes) {
             bs::pool_release(dev, d->vt_buf, d->vt_bytes, d->last_use);
             d->vt_buf = nullptr; d->vt_bytes = 0;
-            e = bs::pool_acquire(dev, vt_need, st, &d->vt_buf, &d->vt_bytes);
+            e = bs::pool_acquire(dev, 2 * pack_bytes, st, &d->vt_buf, &d->vt_bytes);
             if (e != hipSuccess) { d->vt_buf = nullptr; d->vt_bytes = 0; return bs::fail_hip(e, "hipMalloc(K / V^T workspace)"); }
         }
-        __bf16 *kp = static_cast<__bf16 *>(d->vt_buf);
-        __bf16 *vt = reinterpret_cast<__bf16 *>(static_cast<char *>(d->vt_buf) + pack_bytes);
-        // work units: pairs of items that share a KV head (depends on gqa_group; cached)
-        if (d->pair_G != gqa_group) {
-            try {
-                bs_plan_pairs(tm, gqa_group);
-            } catch (const std::bad_alloc &) {
-                return BS_ENOMEM;
-            }
-            const bs::PairPlan &plan = tm->pairs;
-            if (plan.ranges.size() >= (size_t)INT32_MAX) return BS_EUNSUPPORTED;
-            bs::pool_release(dev, d->pair_blob, d->pair_cap, d->last_use);
-            d->pair_blob = nullptr; d->pair_cap = 0; d->pair_G = 0;
-            const size_t items_bytes = (plan.items.size() * sizeof(bs::PairItem) + 255) & ~(size_t)255;
-            const size_t ranges_bytes = std::max<size_t>(plan.ranges.size(), 1) * sizeof(bs::PairRange);
-            e = bs::pool_acquire(dev, items_bytes + ranges_bytes, st, &d->pair_blob, &d->pair_cap);
-            if (e != hipSuccess) { d->pair_blob = nullptr; d->pair_cap = 0; return bs::fail_hip(e, "hipMalloc(work units)"); }
-            e = bs::staged_upload(d->pair_blob, plan.items.data(), plan.items.size() * sizeof(bs::PairItem), st);
-            if (e == hipSuccess)
-                e = bs::staged_upload(static_cast<char *>(d->pair_blob) + items_bytes, plan.ranges.data(),
-                                      plan.ranges.size() * sizeof(bs::PairRange), st);
-            if (e != hipSuccess) return bs::fail_hip(e, "hipMemcpyAsync(work units)");
-            d->pair_items = static_cast<const int4 *>(d->pair_blob);
-            d->pair_ranges = reinterpret_cast<const int2 *>(static_cast<char *>(d->pair_blob) + items_bytes);
-            d->n_pairs = (int32_t)plan.items.size();
-            d->pair_G = gqa_group;
-        }
-        const dim3 tgrid((unsigned)tm->N, (unsigned)n_kv_heads);
-        const dim3 pgrid((unsigned)d->n_pairs), pblock(bs::kPingPongThreads);
-        if (head_dim == 128) {
-            constexpr int lds = bs::bf16_lds_bytes<128>();
-            e = hipFuncSetAttribute(reinterpret_cast<const void *>(bs::attn_prefill_bf16<128>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-            if (e != hipSuccess) return bs::fail_hip(e, "hipFuncSetAttribute");
-            hipLaunchKernelGGL(bs::pack_k_tiles<128>, tgrid, dim3(256), 0, st, static_cast<const __bf16 *>(k), kp, d->key_order, tm->L, tm->N);
-            hipLaunchKernelGGL(bs::pack_vt_tiles<128>, tgrid, dim3(256), 0, st, static_cast<const __bf16 *>(v), vt, d->key_order, tm->L, tm->N);
-            if (ev_main_start) (void)hipEventRecord(static_cast<hipEvent_t>(ev_main_start), st);
-            hipLaunchKernelGGL(bs::attn_prefill_bf16<128>, pgrid, pblock, lds, st, a, d->code, d->text_bits, d->sink_bits,
-                               d->span_range, d->head_class, d->row_order, d->free_before, d->span_free, d->pair_items, d->pair_ranges, kp, vt, tm->N);
-        } else {
-            constexpr int lds = bs::bf16_lds_bytes<64>();
-            e = hipFuncSetAttribute(reinterpret_cast<const void *>(bs::attn_prefill_bf16<64>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-            if (e != hipSuccess) return bs::fail_hip(e, "hipFuncSetAttribute");
-            hipLaunchKernelGGL(bs::pack_k_tiles<64>, tgrid, dim3(256), 0, st, static_cast<const __bf16 *>(k), kp, d->key_order, tm->L, tm->N);
-            hipLaunchKernelGGL(bs::pack_vt_tiles<64>, tgrid, dim3(256), 0, st, static_cast<const __bf16 *>(v), vt, d->key_order, tm->L, tm->N);
-            if (ev_main_start) (void)hipEventRecord(static_cast<hipEvent_t>(ev_main_start), st);
-            hipLaunchKernelGGL(bs::attn_prefill_bf16<64>, pgrid, pblock, lds, st, a, d->code, d->text_bits, d->sink_bits,
-                               d->span_range, d->head_class, d->row_order, d->free_before, d->span_free, d->pair_items, d->pair_ranges, kp, vt, tm->N);
-        }
+        if (head_dim == 128) launch_bf16<128>(a, tm, d, d->vt_buf, pack_bytes, n_kv_heads, st, ev_main_start);
+        else launch_bf16<64>(a, tm, d, d->vt_buf, pack_bytes, n_kv_heads, st, ev_main_start);
     } else {
         if (ev_main_start) (void)hipEventRecord(static_cast<hipEvent_t>(ev_main_start), st);
-        if (head_dim == 128) {
-            constexpr size_t lds = bs::f32_lds_bytes<128>();
-            e = hipFuncSetAttribute(reinterpret_cast<const void *>(bs::attn_prefill_f32<128>),
-                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-            if (e != hipSuccess) return bs::fail_hip(e, "hipFuncSetAttribute");
-            hipLaunchKernelGGL(bs::attn_prefill_f32<128>, grid, block, lds, st, a, BS_MAP_ARGS(d));
-        } else {
-            constexpr size_t lds = bs::f32_lds_bytes<64>();
-            hipLaunchKernelGGL(bs::attn_prefill_f32<64>, grid, block, lds, st, a, BS_MAP_ARGS(d));
-        }
+        const dim3 grid((unsigned)d->n_work), block(bs::kThreads);
+        if (head_dim == 128)
+            hipLaunchKernelGGL(bs::attn_prefill_f32<128>, grid, block, bs::f32_lds_bytes<128>(), st, a, BS_MAP_ARGS(d));
+        else
+            hipLaunchKernelGGL(bs::attn_prefill_f32<64>, grid, block, bs::f32_lds_bytes<64>(), st, a, BS_MAP_ARGS(d));
     }
     e = hipGetLastError();
     if (e != hipSuccess) return bs::fail_hip(e, "kernel launch");
@@ -1420,18 +1100,43 @@ extern "C" int bs_attn_prefill_ex(const void *q, const void *k, const void *v, v
     return BS_OK;
 }
 
-extern "C" const char *bs_last_error(void) { return bs::g_last_error; }
+extern "C" int64_t bs_static_scratch_bytes(void) { return (int64_t)kStaticScratchBytes; }
 
-#ifdef BS_PHASE_TIMING
-extern "C" int bs_debug_phase_cycles(unsigned long long *out8, int reset)   // out8: 12 values
+extern "C" int bs_attn_prefill_static(const void *q, const void *k, const void *v, void *out, bs_tilemap *tm,
+                                      int32_t n_q_heads, int32_t gqa_group, int32_t head_dim, float scale, void *stream)
 {
-    if (hipMemcpyFromSymbol(out8, HIP_SYMBOL(bs::g_phase_cycles), 64) != hipSuccess) return BS_EHIP;
-    if (hipMemcpyFromSymbol(out8 + 8, HIP_SYMBOL(bs::g_unit_cycles), 32) != hipSuccess) return BS_EHIP;
-    if (reset) {
-        unsigned long long z[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-        if (hipMemcpyToSymbol(HIP_SYMBOL(bs::g_phase_cycles), z, 64) != hipSuccess) return BS_EHIP;
-        if (hipMemcpyToSymbol(HIP_SYMBOL(bs::g_unit_cycles), z, 32) != hipSuccess) return BS_EHIP;
+    int rc = check_call(q, k, v, out, tm, BS_BF16, n_q_heads, gqa_group, head_dim, scale);
+    if (rc != BS_OK) return rc;
+    DeviceMap *d = tm->dev;
+    if (!d || d->bind_kind != bs::kBindPairPlan || d->bind_G != gqa_group || d->bind_epoch != tm->class_epoch)
+        return bs::fail_msg(BS_EINVAL, "bs_attn_prefill_static: call bs_tilemap_prepare(tm, BS_BF16, gqa_group, stream) first "
+                                       "(after every bs_tilemap_rebind); this entry point uploads and allocates nothing");
+    const int n_kv_heads = n_q_heads / gqa_group;
+    const size_t pack_bytes = bf16_pack_bytes(tm, n_kv_heads, head_dim);
+    if (2 * pack_bytes > kStaticScratchBytes) {
+        snprintf(bs::g_last_error, sizeof bs::g_last_error,
+                 "bs_attn_prefill_static: packed K / V^T tiles need %zu bytes, the static scratch holds %zu "
+                 "(n_kv_heads * key tiles * head_dim * 256 bytes); use bs_attn_prefill", 2 * pack_bytes, kStaticScratchBytes);
+        return BS_EUNSUPPORTED;
     }
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return bs::fail_hip(e, "hipGetDevice");
+    if (dev != d->device) return BS_EINVAL;  // the map lives on another device
+    void *ws = nullptr;
+    if ((rc = device_setup(dev, &ws)) != BS_OK) return rc;   // looks the address up on the first call per device
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if ((rc = bs::order_after_last_use(d, st)) != BS_OK) return rc;
+    const bs::KernelArgs a = kernel_args(q, k, v, out, tm, gqa_group, scale);
+    // the pre-pass writes every slot of every tile it covers (keys, or zeros): nothing of the
+    // previous call's contents is read
+    if (head_dim == 128) launch_bf16<128>(a, tm, d, ws, pack_bytes, n_kv_heads, st, nullptr);
+    else launch_bf16<64>(a, tm, d, ws, pack_bytes, n_kv_heads, st, nullptr);
+    e = hipGetLastError();
+    if (e != hipSuccess) return bs::fail_hip(e, "kernel launch");
+    e = hipEventRecord(d->last_use->ev, st);
+    if (e != hipSuccess) return bs::fail_hip(e, "hipEventRecord");
     return BS_OK;
 }
-#endif
+
+extern "C" const char *bs_last_error(void) { return bs::g_last_error; }

@@ -3,7 +3,8 @@
 // Alg. 1 compares, per head, the output of attention under each sparse mask with the output under
 // the dense causal mask and keeps the first mask (Sink, Intra-Image, Intra-Image+Sink) whose
 // normalised squared error is below alpha_layer.  Here the four outputs come from the library's
-// own prefill kernel (one call per mask with every head set to that class), the error is reduced
+// own prefill kernel (ONE tile map of the prompt, bound in turn to "every head Dense / Sink /
+// Intra-Image / Intra-Image+Sink"), the error is reduced
 // by an HBM-bound kernel that reads both outputs once, and a last tiny kernel takes the decision
 // in fp64.  Evaluating all three masks for every head instead of stopping at the first that
 // passes gives the same head types (the stop only saves work, and the sparse runs are the cheap
@@ -20,7 +21,7 @@
 #include <vector>
 
 #include "blindsight.h"
-#include "hip_internal.h"
+#include "device_map.h"
 
 namespace bs {
 
@@ -155,15 +156,17 @@ static int launch_sq_error(const void *a, const void *r, int dtype, int heads, i
     return e == hipSuccess ? BS_OK : fail_hip(e, "head_sq_error launch");
 }
 
-// Device buffers of one characterisation, freed on every way out.
+// Device buffers of one characterisation, from the library's block cache; handed back on every way
+// out (the caller has drained the stream by then, so the blocks are free for anyone at once).
 struct Buffers {
-    void *ref = nullptr, *cand = nullptr;
-    double *sums = nullptr, *nmse = nullptr;
-    uint8_t *type = nullptr;
+    int device = -1;
+    void *ref = nullptr, *cand = nullptr, *small = nullptr;   // small: sums [6 Hq], nmse [3 Hq], types [Hq]
+    size_t ref_cap = 0, cand_cap = 0, small_cap = 0;
     ~Buffers()
     {
-        for (void *p : {ref, cand, (void *)sums, (void *)nmse, (void *)type})
-            if (p) (void)hipFree(p);
+        pool_release(device, ref, ref_cap, nullptr);
+        pool_release(device, cand, cand_cap, nullptr);
+        pool_release(device, small, small_cap, nullptr);
     }
 };
 
@@ -199,41 +202,46 @@ extern "C" int bs_characterize_prompt(const void *q, const void *k, const void *
     const size_t out_bytes = (size_t)n_q_heads * per_head * (dtype == BS_BF16 ? 2 : 4);
     Buffers b;
     hipError_t e;
-    if ((e = hipMalloc(&b.ref, out_bytes)) != hipSuccess) return fail_hip(e, "hipMalloc(reference output)");
-    if ((e = hipMalloc(&b.cand, out_bytes)) != hipSuccess) return fail_hip(e, "hipMalloc(masked output)");
-    if ((e = hipMalloc((void **)&b.sums, sizeof(double) * 6 * n_q_heads)) != hipSuccess) return fail_hip(e, "hipMalloc(sums)");
-    if ((e = hipMalloc((void **)&b.nmse, sizeof(double) * 3 * n_q_heads)) != hipSuccess) return fail_hip(e, "hipMalloc(nmse)");
-    if ((e = hipMalloc((void **)&b.type, n_q_heads)) != hipSuccess) return fail_hip(e, "hipMalloc(head_type)");
+    if ((e = hipGetDevice(&b.device)) != hipSuccess) return fail_hip(e, "hipGetDevice");
+    const size_t small_bytes = sizeof(double) * 9 * (size_t)n_q_heads + (size_t)n_q_heads;
+    if ((e = pool_acquire(b.device, out_bytes, st, &b.ref, &b.ref_cap)) != hipSuccess) return fail_hip(e, "hipMalloc(reference output)");
+    if ((e = pool_acquire(b.device, out_bytes, st, &b.cand, &b.cand_cap)) != hipSuccess) return fail_hip(e, "hipMalloc(masked output)");
+    if ((e = pool_acquire(b.device, small_bytes, st, &b.small, &b.small_cap)) != hipSuccess) return fail_hip(e, "hipMalloc(sums)");
+    double *sums = static_cast<double *>(b.small), *nmse_dev = sums + 6 * (size_t)n_q_heads;
+    uint8_t *type_dev = reinterpret_cast<uint8_t *>(nmse_dev + 3 * (size_t)n_q_heads);
 
     int rc = BS_OK;
-    hipLaunchKernelGGL(fill_zero, dim3((6 * n_q_heads + 255) / 256), dim3(256), 0, st, b.sums, 6 * n_q_heads);
+    hipLaunchKernelGGL(fill_zero, dim3((6 * n_q_heads + 255) / 256), dim3(256), 0, st, sums, 6 * n_q_heads);
     std::vector<uint8_t> cls;
     try {
-        cls.resize(n_q_heads);
+        cls.assign(n_q_heads, (uint8_t)BS_DENSE);
     } catch (const std::bad_alloc &) {
-        return BS_ENOMEM;   // nothing queued yet beyond the clearing kernel; the buffers are freed (hipFree waits)
+        rc = BS_ENOMEM;
     }
-    for (int c = 0; c < 4 && rc == BS_OK; ++c) {   // Dense reference, then Sink, Intra-Image, Intra-Image+Sink
-        std::fill(cls.begin(), cls.end(), (uint8_t)c);
-        bs_tilemap *tm = nullptr;
+    // one tile map of the prompt for the four runs: the per-class lists depend on the spans only
+    bs_tilemap *tm = nullptr;
+    if (rc == BS_OK)
         rc = bs_build_tilemap_model(spans, n_spans, seq_len, cls.data(), n_q_heads, sink_len, 128, 64, map_flags,
                                     sink_offsets, n_sink_offsets, window, &tm);
-        if (rc != BS_OK) break;
-        rc = bs_attn_prefill(q, k, v, c == 0 ? b.ref : b.cand, tm, dtype, n_q_heads, gqa_group, head_dim, scale, st);
-        bs_tilemap_destroy(tm);
+    for (int c = 0; c < 4 && rc == BS_OK; ++c) {   // Dense reference, then Sink, Intra-Image, Intra-Image+Sink
+        std::fill(cls.begin(), cls.end(), (uint8_t)c);
+        rc = bs_tilemap_rebind(tm, cls.data(), n_q_heads);
+        if (rc == BS_OK)
+            rc = bs_attn_prefill(q, k, v, c == 0 ? b.ref : b.cand, tm, dtype, n_q_heads, gqa_group, head_dim, scale, st);
         if (rc == BS_OK && c > 0)
-            rc = launch_sq_error(b.cand, b.ref, dtype, n_q_heads, per_head, b.sums + (size_t)(c - 1) * 2 * n_q_heads, st);
+            rc = launch_sq_error(b.cand, b.ref, dtype, n_q_heads, per_head, sums + (size_t)(c - 1) * 2 * n_q_heads, st);
     }
+    bs_tilemap_destroy(tm);
     if (rc == BS_OK) {
-        hipLaunchKernelGGL(select_head_type, dim3((n_q_heads + 63) / 64), dim3(64), 0, st, b.sums, n_q_heads, alpha,
-                           b.nmse, b.type);
+        hipLaunchKernelGGL(select_head_type, dim3((n_q_heads + 63) / 64), dim3(64), 0, st, sums, n_q_heads, alpha,
+                           nmse_dev, type_dev);
         if ((e = hipGetLastError()) != hipSuccess) rc = fail_hip(e, "select_head_type launch");
     }
-    // the buffers are about to be freed: wait for the queued work on every way out
+    // the buffers are about to be handed back: wait for the queued work on every way out
     if ((e = hipStreamSynchronize(st)) != hipSuccess && rc == BS_OK) rc = fail_hip(e, "hipStreamSynchronize");
     if (rc != BS_OK) return rc;
-    if ((e = hipMemcpy(head_type, b.type, n_q_heads, hipMemcpyDeviceToHost)) != hipSuccess) return fail_hip(e, "hipMemcpy(head_type)");
-    if (nmse && (e = hipMemcpy(nmse, b.nmse, sizeof(double) * 3 * n_q_heads, hipMemcpyDeviceToHost)) != hipSuccess)
+    if ((e = hipMemcpy(head_type, type_dev, n_q_heads, hipMemcpyDeviceToHost)) != hipSuccess) return fail_hip(e, "hipMemcpy(head_type)");
+    if (nmse && (e = hipMemcpy(nmse, nmse_dev, sizeof(double) * 3 * n_q_heads, hipMemcpyDeviceToHost)) != hipSuccess)
         return fail_hip(e, "hipMemcpy(nmse)");
     return BS_OK;
 }

@@ -636,25 +636,49 @@ extern "C" int bs_build_tilemap_model(const bs_span *spans, int32_t n_spans, int
         }
         count_pairs(G, tm->code, tm->cls);
 
-        // work list: heaviest (head, query tile) first so the tail of the launch is short;
-        // ties keep one KV group's heads of a query tile next to each other.
-        tm->work.resize((size_t)n_q_heads * tm->M);
-        size_t w = 0;
-        for (int32_t h = 0; h < n_q_heads; ++h)
-            for (int32_t m = 0; m < tm->M; ++m) tm->work[w++] = {h, m};
-        const bs_tilemap *t = tm;
-        std::stable_sort(tm->work.begin(), tm->work.end(), [t](const bs::WorkItem &a, const bs::WorkItem &b) {
-            int32_t ca = t->cls[t->head_class[a.head]].row_tiles[a.q_tile];
-            int32_t cb = t->cls[t->head_class[b.head]].row_tiles[b.q_tile];
-            if (ca != cb) return ca > cb;
-            if (a.q_tile != b.q_tile) return a.q_tile > b.q_tile;
-            return a.head < b.head;
-        });
     } catch (const std::bad_alloc &) {
         delete tm;
         return BS_ENOMEM;
     }
     *out = tm;
+    return BS_OK;
+}
+
+// Work list of the fp32 kernel: heaviest (head, query tile) first so the tail of the launch is
+// short; ties keep one KV group's heads of a query tile next to each other.
+void bs_plan_work(bs_tilemap *tm)
+{
+    if (tm->work_epoch == tm->class_epoch) return;
+    const int32_t H = tm->n_q_heads;
+    tm->work.resize((size_t)H * tm->M);
+    size_t w = 0;
+    for (int32_t h = 0; h < H; ++h)
+        for (int32_t m = 0; m < tm->M; ++m) tm->work[w++] = {h, m};
+    const bs_tilemap *t = tm;
+    std::stable_sort(tm->work.begin(), tm->work.end(), [t](const bs::WorkItem &a, const bs::WorkItem &b) {
+        int32_t ca = t->cls[t->head_class[a.head]].row_tiles[a.q_tile];
+        int32_t cb = t->cls[t->head_class[b.head]].row_tiles[b.q_tile];
+        if (ca != cb) return ca > cb;
+        if (a.q_tile != b.q_tile) return a.q_tile > b.q_tile;
+        return a.head < b.head;
+    });
+    tm->work_epoch = tm->class_epoch;
+}
+
+extern "C" int bs_tilemap_rebind(bs_tilemap *tm, const uint8_t *head_class, int32_t n_q_heads)
+{
+    if (!tm || !head_class || n_q_heads <= 0) return BS_EINVAL;
+    for (int32_t h = 0; h < n_q_heads; ++h)
+        if (head_class[h] > 3) return BS_EINVAL;
+    if ((size_t)n_q_heads == tm->head_class.size() && std::equal(head_class, head_class + n_q_heads, tm->head_class.begin()))
+        return BS_OK;   // same vector: the work units stay valid
+    try {
+        tm->head_class.assign(head_class, head_class + n_q_heads);
+    } catch (const std::bad_alloc &) {
+        return BS_ENOMEM;
+    }
+    tm->n_q_heads = n_q_heads;
+    ++tm->class_epoch;
     return BS_OK;
 }
 
@@ -671,7 +695,7 @@ extern "C" int bs_build_tilemap_model(const bs_span *spans, int32_t n_spans, int
 void bs_plan_pairs(bs_tilemap *tm, int32_t G)
 {
     bs::PairPlan &plan = tm->pairs;
-    if (plan.gqa_group == G) return;
+    if (plan.gqa_group == G && plan.epoch == tm->class_epoch) return;
     plan.ranges.clear();
     plan.items.clear();
     const int32_t M = tm->M, H = tm->n_q_heads;
@@ -821,7 +845,10 @@ void bs_plan_pairs(bs_tilemap *tm, int32_t G)
         for (size_t b = 0; b < n; ++b) dealt[b] = plan.items[slot[b].second];
         plan.items.swap(dealt);
     }
+    for (bs::PairItem &it : plan.items)
+        it.classes = tm->head_class[it.head_a] | (it.head_b >= 0 ? tm->head_class[it.head_b] << 8 : 0);
     plan.gqa_group = G;
+    plan.epoch = tm->class_epoch;
 }
 
 extern "C" int bs_tilemap_pair_plan(bs_tilemap *tm, int32_t gqa_group, int64_t *n_units, int64_t *unit_tiles,

@@ -37,7 +37,7 @@ struct PairItem {
     int32_t head_a, tile_a, head_b, tile_b;
     int32_t list_begin, list_end;  // entries of PairPlan::ranges
     int32_t n_tiles;               // key tiles in the merged list (scheduling weight)
-    int32_t pad;
+    int32_t classes;               // head class of item A | head class of item B << 8
 };
 
 // Run of key tiles [begin, end) with one state per item: 0 skip, 1 partial, 2 full.
@@ -47,7 +47,8 @@ struct PairRange {
 };
 
 struct PairPlan {
-    int32_t gqa_group = 0;  // the plan depends on which heads share a KV head
+    int32_t gqa_group = 0;  // the plan depends on which heads share a KV head ...
+    uint64_t epoch = 0;     // ... and on the class vector (bs_tilemap::class_epoch when it was made)
     std::vector<PairRange> ranges;
     std::vector<PairItem> items;  // heaviest first
 };
@@ -58,6 +59,8 @@ struct DeviceMap;  // defined by the HIP side
 
 // Pair up the work items for KV-sharing workgroups (host only; see PairItem).
 void bs_plan_pairs(bs_tilemap *tm, int32_t gqa_group);
+// The plain work list of the fp32 kernel: every (head, query tile), heaviest first (host only).
+void bs_plan_work(bs_tilemap *tm);
 
 struct bs_tilemap {
     int32_t L = 0, bm = 0, bn = 0, M = 0, N = 0, n_q_heads = 0, sink_len = 0;
@@ -79,8 +82,10 @@ struct bs_tilemap {
     std::vector<uint64_t> text_bits;       // N: bit b of entry n = key n*bn + b is a text key (bn <= 64 only)
     std::vector<uint64_t> sink_bits;       // N: same for sink keys
     bs::ClassLists cls[4];
-    std::vector<bs::WorkItem> work;        // n_q_heads * M items, heaviest first
-    bs::PairPlan pairs;                    // built on first use for a given gqa_group
+    uint64_t class_epoch = 1;              // bumped by bs_tilemap_rebind: work list, work units and their device copies are stale
+    std::vector<bs::WorkItem> work;        // n_q_heads * M items, heaviest first; built on first use (work_epoch)
+    uint64_t work_epoch = 0;
+    bs::PairPlan pairs;                    // built on first use for a given gqa_group and class vector
     bs::DeviceMap *dev = nullptr;          // created lazily by bs_tilemap_upload
     void (*dev_free)(bs::DeviceMap *) = nullptr;
 };

@@ -17,7 +17,7 @@ import re
 import subprocess
 import tempfile
 
-from . import build as _build
+from paper_2507_09071_amd import build as _build
 
 WAIT_STATES = 12
 KERNELS = ("_ZN2bs17attn_prefill_bf16ILi128EEE", "_ZN2bs17attn_prefill_bf16ILi64EEE")

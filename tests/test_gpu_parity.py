@@ -287,3 +287,28 @@ def test_map_recycling_without_synchronisation():
         want = oracle_rows(p, q, k, v)
         for h in range(p.n_q_heads):
             assert_close(outs[i][h].float().cpu().numpy(), want[h], "bf16", f"prompt {i} head {h}")
+
+
+def test_one_map_per_prompt_rebound_per_layer_without_synchronisation():
+    """A model's prefill: ONE tile map of the prompt, bound to each layer's class vector in turn, the
+    launches queued back to back on one stream (the re-planned work units of layer l + 1 are uploaded
+    while layer l's kernels still run).  Every layer's output against the oracle; both dtypes."""
+    rng = np.random.default_rng(11)
+    for dtype, d, tol in (("bf16", 128, "bf16"), ("f32", 64, "f32")):
+        base = W.custom_prompt([("T", 33), ("I", 420), ("T", 6), ("I", 515), ("I", 90), ("T", 40)], [D, S, I, IS, IS, I], 3, d,
+                               dtype=dtype, sink_len=33, name=f"layers-{dtype}")
+        layers = [base.head_class] + [rng.integers(0, 4, size=base.n_q_heads).astype(np.uint8) for _ in range(3)]
+        layers.append(np.zeros(base.n_q_heads, np.uint8))
+        q, k, v = W.make_qkv(base, 12, DEV)
+        tm = bs.bs_build_tilemap(base.spans, base.seq_len, layers[0], base.sink_len, 128, 64, flags=bs.BS_MAP_PACK_KEYS)
+        outs = [torch.full_like(q, float("nan")) for _ in layers]
+        st = torch.cuda.current_stream().cuda_stream
+        dt = bs.BS_BF16 if dtype == "bf16" else bs.BS_F32
+        for hc, o in zip(layers, outs):
+            tm.rebind(hc)
+            bs.bs_attn_prefill(q, k, v, o, tm, dt, base.n_q_heads, base.gqa_group, base.head_dim, base.scale, st)
+        torch.cuda.synchronize()
+        for li, (hc, o) in enumerate(zip(layers, outs)):
+            want = oracle_rows(base.with_classes(hc), q, k, v)
+            for h in range(base.n_q_heads):
+                assert_close(o[h].float().cpu().numpy(), want[h], tol, f"{dtype} layer {li} head {h} class {hc[h]}")

@@ -7,7 +7,7 @@ import shutil
 import pytest
 
 from paper_2507_09071_amd import build as bs_build
-from paper_2507_09071_amd import isa_check
+import isa_check
 
 
 def test_checker_flags_a_copy_right_behind_an_mfma():

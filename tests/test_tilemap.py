@@ -434,6 +434,34 @@ def test_pair_plan_configs(cfg):
         tm.pair_plan(5 if p.n_q_heads % 5 else 0)
 
 
+# ------------------------------------------------------------------------- one map per prompt, one class vector per layer
+
+def test_rebind_keeps_the_lists_and_replans_the_units():
+    p = W.config(2)
+    tm = bs.bs_build_tilemap(p.spans, p.seq_len, p.head_class, p.sink_len, flags=bs.BS_MAP_PACK_KEYS)
+    before = [(tm.stats(c), tm.tile_states(c, 50, 8)) for c in range(4)]
+    plan_a = tm.pair_plan(p.gqa_group)
+    rng = np.random.default_rng(3)
+    for _ in range(3):
+        hc = rng.integers(0, 4, size=p.n_q_heads).astype(np.uint8)
+        tm.rebind(hc)
+        fresh = bs.bs_build_tilemap(p.spans, p.seq_len, hc, p.sink_len, flags=bs.BS_MAP_PACK_KEYS)
+        assert tm.pair_plan(p.gqa_group) == fresh.pair_plan(p.gqa_group)    # validated unit by unit inside the call
+        for c in range(4):
+            assert tm.stats(c) == before[c][0] and np.array_equal(tm.tile_states(c, 50, 8), before[c][1])
+    tm.rebind(p.head_class)
+    assert tm.pair_plan(p.gqa_group) == plan_a
+    # another head count (same prompt, a layer with fewer heads)
+    tm.rebind(np.array([0, 1, 2, 3, 3, 2, 1, 0], dtype=np.uint8))
+    assert tm.n_q_heads == 8
+    assert tm.pair_plan(2)["n_units"] == 4 * tm.n_q_tiles
+    with pytest.raises(bs.BlindsightError):
+        tm.rebind(np.array([0, 4], dtype=np.uint8))
+    with pytest.raises(bs.BlindsightError):
+        tm.rebind(np.zeros(0, dtype=np.uint8))
+    assert tm.n_q_heads == 8
+
+
 # ------------------------------------------------------------------------- error behaviour
 
 def _raw_build(spans, n_spans, L, hc, nh, sink_len, bm, bn, out):
@@ -503,6 +531,17 @@ def test_attn_prefill_argument_checks_need_no_gpu():
     assert f(one, one, one, one, tm.handle, 5, 2, 2, 128, 0.1, None) == -2
     assert f(one, one, one, one, small.handle, 0, 2, 2, 128, 0.1, None) == -2   # 64x64 map
     assert f(ctypes.c_void_p(260), one, one, one, tm.handle, 0, 2, 2, 128, 0.1, None) == -1  # alignment
+
+
+def test_static_entry_point_rejects_an_unprepared_map_without_touching_the_gpu():
+    lib = binding.load_library()
+    tm = bs.bs_build_tilemap([(2, 9, 1)], 300, [0, 1])
+    one = ctypes.c_void_p(256)
+    assert lib.bs_attn_prefill_static(one, one, one, one, tm.handle, 2, 2, 128, 0.1, None) == -1
+    assert b"bs_tilemap_prepare" in lib.bs_last_error()
+    assert lib.bs_attn_prefill_static(None, one, one, one, tm.handle, 2, 2, 128, 0.1, None) == -1
+    assert lib.bs_attn_prefill_static(one, one, one, one, tm.handle, 2, 2, 96, 0.1, None) == -2
+    assert lib.bs_static_scratch_bytes() == 96 << 20
 
 
 def test_library_exports_every_declared_symbol():
