@@ -129,8 +129,8 @@ int bs_build_tilemap_ex(const bs_span *spans, int32_t n_spans, int32_t seq_len,
  * window depending on the model; the sparse masks live inside the dense mask).  0 = no window; a window of seq_len or
  * more is no window.  With a window BS_MAP_PACK_KEYS acts as BS_MAP_REGROUP_ROWS (a windowed query tile
  * visits a handful of key tiles: there is nothing to pack).  Together with BS_MAP_BIDIR_IMAGES the keys of
- * the query's own image stay visible at any distance; the map supports that for images of at most
- * `window` tokens (where the window alone already implies it) and returns BS_EUNSUPPORTED otherwise.
+ * the query's own image stay visible at any distance, also for images longer than the window: an image
+ * query then sees its class pattern inside [min(window start, image start), image end).
  * Errors: as bs_build_tilemap_ex; BS_EINVAL for a negative offset, count or window.
  */
 int bs_build_tilemap_model(const bs_span *spans, int32_t n_spans, int32_t seq_len,

@@ -127,8 +127,8 @@ struct QueryView {
         if (!(qcode & kCodeText) && (bidir || (cls & 2))) {
             const int2 sp = span_range[qcode & kCodeImgMask];
             // an image query that sees its whole image behaves, for every class, like the
-            // image's last query under the causal mask
-            if (bidir) row = sp.y - 1;
+            // image's last query under the causal mask; its image stays visible beyond a window
+            if (bidir) { row = sp.y - 1; first = min(first, sp.x); }
             if (!sees_all && (cls & 2)) { own_lo = sp.x; own_hi = sp.y; }
         }
         if (packed && !sees_all && (cls != BS_INTRA || intra_compact)) {

@@ -40,8 +40,12 @@ struct Geometry {
     bool bidir = false;                // tokens of one image also see the later tokens of that image
     int32_t window = 0;                // > 0: a query at position i sees no key before i - window + 1
     int32_t Nc = 0, n_free = 0;
-    // first key position a query at position i may see
-    int32_t lo(int32_t i) const { return window > 0 ? std::max(0, i - window + 1) : 0; }
+    // first key position a query at position i may see: the start of its window; with bidirectional
+    // images the query's own image stays visible at any distance, so for an image token it is the
+    // smaller of the window's start and the image's start (the visible keys stay one interval, and the
+    // bound still grows with the position)
+    std::vector<int32_t> first_visible;   // L entries when window > 0
+    int32_t lo(int32_t i) const { return window > 0 ? first_visible[i] : 0; }
     std::vector<int32_t> ctext;        // n_free + 1: text keys among compact slots [0, s)
 
     const std::vector<int32_t> &free_count(int cls) const { return (cls & 1) ? n_free_sink : n_text; }
@@ -447,12 +451,6 @@ extern "C" int bs_build_tilemap_model(const bs_span *spans, int32_t n_spans, int
         // a windowed query tile visits a few key tiles only: nothing to pack; the rows stay regrouped
         flags = (flags & ~(uint32_t)BS_MAP_PACK_KEYS) | BS_MAP_REGROUP_ROWS;
     }
-    if (window > 0 && (flags & BS_MAP_BIDIR_IMAGES)) {
-        // the own image stays visible at any distance; with images no longer than the window that
-        // is implied by the window itself, which is the case the map handles
-        for (int32_t g = 0; g < n_spans; ++g)
-            if (spans && spans[g].end - spans[g].start > window) return BS_EUNSUPPORTED;
-    }
     if (n_sink_offsets < 0 || (n_sink_offsets > 0 && !sink_offsets)) return BS_EINVAL;
     for (int32_t o = 0; o < n_sink_offsets; ++o)
         if (sink_offsets[o] < 0) return BS_EINVAL;
@@ -552,6 +550,14 @@ extern "C" int bs_build_tilemap_model(const bs_span *spans, int32_t n_spans, int
         G.L = L; G.bm = block_m; G.bn = block_n; G.M = tm->M; G.N = tm->N0; G.spans = &tm->spans;
         G.bidir = tm->bidir;
         G.window = tm->window = window;
+        if (window > 0) {
+            G.first_visible.resize(L);
+            for (int32_t t = 0; t < L; ++t) G.first_visible[t] = std::max(0, t - window + 1);
+            if (tm->bidir)
+                for (int32_t g = 0; g < n_spans; ++g)
+                    for (int32_t t = spans[g].start; t < spans[g].end; ++t)
+                        G.first_visible[t] = std::min(G.first_visible[t], spans[g].start);
+        }
         G.n_text.assign(L + 1, 0);
         G.n_free_sink.assign(L + 1, 0);
         G.last_text.assign(L, -1);

@@ -18,13 +18,6 @@ from test_tilemap_model import random_layout
 @pytest.mark.parametrize("bm,bn", [(1, 1), (2, 2), (4, 2), (3, 5)])
 def test_golden_prompts(path, bm, bn):
     L, spans, sink_len, offsets, bidir, _, window = load_full(path)
-    longest = int((spans[:, 1] - spans[:, 0]).max())
-    if bidir and longest > window:
-        with pytest.raises(bs.BlindsightError) as e:   # own image beyond the window: not a case the map takes
-            bs.bs_build_tilemap(spans, L, np.zeros(1, np.uint8), sink_len, bm, bn, flags=bs.BS_MAP_BIDIR_IMAGES,
-                                sink_offsets=offsets, window=window)
-        assert e.value.code == -2
-        return
     check_against_oracle(spans, L, sink_len, bm, bn, bidir=bidir, offsets=offsets, window=window)
     check_regrouped(spans, L, sink_len, bm, bn, bidir=bidir, offsets=offsets, window=window)
 
@@ -49,7 +42,8 @@ def test_random_prompts_bidirectional_images(seed):
         return
     longest = int((spans[:, 1] - spans[:, 0]).max())
     rng = np.random.default_rng(seed)
-    for window in (longest, longest + int(rng.integers(1, 30))):
+    # windows shorter than the longest image too: the own image stays visible beyond the window
+    for window in (1, max(1, longest // 3), max(1, longest - 1), longest, longest + int(rng.integers(1, 30))):
         if window >= L:
             continue
         check_against_oracle(spans, L, sink_len, bm, bn, bidir=True, offsets=offsets, window=window)
@@ -87,9 +81,9 @@ def test_negative_window_is_rejected():
     hc = (ctypes.c_uint8 * 1)(0)
     out = ctypes.c_void_p()
     assert lib.bs_build_tilemap_model(sp, 1, 20, hc, 1, 0, 4, 4, 0, None, 0, -1, ctypes.byref(out)) == -1
-    assert lib.bs_build_tilemap_model(sp, 1, 20, hc, 1, 0, 4, 4, 4, None, 0, 6, ctypes.byref(out)) == -2   # image of 7 > window
-    assert lib.bs_build_tilemap_model(sp, 1, 20, hc, 1, 0, 4, 4, 4, None, 0, 7, ctypes.byref(out)) == 0
-    lib.bs_tilemap_destroy(out)
+    for window in (6, 7):   # an image of 7 tokens that attends in both directions: longer than the window, and not
+        assert lib.bs_build_tilemap_model(sp, 1, 20, hc, 1, 0, 4, 4, 4, None, 0, window, ctypes.byref(out)) == 0
+        lib.bs_tilemap_destroy(out)
 
 
 @pytest.mark.parametrize("seed", range(24))
