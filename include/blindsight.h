@@ -139,6 +139,23 @@ int bs_build_tilemap_model(const bs_span *spans, int32_t n_spans, int32_t seq_le
                            const int32_t *sink_offsets, int32_t n_sink_offsets, int32_t window,
                            bs_tilemap **out);
 
+/*
+ * Same, for a chunk of queries at the end of the prompt: the query rows are the positions q_begin .. seq_len - 1
+ * only (0 <= q_begin < seq_len), attending to all seq_len keys under the same masks.  This is how the masks of
+ * Sec. 3.2 carry over to chunked prefill and to decoding with the KV cache kept whole (the paper prunes no
+ * KV entries, Sec. 6.1: its masks only drop attention pairs): the chunk's rows are rows of the same L x L mask.
+ * With such a map, q and out of bs_attn_prefill hold seq_len - q_begin rows per head ([n_q_heads][seq_len -
+ * q_begin][head_dim], row r = position q_begin + r); k and v hold all seq_len positions.  n_q_tiles counts the
+ * tiles of those rows, bs_tilemap_row_order reports positions, allowed_pairs / empty_rows count those rows.
+ * q_begin = 0 is bs_build_tilemap_model.  Errors: as bs_build_tilemap_model; BS_EINVAL for q_begin outside
+ * [0, seq_len).
+ */
+int bs_build_tilemap_suffix(const bs_span *spans, int32_t n_spans, int32_t seq_len,
+                            const uint8_t *head_class, int32_t n_q_heads, int32_t sink_len,
+                            int32_t block_m, int32_t block_n, uint32_t flags,
+                            const int32_t *sink_offsets, int32_t n_sink_offsets, int32_t window,
+                            int32_t q_begin, bs_tilemap **out);
+
 /* End of a map's life (the paper builds its mask metadata once per prompt, Sec. 5 "no runtime overhead";
  * so does a caller here, and destroys the map when the prompt's prefill is over).
  * Frees the host arrays; device buffers (if any) go back to a per-process cache of the library

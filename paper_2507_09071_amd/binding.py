@@ -17,7 +17,7 @@ from . import build as _build
 BS_BF16, BS_F32 = 0, 1
 DENSE, SINK, INTRA, INTRA_SINK = 0, 1, 2, 3
 
-EXPORTS = ("bs_build_tilemap", "bs_build_tilemap_ex", "bs_build_tilemap_model", "bs_tilemap_destroy", "bs_tilemap_dims", "bs_tilemap_row_order", "bs_tilemap_layout", "bs_tilemap_key_order", "bs_tilemap_tile_states",
+EXPORTS = ("bs_build_tilemap", "bs_build_tilemap_ex", "bs_build_tilemap_model", "bs_build_tilemap_suffix", "bs_tilemap_destroy", "bs_tilemap_dims", "bs_tilemap_row_order", "bs_tilemap_layout", "bs_tilemap_key_order", "bs_tilemap_tile_states",
            "bs_tilemap_stats", "bs_tilemap_pair_plan", "bs_tilemap_upload", "bs_tilemap_rebind", "bs_tilemap_prepare",
            "bs_attn_prefill", "bs_attn_prefill_ex", "bs_attn_prefill_static", "bs_static_scratch_bytes",
            "bs_characterize_prompt", "bs_head_sq_error", "bs_aggregate_head_type", "bs_aggregate_layer", "bs_alpha_layer", "bs_strerror",
@@ -75,6 +75,9 @@ def load_library():
     lib.bs_build_tilemap_model.argtypes = [ctypes.POINTER(_Span), i32, i32, u8p, i32, i32, i32, i32, ctypes.c_uint32,
                                            i32p, i32, i32, ctypes.POINTER(ctypes.c_void_p)]
     lib.bs_build_tilemap_model.restype = ctypes.c_int
+    lib.bs_build_tilemap_suffix.argtypes = [ctypes.POINTER(_Span), i32, i32, u8p, i32, i32, i32, i32, ctypes.c_uint32,
+                                            i32p, i32, i32, i32, ctypes.POINTER(ctypes.c_void_p)]
+    lib.bs_build_tilemap_suffix.restype = ctypes.c_int
     lib.bs_tilemap_row_order.argtypes = [vp, i32p]
     lib.bs_tilemap_row_order.restype = ctypes.c_int
     lib.bs_tilemap_layout.argtypes = [vp, i32p, i32p, i32p]
@@ -226,18 +229,26 @@ BS_MAP_BIDIR_IMAGES = 4
 
 def bs_build_tilemap(spans, seq_len: int, head_class, sink_len: int = 0,
                      block_m: int = 128, block_n: int = 64, flags: int = 0, sink_offsets=None,
-                     window: int = 0) -> TileMap:
+                     window: int = 0, q_begin: int = 0) -> TileMap:
     """spans: int array [G,3] of (start, end, sink); head_class: uint8 [n_q_heads];
     flags: 0 or BS_MAP_* bits (goes through bs_build_tilemap_ex); sink_offsets: in-image offsets that
     are sink keys in every image, window: sliding window of the layer (both go through
-    bs_build_tilemap_model)."""
+    bs_build_tilemap_model); q_begin: the query rows are positions q_begin .. seq_len - 1 only
+    (bs_build_tilemap_suffix)."""
     lib = load_library()
     sp = np.ascontiguousarray(np.asarray(spans, dtype=np.int32).reshape(-1, 3))
     hc = np.ascontiguousarray(head_class, dtype=np.uint8)
     handle = ctypes.c_void_p()
     sp_ptr = sp.ctypes.data_as(ctypes.POINTER(_Span)) if len(sp) else None
     hc_ptr = hc.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8))
-    if (sink_offsets is not None and len(sink_offsets)) or window:
+    if q_begin:
+        so = np.ascontiguousarray([] if sink_offsets is None else sink_offsets, dtype=np.int32).reshape(-1)
+        rc = lib.bs_build_tilemap_suffix(sp_ptr, len(sp), int(seq_len), hc_ptr, len(hc), int(sink_len),
+                                         int(block_m), int(block_n), int(flags),
+                                         so.ctypes.data_as(ctypes.POINTER(ctypes.c_int32)) if len(so) else None, len(so),
+                                         int(window), int(q_begin), ctypes.byref(handle))
+        _check(rc, "bs_build_tilemap_suffix")
+    elif (sink_offsets is not None and len(sink_offsets)) or window:
         so = np.ascontiguousarray([] if sink_offsets is None else sink_offsets, dtype=np.int32).reshape(-1)
         rc = lib.bs_build_tilemap_model(sp_ptr, len(sp), int(seq_len), hc_ptr, len(hc), int(sink_len),
                                         int(block_m), int(block_n), int(flags),

@@ -51,6 +51,7 @@ struct KernelArgs {
     int32_t packed, intra_compact;
     int32_t bidir;            // tokens of one image also see the later tokens of that image
     int32_t window;           // > 0: keys more than window - 1 positions before the query are masked
+    int32_t q_begin;          // q / out hold the query positions q_begin .. L - 1, row r = position q_begin + r
 };
 #define BS_MAP_PARAMS                                                                              \
     const uint32_t *__restrict__ map_code, const uint64_t *__restrict__ map_text_bits,             \
@@ -488,7 +489,8 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(
     const int row_slot = map_row_order[max(m, 0) * kBlockM + wave * 32 + col];
     const int row = row_slot < 0 ? L : row_slot;
 
-    const __bf16 *qh = reinterpret_cast<const __bf16 *>(a.q) + (size_t)hsafe * L * D;
+    const int R = L - a.q_begin;   // query rows per head
+    const __bf16 *qh = reinterpret_cast<const __bf16 *>(a.q) + (size_t)hsafe * R * D;
     // packed K and V^T tiles of this KV head (one TILE-byte block per key tile)
     const char *kph = reinterpret_cast<const char *>(kp + (size_t)kvh * n_k_tiles * (size_t)(D * kBlockN));
     const char *vth = reinterpret_cast<const char *>(vt + (size_t)kvh * n_k_tiles * (size_t)(D * kBlockN));
@@ -496,7 +498,7 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(
     // Q^T operand: lane holds Q[row][16t + 8hl .. +8] for every 16-wide slice t of the head dim.
     bf16x8 qreg[NT];
     {
-        const int qrow = min(row, L - 1);  // rows past the end compute on a copy and are not stored
+        const int qrow = min(row, L - 1) - a.q_begin;  // rows past the end compute on a copy and are not stored
 #pragma unroll
         for (int t = 0; t < NT; ++t)
             qreg[t] = *reinterpret_cast<const bf16x8 *>(qh + (size_t)qrow * D + 16 * t + 8 * hl);
@@ -780,7 +782,7 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(
     const float l_tot = sum_across_halves(l_run);
     const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
     if (have_item && row < L) {
-        __bf16 *orow = reinterpret_cast<__bf16 *>(a.out) + ((size_t)head * L + row) * D;
+        __bf16 *orow = reinterpret_cast<__bf16 *>(a.out) + ((size_t)head * R + (row - a.q_begin)) * D;
 #pragma unroll
         for (int db = 0; db < NDB; ++db)
 #pragma unroll
@@ -815,13 +817,14 @@ __global__ __launch_bounds__(kThreads, 1) void attn_prefill_f32(KernelArgs a, BS
     const int row_slot = map_row_order[m * kBlockM + wave * 32 + col];
     const int row = row_slot < 0 ? L : row_slot;
 
-    const float *qh = reinterpret_cast<const float *>(a.q) + (size_t)head * L * D;
+    const int R = L - a.q_begin;   // query rows per head
+    const float *qh = reinterpret_cast<const float *>(a.q) + (size_t)head * R * D;
     const float *kh = reinterpret_cast<const float *>(a.k) + (size_t)kvh * L * D;
     const float *vh = reinterpret_cast<const float *>(a.v) + (size_t)kvh * L * D;
 
     float qreg[D / 2];  // Q[row][2t + hl]
     {
-        const int qrow = min(row, L - 1);
+        const int qrow = min(row, L - 1) - a.q_begin;
 #pragma unroll
         for (int t = 0; t < D / 2; ++t) qreg[t] = qh[(size_t)qrow * D + 2 * t + hl];
     }
@@ -894,7 +897,7 @@ __global__ __launch_bounds__(kThreads, 1) void attn_prefill_f32(KernelArgs a, BS
     const float l_tot = sum_across_halves(l_run);
     const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
     if (row < L) {
-        float *orow = reinterpret_cast<float *>(a.out) + ((size_t)head * L + row) * D;
+        float *orow = reinterpret_cast<float *>(a.out) + ((size_t)head * R + (row - a.q_begin)) * D;
 #pragma unroll
         for (int db = 0; db < D / 32; ++db)
 #pragma unroll
@@ -987,6 +990,7 @@ bs::KernelArgs kernel_args(const void *q, const void *k, const void *v, void *ou
     a.intra_compact = tm->intra_compact;
     a.bidir = tm->bidir;
     a.window = tm->window;
+    a.q_begin = tm->q_begin;
     return a;
 }
 

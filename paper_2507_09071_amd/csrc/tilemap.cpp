@@ -382,12 +382,12 @@ void build_class(const Geometry &G, int cls, const std::vector<int32_t> &row_ord
 }
 
 // Allowed pairs and empty rows per class, from prefix counts (no pair enumeration).
-void count_pairs(const Geometry &G, const std::vector<uint32_t> &code, ClassLists lists[4])
+void count_pairs(const Geometry &G, const std::vector<uint32_t> &code, int32_t q_begin, ClassLists lists[4])
 {
     const auto &sp = *G.spans;
     int64_t pairs[4] = {0, 0, 0, 0}, empty[4] = {0, 0, 0, 0};
     size_t g = 0;
-    for (int32_t i = 0; i < G.L; ++i) {
+    for (int32_t i = q_begin; i < G.L; ++i) {
         const int32_t lo = G.lo(i);   // first key position the row may see
         if (code[i] & bs::kCodeText) {
             for (int c = 0; c < 4; ++c) pairs[c] += i + 1 - lo;
@@ -444,6 +444,17 @@ extern "C" int bs_build_tilemap_model(const bs_span *spans, int32_t n_spans, int
                                       const int32_t *sink_offsets, int32_t n_sink_offsets, int32_t window,
                                       bs_tilemap **out)
 {
+    return bs_build_tilemap_suffix(spans, n_spans, seq_len, head_class, n_q_heads, sink_len, block_m, block_n, flags,
+                                   sink_offsets, n_sink_offsets, window, 0, out);
+}
+
+extern "C" int bs_build_tilemap_suffix(const bs_span *spans, int32_t n_spans, int32_t seq_len,
+                                       const uint8_t *head_class, int32_t n_q_heads, int32_t sink_len,
+                                       int32_t block_m, int32_t block_n, uint32_t flags,
+                                       const int32_t *sink_offsets, int32_t n_sink_offsets, int32_t window,
+                                       int32_t q_begin, bs_tilemap **out)
+{
+    if (q_begin < 0 || (seq_len > 0 && q_begin >= seq_len)) return BS_EINVAL;
     if (flags & ~(uint32_t)(BS_MAP_REGROUP_ROWS | BS_MAP_PACK_KEYS | BS_MAP_BIDIR_IMAGES)) return BS_EINVAL;
     if (window < 0) return BS_EINVAL;
     if (window >= seq_len) window = 0;   // every earlier key is inside the window
@@ -468,6 +479,7 @@ extern "C" int bs_build_tilemap_model(const bs_span *spans, int32_t n_spans, int
         tm = new bs_tilemap();
         const int32_t L = seq_len;
         tm->L = L; tm->bm = block_m; tm->bn = block_n; tm->sink_len = sink_len;
+        tm->q_begin = q_begin;
         tm->N0 = tm->N = (L + block_n - 1) / block_n;
         tm->n_q_heads = n_q_heads;
         tm->spans.assign(spans, spans + n_spans);
@@ -528,14 +540,15 @@ extern "C" int bs_build_tilemap_model(const bs_span *spans, int32_t n_spans, int
         // text rows stop costing the image rows of the sparse classes their skipped tiles.
         {
             const int64_t bm = block_m;
+            const int64_t R = L - q_begin;                 // the query rows are positions q_begin .. L - 1
             std::vector<int32_t> img_rows, txt_rows;
             if (flags & BS_MAP_REGROUP_ROWS) {
-                for (int32_t t = 0; t < L; ++t) ((tm->code[t] & bs::kCodeText) ? txt_rows : img_rows).push_back(t);
+                for (int32_t t = q_begin; t < L; ++t) ((tm->code[t] & bs::kCodeText) ? txt_rows : img_rows).push_back(t);
             }
             if (img_rows.empty() || txt_rows.empty()) {   // natural order (also: nothing to separate)
-                tm->M = (int32_t)((L + bm - 1) / bm);
+                tm->M = (int32_t)((R + bm - 1) / bm);
                 tm->row_order.assign((size_t)tm->M * bm, -1);
-                for (int32_t t = 0; t < L; ++t) tm->row_order[t] = t;
+                for (int64_t r = 0; r < R; ++r) tm->row_order[r] = (int32_t)(q_begin + r);
             } else {
                 const int64_t m_img = ((int64_t)img_rows.size() + bm - 1) / bm, m_txt = ((int64_t)txt_rows.size() + bm - 1) / bm;
                 tm->M = (int32_t)(m_img + m_txt);
@@ -640,7 +653,7 @@ extern "C" int bs_build_tilemap_model(const bs_span *spans, int32_t n_spans, int
             }
             G.intra_compact = tm->intra_compact;
         }
-        count_pairs(G, tm->code, tm->cls);
+        count_pairs(G, tm->code, q_begin, tm->cls);
 
     } catch (const std::bad_alloc &) {
         delete tm;

@@ -70,6 +70,7 @@ struct bs_tilemap {
     bool packed = false;
     bool bidir = false;                    // image tokens also attend to the later tokens of their own image
     int32_t window = 0;                    // > 0: sliding window, keys with i - j >= window are masked
+    int32_t q_begin = 0;                   // the query rows are positions q_begin .. L - 1 (q / out hold L - q_begin rows per head)
     bool intra_compact = false;            // packed: Intra-Image rows take their text keys from the compact tiles
     std::vector<int32_t> key_order;        // N * bn: position of each key-tile slot, -1 = none
     std::vector<int32_t> free_before;      // packed: L + 1, free keys at positions < t

@@ -10,6 +10,7 @@ import workloads as W
 from oracle import characterize as C
 from dataclasses import replace
 
+from gpu_util import assert_close, oracle_rows
 from test_gpu_parity import RUNS_A, full_parity, sampled_parity
 
 pytestmark = pytest.mark.gpu
@@ -157,3 +158,49 @@ def test_random_prompts_random_options(seed):
                         name=f"rand{seed}-{dtype}-d{d}-f{flags}-w{window}-b{int(bidir)}",
                         value_recipe={"std": 1.0, "first_key_scale": 3.0}, img_bidir=bidir, sink_offsets=offsets, window=window)
     full_parity(p, seed=seed, flags=flags)
+
+
+# --- a chunk of queries at the end of the prompt (chunked prefill, decoding): same masks, rows q_begin .. L - 1
+
+def suffix_parity(p, q_begin, seed, flags, row_step=1):
+    q, k, v = W.make_qkv(p, seed, DEV)
+    f = flags | (bs.BS_MAP_BIDIR_IMAGES if p.img_bidir else 0)
+    tm = bs.bs_build_tilemap(p.spans, p.seq_len, p.head_class, p.sink_len, 128, 64, flags=f,
+                             sink_offsets=p.sink_offsets or None, window=p.window, q_begin=q_begin)
+    qs = q[:, q_begin:].contiguous()
+    out = torch.full_like(qs, float("nan"))
+    dt = bs.BS_BF16 if p.dtype == "bf16" else bs.BS_F32
+    print(p.name, "L", p.seq_len, "q_begin", q_begin, flush=True)
+    bs.bs_attn_prefill(qs, k, v, out, tm, dt, p.n_q_heads, p.gqa_group, p.head_dim, p.scale,
+                       torch.cuda.current_stream().cuda_stream)
+    torch.cuda.synchronize()
+    rows = np.unique(np.concatenate([np.arange(q_begin, p.seq_len, row_step), [p.seq_len - 1]])).astype(np.int32)
+    want = oracle_rows(p, q.float().cpu().numpy(), k.float().cpu().numpy(), v.float().cpu().numpy(), rows)
+    got = out[:, torch.from_numpy(rows - q_begin).long().to(out.device)].float().cpu().numpy()
+    for h in range(p.n_q_heads):
+        assert_close(got[h], want[h], p.dtype, f"{p.name} q_begin {q_begin} head {h} class {p.head_class[h]}")
+
+
+@pytest.mark.parametrize("dtype,d,flags", [("bf16", 128, 0), ("bf16", 64, bs.BS_MAP_REGROUP_ROWS), ("bf16", 128, bs.BS_MAP_PACK_KEYS),
+                                           ("f32", 64, bs.BS_MAP_PACK_KEYS), ("f32", 128, 0)])
+def test_suffix_queries_small_prompt(dtype, d, flags):
+    p = W.custom_prompt(RUNS_A, [D, S, I, IS, IS, I, S, D], 4, d, dtype=dtype, sink_len=5,
+                        name=f"suffix-{dtype}-d{d}-f{flags}", value_recipe={"std": 1.0, "first_key_scale": 4.0})
+    for q_begin in (p.seq_len - 1, p.seq_len - 130, 400, 37):   # one decode row; inside the last text run; inside images
+        suffix_parity(p, q_begin, 31, flags)
+
+
+def test_suffix_queries_with_model_options():
+    runs = [("T", 20), ("I", 300), ("T", 9), ("I", 700), ("I", 120), ("T", 30), ("I", 300), ("T", 11)]
+    p = W.custom_prompt(runs, [S, I, IS, D, IS, S, I, D], 4, 128, dtype="bf16", sink_len=3, span_sink=0, name="suffix-bidir-window",
+                        value_recipe={"std": 1.0, "first_key_scale": 3.0}, img_bidir=True, sink_offsets=(0, 5, 64, 130, 299, 650),
+                        window=150)
+    for q_begin in (p.seq_len - 1, 1200, 333):
+        suffix_parity(p, q_begin, 32, bs.BS_MAP_REGROUP_ROWS)
+    suffix_parity(replace(p, window=0), 777, 33, bs.BS_MAP_PACK_KEYS)
+
+
+@pytest.mark.parametrize("chunk", [1, 2048])
+def test_suffix_queries_config2(chunk):
+    p = W.config(2)
+    suffix_parity(p, p.seq_len - chunk, 0, bs.BS_MAP_PACK_KEYS, row_step=16)
