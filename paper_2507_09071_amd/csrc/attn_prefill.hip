@@ -354,11 +354,10 @@ __device__ inline void mfma_drain(floatx16 &c0, floatx16 &c1)
 // The key of every tile slot comes from the map's key order (the prompt in position order, then
 // the compact tiles of a packed map); slots without a key are zero-filled.
 template <int D>
-__global__ __launch_bounds__(256) void pack_vt_tiles(const __bf16 *__restrict__ v, __bf16 *__restrict__ vt,
-                                                     const int32_t *__restrict__ key_order, int L, int N)
+__device__ inline void pack_vt_tile(const __bf16 *__restrict__ v, __bf16 *__restrict__ vt,
+                                    const int32_t *__restrict__ key_order, int L, int N, __bf16 *tile)
 {
     constexpr int PAD = D + 2;  // odd word stride: the column gathers below spread over banks
-    __shared__ __bf16 tile[kBlockN * PAD];
     const int n = blockIdx.x, kvh = blockIdx.y, tid = threadIdx.x;
     const __bf16 *src = v + (size_t)kvh * L * D;
     for (int idx = tid; idx < kBlockN * (D / 8); idx += 256) {
@@ -384,8 +383,8 @@ __global__ __launch_bounds__(256) void pack_vt_tiles(const __bf16 *__restrict__ 
 }
 
 template <int D>
-__global__ __launch_bounds__(256) void pack_k_tiles(const __bf16 *__restrict__ k, __bf16 *__restrict__ kp,
-                                                    const int32_t *__restrict__ key_order, int L, int N)
+__device__ inline void pack_k_tile(const __bf16 *__restrict__ k, __bf16 *__restrict__ kp,
+                                   const int32_t *__restrict__ key_order, int L, int N)
 {
     const int n = blockIdx.x, kvh = blockIdx.y;
     const __bf16 *src = k + (size_t)kvh * L * D;
@@ -398,6 +397,17 @@ __global__ __launch_bounds__(256) void pack_k_tiles(const __bf16 *__restrict__ k
         if (pos >= 0) val = *reinterpret_cast<const uint4 *>(src + (size_t)pos * D + 16 * t + 8 * h);
         *reinterpret_cast<uint4 *>(dst + (size_t)idx * 8) = val;
     }
+}
+
+// The pre-pass of a bf16 call, one launch: grid (key tiles, KV heads, 2); z = 0 packs K, z = 1 packs V^T.
+template <int D>
+__global__ __launch_bounds__(256) void pack_kv_tiles(const __bf16 *__restrict__ k, const __bf16 *__restrict__ v,
+                                                     __bf16 *__restrict__ kp, __bf16 *__restrict__ vt,
+                                                     const int32_t *__restrict__ key_order, int L, int N)
+{
+    __shared__ __bf16 tile[kBlockN * (D + 2)];
+    if (blockIdx.z == 0) pack_k_tile<D>(k, kp, key_order, L, N);
+    else pack_vt_tile<D>(v, vt, key_order, L, N, tile);
 }
 
 constexpr int kPingPongThreads = 512;
@@ -1001,10 +1011,10 @@ void launch_bf16(const bs::KernelArgs &a, const bs_tilemap *tm, const DeviceMap 
 {
     __bf16 *kp = static_cast<__bf16 *>(workspace);
     __bf16 *vt = reinterpret_cast<__bf16 *>(static_cast<char *>(workspace) + pack_bytes);
-    const dim3 tgrid((unsigned)tm->N, (unsigned)n_kv_heads);
+    const dim3 tgrid((unsigned)tm->N, (unsigned)n_kv_heads, 2);
     const dim3 pgrid((unsigned)d->n_pairs), pblock(bs::kPingPongThreads);
-    hipLaunchKernelGGL(bs::pack_k_tiles<D>, tgrid, dim3(256), 0, st, static_cast<const __bf16 *>(a.k), kp, d->key_order, tm->L, tm->N);
-    hipLaunchKernelGGL(bs::pack_vt_tiles<D>, tgrid, dim3(256), 0, st, static_cast<const __bf16 *>(a.v), vt, d->key_order, tm->L, tm->N);
+    hipLaunchKernelGGL(bs::pack_kv_tiles<D>, tgrid, dim3(256), 0, st, static_cast<const __bf16 *>(a.k),
+                       static_cast<const __bf16 *>(a.v), kp, vt, d->key_order, tm->L, tm->N);
     if (ev_main_start) (void)hipEventRecord(static_cast<hipEvent_t>(ev_main_start), st);
     hipLaunchKernelGGL(bs::attn_prefill_bf16<D>, pgrid, pblock, bs::bf16_lds_bytes<D>(), st, a, d->code, d->text_bits,
                        d->sink_bits, d->span_range, d->row_order, d->free_before, d->span_free, d->pair_items,
