@@ -403,9 +403,12 @@ __device__ inline void pack_k_tile(const __bf16 *__restrict__ k, __bf16 *__restr
 template <int D>
 __global__ __launch_bounds__(256) void pack_kv_tiles(const __bf16 *__restrict__ k, const __bf16 *__restrict__ v,
                                                      __bf16 *__restrict__ kp, __bf16 *__restrict__ vt,
-                                                     const int32_t *__restrict__ key_order, int L, int N)
+                                                     const int32_t *__restrict__ key_order, int L, int N,
+                                                     int32_t *__restrict__ queue_ctr)
 {
     __shared__ __bf16 tile[kBlockN * (D + 2)];
+    // the attention kernel that follows starts on fresh unit queues
+    if (blockIdx.x == 0 && blockIdx.y == 0 && blockIdx.z == 0 && threadIdx.x < 8) queue_ctr[threadIdx.x] = 0;
     if (blockIdx.z == 0) pack_k_tile<D>(k, kp, key_order, L, N);
     else pack_vt_tile<D>(v, vt, key_order, L, N, tile);
 }
@@ -419,7 +422,7 @@ struct NoBatch { static constexpr int kind = 0, idx = 0; static constexpr bool f
 
 constexpr int kRing = 4;   // K slots = V^T slots of the LDS ring
 template <int D>
-constexpr int bf16_lds_bytes() { return 2 * kRing * kBlockN * D * 2; }
+constexpr int bf16_lds_bytes() { return 2 * kRing * kBlockN * D * 2 + 64; }   // ring, then the unit mailbox
 
 // Walks the merged key-tile list of a work unit: runs of [begin, end) with a state per item.
 struct PairWalker {
@@ -469,7 +472,7 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(
     const int32_t *__restrict__ map_free_before, const int2 *__restrict__ map_span_free,
     const int4 *__restrict__ pair_items,
     const int2 *__restrict__ pair_ranges, const __bf16 *__restrict__ kp, const __bf16 *__restrict__ vt,
-    int32_t n_k_tiles)
+    int32_t n_k_tiles, int32_t *__restrict__ queue_ctr, const int32_t *__restrict__ queue_off)
 {
     constexpr int ROW = D * 2;            // bytes per K row in LDS
     constexpr int TILE = kBlockN * ROW;   // bytes per K or V^T tile
@@ -484,37 +487,44 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(
     const int wave8 = __builtin_amdgcn_readfirstlane(tid >> 6);        // wave within the workgroup
     const int L = a.L;
 
-    // the work unit and this group's item in it
-    const int4 it0 = pair_items[2 * blockIdx.x], it1 = pair_items[2 * blockIdx.x + 1];
-    const int head = __builtin_amdgcn_readfirstlane(grp ? it0.z : it0.x);
-    const int m = __builtin_amdgcn_readfirstlane(grp ? it0.w : it0.y);
-    const bool have_item = head >= 0;
-    const int T = __builtin_amdgcn_readfirstlane(it1.z);            // key tiles in the merged list
-    const int n_steps = T + 1;                                      // the last step only adds P(T-1) V(T-1)
-    const int hsafe = max(head, 0);
-    const int cls = __builtin_amdgcn_readfirstlane((grp ? it1.w >> 8 : it1.w) & 3);   // head classes travel with the unit
-    const int kvh = __builtin_amdgcn_readfirstlane(it0.x / a.G);    // both items share it
-    // the query position of this lane's row; a tile slot without a row behaves like a row past
-    // the end of the prompt (computed on a copy of the last row, never stored)
-    const int row_slot = map_row_order[max(m, 0) * kBlockM + wave * 32 + col];
-    const int row = row_slot < 0 ? L : row_slot;
-
     const int R = L - a.q_begin;   // query rows per head
-    const __bf16 *qh = reinterpret_cast<const __bf16 *>(a.q) + (size_t)hsafe * R * D;
-    // packed K and V^T tiles of this KV head (one TILE-byte block per key tile)
-    const char *kph = reinterpret_cast<const char *>(kp + (size_t)kvh * n_k_tiles * (size_t)(D * kBlockN));
-    const char *vth = reinterpret_cast<const char *>(vt + (size_t)kvh * n_k_tiles * (size_t)(D * kBlockN));
 
-    // Q^T operand: lane holds Q[row][16t + 8hl .. +8] for every 16-wide slice t of the head dim.
-    bf16x8 qreg[NT];
-    {
+    // ---- state of the work unit in progress (a workgroup takes units from its XCD's queue until
+    // ---- the queues are empty; see the unit loop below)
+    int head = 0, m = 0, T = 0, n_steps = 1, cls = 0;
+    bool have_item = false;
+    int row = 0;                    // the query position of this lane's row
+    const char *kph = nullptr, *vth = nullptr;   // packed K / V^T tiles of the unit's KV head
+    bf16x8 qreg[NT];                // Q^T operand: Q[row][16t + 8hl .. +8] for every 16-wide slice t
+    QueryView qv;
+    int list_begin = 0, list_end = 0;
+    auto load_unit = [&](int unit) __attribute__((always_inline)) {
+        const int4 it0 = pair_items[2 * unit], it1 = pair_items[2 * unit + 1];
+        head = __builtin_amdgcn_readfirstlane(grp ? it0.z : it0.x);
+        m = __builtin_amdgcn_readfirstlane(grp ? it0.w : it0.y);
+        have_item = head >= 0;
+        T = __builtin_amdgcn_readfirstlane(it1.z);            // key tiles in the merged list
+        n_steps = T + 1;                                      // the last step only adds P(T-1) V(T-1)
+        list_begin = __builtin_amdgcn_readfirstlane(it1.x);
+        list_end = __builtin_amdgcn_readfirstlane(it1.y);
+        const int hsafe = max(head, 0);
+        cls = __builtin_amdgcn_readfirstlane((grp ? it1.w >> 8 : it1.w) & 3);   // head classes travel with the unit
+        const int kvh = __builtin_amdgcn_readfirstlane(it0.x / a.G);            // both items share it
+        // a tile slot without a row behaves like a row past the end of the prompt (computed on a
+        // copy of the last row, never stored)
+        const int row_slot = map_row_order[max(m, 0) * kBlockM + wave * 32 + col];
+        row = row_slot < 0 ? L : row_slot;
+        const __bf16 *qh = reinterpret_cast<const __bf16 *>(a.q) + (size_t)hsafe * R * D;
+        // one TILE-byte block per key tile
+        kph = reinterpret_cast<const char *>(kp + (size_t)kvh * n_k_tiles * (size_t)(D * kBlockN));
+        vth = reinterpret_cast<const char *>(vt + (size_t)kvh * n_k_tiles * (size_t)(D * kBlockN));
         const int qrow = min(row, L - 1) - a.q_begin;  // rows past the end compute on a copy and are not stored
 #pragma unroll
         for (int t = 0; t < NT; ++t)
             qreg[t] = *reinterpret_cast<const bf16x8 *>(qh + (size_t)qrow * D + 16 * t + 8 * hl);
-    }
-    QueryView qv;
-    qv.init(map_code, map_span_range, map_free_before, map_span_free, L, cls, row, a.packed != 0, a.intra_compact != 0, a.bidir != 0, a.window);
+        qv.init(map_code, map_span_range, map_free_before, map_span_free, L, cls, row, a.packed != 0, a.intra_compact != 0,
+                a.bidir != 0, a.window);
+    };
 
     // LDS byte address of this lane's MFMA operand fragments inside a K / V^T tile (see the
     // tile layouts above): key or channel `col`, half hl; slices, blocks and groups are
@@ -523,34 +533,37 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(
     const uint32_t kaddr0 = ring + col * 32 + ((hl ^ ((col >> 3) & 1)) << 4);
 
     floatx16 o[NDB];
-#pragma unroll
-    for (int db = 0; db < NDB; ++db)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) o[db][v] = 0.f;
     floatx16 s[2];
-#pragma unroll
-    for (int kb = 0; kb < 2; ++kb)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) s[kb][v] = 0.f;
     bf16x8 pf[2][2];   // P^T of the previous tile as MFMA B operands
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-#pragma unroll
-        for (int e = 0; e < 8; ++e) pf[i >> 1][i & 1][e] = (__bf16)0.f;
     float m_run = -INFINITY, l_run = 0.f;
-
     // three walkers over the merged tile list: w0 names the tile of the current step (state),
     // w1 the next tile (V^T refill), w2 the one after (K refill)
-    PairWalker w0, w1, w2;
-    w0.init(pair_ranges, it1.x, it1.y);
+    PairWalker w0, w1, w2, wt1, wt2;
     // the second group's matrix phase k runs one barrier interval before the first group's phase
     // k + 1, in which the first group fetches the same tiles: it fetches one tile further ahead
     const int ahead = grp;
-    w1 = w0; if (w1.valid()) w1.next();
-    PairWalker wt1 = w1;                                   // tile 1 (prologue)
-    if (ahead && w1.valid()) w1.next();
-    w2 = w1; if (w2.valid()) w2.next();
-    PairWalker wt2 = wt1; if (wt2.valid()) wt2.next();     // tile 2 (prologue of the second group)
+    auto reset_unit_state = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int db = 0; db < NDB; ++db)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) o[db][v] = 0.f;
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) s[kb][v] = 0.f;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) pf[i >> 1][i & 1][e] = (__bf16)0.f;
+        m_run = -INFINITY;
+        l_run = 0.f;
+        w0.init(pair_ranges, list_begin, list_end);
+        w1 = w0; if (w1.valid()) w1.next();
+        wt1 = w1;                                              // tile 1 (prologue)
+        if (ahead && w1.valid()) w1.next();
+        w2 = w1; if (w2.valid()) w2.next();
+        wt2 = wt1; if (wt2.valid()) wt2.next();                // tile 2 (prologue of the second group)
+    };
 
     // LDS-direct loads of packed tiles into ring slots: straight TILE-byte copies.  Each wave
     // instruction moves 1 KB (lane l -> bytes 16l..16l+15); instruction r of wave w (0..7) covers
@@ -682,12 +695,7 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(
     };
 
     // text / sink key bits of the tile w0 names (scalar registers, fetched one step ahead)
-    uint64_t tb_cur, sb_cur;
-    {
-        const int nn = min(__builtin_amdgcn_readfirstlane(w0.n), n_k_tiles - 1);
-        tb_cur = map_text_bits[nn];
-        sb_cur = map_sink_bits[nn];
-    }
+    uint64_t tb_cur = 0, sb_cur = 0;
     // Phase Y of step k: mask (PARTIAL tiles), online softmax, rescale O, round P to bf16.
     auto phase_y = [&](int k) __attribute__((always_inline)) {
         if (k < T) {
@@ -734,74 +742,140 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(
         }
     };
 
-    // Zero the ring once: phase X reads every slot from its first step on, and stale LDS bits
-    // could be NaN patterns (0 * NaN would poison the accumulators).
+    // Zero the ring once per workgroup: phase X reads every slot from its first step on, and stale LDS
+    // bits could be NaN patterns (0 * NaN would poison the accumulators).  Between units the slots hold
+    // tiles of the previous unit: finite values, which P = 0 wipes out just as well.
     {
         const uint4 z4 = make_uint4(0, 0, 0, 0);
         for (int i = tid * 16; i < 2 * kRing * TILE; i += kPingPongThreads * 16) *reinterpret_cast<uint4 *>(lds + i) = z4;
     }
-    __syncthreads();
-    // prologue: K(0) -> K slot 0, K(1) -> K slot 1, V^T(0) -> V^T slot 0 (unconditional, clamped)
-    {
-        const char *k0 = tile_ptr(kph, w0.n), *k1 = tile_ptr(kph, wt1.n), *v0 = tile_ptr(vth, w0.n);
-#pragma unroll
-        for (int r = 0; r < DMA_PER_WAVE; ++r) dma(r, k0, 0);
-#pragma unroll
-        for (int r = 0; r < DMA_PER_WAVE; ++r) dma(r, k1, TILE);
-#pragma unroll
-        for (int r = 0; r < DMA_PER_WAVE; ++r) dma(r, v0, kRing * TILE);
-        if (ahead) {
-            // the second group's share of K(2) and V^T(1): the first group fetches its share in
-            // its first matrix phase, which this group has no counterpart for
-            const char *k2 = tile_ptr(kph, wt2.n), *v1 = tile_ptr(vth, wt1.n);
-#pragma unroll
-            for (int r = 0; r < DMA_PER_WAVE; ++r) dma(r, k2, 2 * TILE);
-#pragma unroll
-            for (int r = 0; r < DMA_PER_WAVE; ++r) dma(r, v1, (kRing + 1) * TILE);
-        }
-    }
-    // Raw barriers: every LDS access of this kernel is an LDS-direct load (drained with vmcnt
-    // at the end of phase X) or an asm read (drained with lgkmcnt inside phase X), so no fence
-    // is wanted here -- a fence would drain loads that are meant to stay in flight.
-    __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0)
-    __builtin_amdgcn_s_barrier();
-    // ONE barrier per step.  Group 0 runs  X(k) | barrier | Y(k),  group 1  barrier | X(k) Y(k):
-    // between two barriers group 0 does Y(k) then X(k+1) while group 1 does X(k) then Y(k), so
-    // the waves of a SIMD are in opposite phases by program order but nothing holds them to a
-    // half-step grid.  Between barrier k and k+1 the ring is read at K(k), K(k+1), V^T(k-1),
-    // V^T(k) and written at K(k+3), V^T(k+2), whose slots (of K(k-1), V^T(k-2)) nobody reads
-    // after barrier k; a tile written in one interval is waited for (vmcnt) in the next and
-    // read in the one after: four slots each.
-    if (grp == 0) {
-        for (int k = 0, slot = 0; k < n_steps; ++k) {
-            phase_x(slot);
-            __builtin_amdgcn_s_barrier();
-            phase_y(k);
-            slot = slot == kRing - 1 ? 0 : slot + 1;
-        }
-    } else {
-        for (int k = 0, slot = 0; k < n_steps; ++k) {
-            __builtin_amdgcn_s_barrier();
-            phase_x(slot);
-            phase_y(k);
-            slot = slot == kRing - 1 ? 0 : slot + 1;
-        }
-    }
 
-    // epilogue: divide by the running sum, round, store.  Empty rows (l = 0) give zeros.
-    const float l_tot = sum_across_halves(l_run);
-    const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
-    if (have_item && row < L) {
-        __bf16 *orow = reinterpret_cast<__bf16 *>(a.out) + ((size_t)head * R + (row - a.q_begin)) * D;
-#pragma unroll
-        for (int db = 0; db < NDB; ++db)
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                bf16x4 w;
-#pragma unroll
-                for (int r = 0; r < 4; ++r) w[r] = (__bf16)(o[db][4 * g + r] * inv);
-                *reinterpret_cast<bf16x4 *>(orow + 32 * db + 8 * g + 4 * hl) = w;
+    // ---- Work distribution.  The host deals the units (heaviest first) to eight queues, one per XCD,
+    // so that units walking the same K / V^T tiles at about the same time share an L2.  A workgroup
+    // reads the id of the XCD it runs on from the hardware register (it does not depend on the launch
+    // order, which other streams can perturb) and claims the next unit of that queue with an atomic
+    // counter; when the queue is empty it helps out on the next one.  The first wave claims unit u + 1
+    // while unit u is set up (the atomic returns under the prologue's memory waits) and passes it on
+    // through a two-entry mailbox behind the ring.  Every wave reads the same mailbox entry, so the
+    // workgroup leaves the loop together.
+    volatile int32_t *mailbox = reinterpret_cast<volatile int32_t *>(lds + 2 * kRing * TILE);
+    int xcc;
+    asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID, 0, 4)" : "=s"(xcc));
+    xcc &= 7;
+    // claims on queue q, then on the following ones: index of a unit, or -1 when all are empty
+    auto claim_from = [&](int q0, int first_ticket) {
+        int ticket = first_ticket;
+        for (int t = 0; t < 8; ++t) {
+            const int q = (q0 + t) & 7;
+            const int begin = queue_off[q], len = queue_off[q + 1] - begin;
+            if (t > 0) {
+                ticket = len;
+                if (len > 0) {
+                    int r = 0;
+                    if (lane == 0) r = atomicAdd(&queue_ctr[q], 1);
+                    ticket = __builtin_amdgcn_readfirstlane(r);
+                }
             }
+            if (ticket < len) return begin + ticket;
+        }
+        return -1;
+    };
+    auto take_ticket = [&]() {   // one atomic on the own queue; lane 0's result counts
+        int r = 0;
+        if (lane == 0) r = atomicAdd(&queue_ctr[xcc], 1);
+        return r;
+    };
+    if (wave8 == 0) {
+        const int first = claim_from(xcc, __builtin_amdgcn_readfirstlane(take_ticket()));
+        if (lane == 0) mailbox[0] = first;
+    }
+    __syncthreads();
+    int unit = __builtin_amdgcn_readfirstlane(mailbox[0]);
+
+    for (int parity = 0; unit >= 0; parity ^= 1) {
+        int next_ticket = 0;
+        if (wave8 == 0) next_ticket = take_ticket();   // for the unit after this one; consumed after the prologue
+        load_unit(unit);
+        reset_unit_state();
+        {
+            const int nn = min(__builtin_amdgcn_readfirstlane(w0.n), n_k_tiles - 1);
+            tb_cur = map_text_bits[nn];
+            sb_cur = map_sink_bits[nn];
+        }
+        // prologue: K(0) -> K slot 0, K(1) -> K slot 1, V^T(0) -> V^T slot 0 (unconditional, clamped)
+        {
+            const char *k0 = tile_ptr(kph, w0.n), *k1 = tile_ptr(kph, wt1.n), *v0 = tile_ptr(vth, w0.n);
+#pragma unroll
+            for (int r = 0; r < DMA_PER_WAVE; ++r) dma(r, k0, 0);
+#pragma unroll
+            for (int r = 0; r < DMA_PER_WAVE; ++r) dma(r, k1, TILE);
+#pragma unroll
+            for (int r = 0; r < DMA_PER_WAVE; ++r) dma(r, v0, kRing * TILE);
+            if (ahead) {
+                // the second group's share of K(2) and V^T(1): the first group fetches its share in
+                // its first matrix phase, which this group has no counterpart for
+                const char *k2 = tile_ptr(kph, wt2.n), *v1 = tile_ptr(vth, wt1.n);
+#pragma unroll
+                for (int r = 0; r < DMA_PER_WAVE; ++r) dma(r, k2, 2 * TILE);
+#pragma unroll
+                for (int r = 0; r < DMA_PER_WAVE; ++r) dma(r, v1, (kRing + 1) * TILE);
+            }
+        }
+        // Raw barriers: every LDS access of the loop is an LDS-direct load (drained with vmcnt
+        // at the end of phase X) or an asm read (drained with lgkmcnt inside phase X), so no fence
+        // is wanted there -- a fence would drain loads that are meant to stay in flight.
+        __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): the first tiles, and the ticket
+        if (wave8 == 0) {
+            const int nxt = claim_from(xcc, __builtin_amdgcn_readfirstlane(next_ticket));
+            if (lane == 0) mailbox[parity ^ 1] = nxt;
+            __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): the mailbox write is in LDS before the barrier
+        }
+        __builtin_amdgcn_s_barrier();
+        // ONE barrier per step.  Group 0 runs  X(k) | barrier | Y(k),  group 1  barrier | X(k) Y(k):
+        // between two barriers group 0 does Y(k) then X(k+1) while group 1 does X(k) then Y(k), so
+        // the waves of a SIMD are in opposite phases by program order but nothing holds them to a
+        // half-step grid.  Between barrier k and k+1 the ring is read at K(k), K(k+1), V^T(k-1),
+        // V^T(k) and written at K(k+3), V^T(k+2), whose slots (of K(k-1), V^T(k-2)) nobody reads
+        // after barrier k; a tile written in one interval is waited for (vmcnt) in the next and
+        // read in the one after: four slots each.
+        if (grp == 0) {
+            for (int k = 0, slot = 0; k < n_steps; ++k) {
+                phase_x(slot);
+                __builtin_amdgcn_s_barrier();
+                phase_y(k);
+                slot = slot == kRing - 1 ? 0 : slot + 1;
+            }
+        } else {
+            for (int k = 0, slot = 0; k < n_steps; ++k) {
+                __builtin_amdgcn_s_barrier();
+                phase_x(slot);
+                phase_y(k);
+                slot = slot == kRing - 1 ? 0 : slot + 1;
+            }
+        }
+        // End of the unit: the refills of its last steps (tiles nobody needs) must have landed
+        // before the next unit's first tiles go into the same slots, and every wave must be done
+        // reading the ring.
+        __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0)
+        __builtin_amdgcn_s_barrier();
+        const int next_unit = __builtin_amdgcn_readfirstlane(mailbox[parity ^ 1]);
+
+        // epilogue: divide by the running sum, round, store.  Empty rows (l = 0) give zeros.
+        const float l_tot = sum_across_halves(l_run);
+        const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
+        if (have_item && row < L) {
+            __bf16 *orow = reinterpret_cast<__bf16 *>(a.out) + ((size_t)head * R + (row - a.q_begin)) * D;
+#pragma unroll
+            for (int db = 0; db < NDB; ++db)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    bf16x4 w;
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) w[r] = (__bf16)(o[db][4 * g + r] * inv);
+                    *reinterpret_cast<bf16x4 *>(orow + 32 * db + 8 * g + 4 * hl) = w;
+                }
+        }
+        unit = next_unit;
     }
 }
 
@@ -942,10 +1016,11 @@ constexpr int kMaxDevices = 64;
 std::mutex g_device_mutex;
 void *g_scratch_ptr[kMaxDevices];       // device address of `scratch` on each device (looked up once)
 bool g_attr_set[kMaxDevices];           // dynamic-LDS limits of the kernels raised on this device
+int g_n_cus[kMaxDevices];               // compute units of the device
 
 // Once per device, with that device current: the address of its copy of `scratch`, and the
 // kernels' dynamic LDS limits.  Allocates nothing.
-int device_setup(int dev, void **scratch_out)
+int device_setup(int dev, void **scratch_out, int *n_cus_out)
 {
     if (dev < 0 || dev >= kMaxDevices) return bs::fail_msg(BS_EUNSUPPORTED, "device ordinal above 63");
     std::lock_guard<std::mutex> lock(g_device_mutex);
@@ -960,8 +1035,13 @@ int device_setup(int dev, void **scratch_out)
             e = hipFuncSetAttribute(reinterpret_cast<const void *>(bs::attn_prefill_f32<128>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)bs::f32_lds_bytes<128>());
         if (e != hipSuccess) return bs::fail_hip(e, "hipFuncSetAttribute");
+        int cus = 0;
+        e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+        if (e != hipSuccess || cus <= 0) return bs::fail_hip(e, "hipDeviceGetAttribute(compute units)");
+        g_n_cus[dev] = cus;
         g_attr_set[dev] = true;
     }
+    if (n_cus_out) *n_cus_out = g_n_cus[dev];
     if (scratch_out) {
         if (!g_scratch_ptr[dev]) {
             void *ptr = nullptr;
@@ -1007,18 +1087,19 @@ bs::KernelArgs kernel_args(const void *q, const void *k, const void *v, void *ou
 // Pre-pass (K and V^T into per-key-tile blocks of `workspace`) and the attention kernel.
 template <int D>
 void launch_bf16(const bs::KernelArgs &a, const bs_tilemap *tm, const DeviceMap *d, void *workspace, size_t pack_bytes,
-                 int n_kv_heads, hipStream_t st, void *ev_main_start)
+                 int n_kv_heads, int n_cus, hipStream_t st, void *ev_main_start)
 {
     __bf16 *kp = static_cast<__bf16 *>(workspace);
     __bf16 *vt = reinterpret_cast<__bf16 *>(static_cast<char *>(workspace) + pack_bytes);
     const dim3 tgrid((unsigned)tm->N, (unsigned)n_kv_heads, 2);
-    const dim3 pgrid((unsigned)d->n_pairs), pblock(bs::kPingPongThreads);
+    // one workgroup per CU (128 KB of LDS each), which take the units from the queues until they are empty
+    const dim3 pgrid((unsigned)std::min(d->n_pairs, n_cus)), pblock(bs::kPingPongThreads);
     hipLaunchKernelGGL(bs::pack_kv_tiles<D>, tgrid, dim3(256), 0, st, static_cast<const __bf16 *>(a.k),
-                       static_cast<const __bf16 *>(a.v), kp, vt, d->key_order, tm->L, tm->N);
+                       static_cast<const __bf16 *>(a.v), kp, vt, d->key_order, tm->L, tm->N, d->queue_ctr);
     if (ev_main_start) (void)hipEventRecord(static_cast<hipEvent_t>(ev_main_start), st);
     hipLaunchKernelGGL(bs::attn_prefill_bf16<D>, pgrid, pblock, bs::bf16_lds_bytes<D>(), st, a, d->code, d->text_bits,
                        d->sink_bits, d->span_range, d->row_order, d->free_before, d->span_free, d->pair_items,
-                       d->pair_ranges, kp, vt, tm->N);
+                       d->pair_ranges, kp, vt, tm->N, d->queue_ctr, d->queue_off);
 }
 
 size_t bf16_pack_bytes(const bs_tilemap *tm, int n_kv_heads, int head_dim)
@@ -1052,7 +1133,7 @@ extern "C" int bs_tilemap_prepare(bs_tilemap *tm, int32_t dtype, int32_t gqa_gro
     if (e != hipSuccess) return bs::fail_hip(e, "hipGetDevice");
     if (dev != d->device) return BS_EINVAL;  // the map lives on another device
     void *unused = nullptr;
-    if ((rc = device_setup(dev, &unused)) != BS_OK) return rc;
+    if ((rc = device_setup(dev, &unused, nullptr)) != BS_OK) return rc;
     if ((rc = bs::order_after_last_use(d, st)) != BS_OK) return rc;
     rc = bs::upload_binding(tm, dtype == BS_BF16 ? bs::kBindPairPlan : bs::kBindWorkList, gqa_group, st);
     if (rc != BS_OK) return rc;
@@ -1080,7 +1161,8 @@ extern "C" int bs_attn_prefill_ex(const void *q, const void *k, const void *v, v
     hipError_t e = hipGetDevice(&dev);
     if (e != hipSuccess) return bs::fail_hip(e, "hipGetDevice");
     if (dev != d->device) return BS_EINVAL;  // the map lives on another device
-    if ((rc = device_setup(dev, nullptr)) != BS_OK) return rc;
+    int n_cus = 0;
+    if ((rc = device_setup(dev, nullptr, &n_cus)) != BS_OK) return rc;
     if ((rc = bs::order_after_last_use(d, st)) != BS_OK) return rc;
     rc = bs::upload_binding(tm, dtype == BS_BF16 ? bs::kBindPairPlan : bs::kBindWorkList, gqa_group, st);
     if (rc != BS_OK) return rc;
@@ -1096,8 +1178,8 @@ extern "C" int bs_attn_prefill_ex(const void *q, const void *k, const void *v, v
             e = bs::pool_acquire(dev, 2 * pack_bytes, st, &d->vt_buf, &d->vt_bytes);
             if (e != hipSuccess) { d->vt_buf = nullptr; d->vt_bytes = 0; return bs::fail_hip(e, "hipMalloc(K / V^T workspace)"); }
         }
-        if (head_dim == 128) launch_bf16<128>(a, tm, d, d->vt_buf, pack_bytes, n_kv_heads, st, ev_main_start);
-        else launch_bf16<64>(a, tm, d, d->vt_buf, pack_bytes, n_kv_heads, st, ev_main_start);
+        if (head_dim == 128) launch_bf16<128>(a, tm, d, d->vt_buf, pack_bytes, n_kv_heads, n_cus, st, ev_main_start);
+        else launch_bf16<64>(a, tm, d, d->vt_buf, pack_bytes, n_kv_heads, n_cus, st, ev_main_start);
     } else {
         if (ev_main_start) (void)hipEventRecord(static_cast<hipEvent_t>(ev_main_start), st);
         const dim3 grid((unsigned)d->n_work), block(bs::kThreads);
@@ -1138,14 +1220,15 @@ extern "C" int bs_attn_prefill_static(const void *q, const void *k, const void *
     if (e != hipSuccess) return bs::fail_hip(e, "hipGetDevice");
     if (dev != d->device) return BS_EINVAL;  // the map lives on another device
     void *ws = nullptr;
-    if ((rc = device_setup(dev, &ws)) != BS_OK) return rc;   // looks the address up on the first call per device
+    int n_cus = 0;
+    if ((rc = device_setup(dev, &ws, &n_cus)) != BS_OK) return rc;   // looks the address up on the first call per device
     hipStream_t st = static_cast<hipStream_t>(stream);
     if ((rc = bs::order_after_last_use(d, st)) != BS_OK) return rc;
     const bs::KernelArgs a = kernel_args(q, k, v, out, tm, gqa_group, scale);
     // the pre-pass writes every slot of every tile it covers (keys, or zeros): nothing of the
     // previous call's contents is read
-    if (head_dim == 128) launch_bf16<128>(a, tm, d, ws, pack_bytes, n_kv_heads, st, nullptr);
-    else launch_bf16<64>(a, tm, d, ws, pack_bytes, n_kv_heads, st, nullptr);
+    if (head_dim == 128) launch_bf16<128>(a, tm, d, ws, pack_bytes, n_kv_heads, n_cus, st, nullptr);
+    else launch_bf16<64>(a, tm, d, ws, pack_bytes, n_kv_heads, n_cus, st, nullptr);
     e = hipGetLastError();
     if (e != hipSuccess) return bs::fail_hip(e, "kernel launch");
     e = hipEventRecord(d->last_use->ev, st);

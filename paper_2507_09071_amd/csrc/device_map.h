@@ -58,6 +58,8 @@ struct DeviceMap {
     const int4 *pair_items = nullptr;     // bf16 kernel: work units, two int4 each
     const int2 *pair_ranges = nullptr;
     int32_t n_pairs = 0;
+    const int32_t *queue_off = nullptr;   // [9] the units of XCD x are pair_items[queue_off[x] .. queue_off[x + 1])
+    int32_t *queue_ctr = nullptr;         // [8] next unit of each queue; cleared by the pre-pass of every call
     // ---- bf16 workspace: packed K tiles, then packed V^T tiles, of the last call
     void *vt_buf = nullptr;
     size_t vt_bytes = 0;

@@ -305,7 +305,8 @@ int upload_binding(bs_tilemap *tm, int32_t kind, int32_t gqa_group, hipStream_t 
     const size_t a_bytes = kind == kBindPairPlan ? plan.items.size() * sizeof(PairItem) : tm->work.size() * sizeof(WorkItem);
     const size_t off_b = align256(off_a + a_bytes);        // ranges of the work units
     const size_t b_bytes = kind == kBindPairPlan ? std::max<size_t>(plan.ranges.size(), 1) * sizeof(PairRange) : 0;
-    const size_t bytes = align256(off_b + b_bytes);
+    const size_t off_q = align256(off_b + b_bytes);        // queue offsets [9], then queue counters [8]
+    const size_t bytes = align256(off_q + 256);
 
     Staging sg;
     hipError_t e = staging_begin(bytes, &sg);
@@ -316,6 +317,8 @@ int upload_binding(bs_tilemap *tm, int32_t kind, int32_t gqa_group, hipStream_t 
         static_assert(sizeof(PairItem) == 2 * sizeof(int4) && sizeof(PairRange) == sizeof(int2), "copied as they are");
         std::memcpy(host + off_a, plan.items.data(), a_bytes);
         if (!plan.ranges.empty()) std::memcpy(host + off_b, plan.ranges.data(), plan.ranges.size() * sizeof(PairRange));
+        std::memset(host + off_q, 0, 256);
+        std::memcpy(host + off_q, plan.queue_off, sizeof plan.queue_off);
     } else {
         static_assert(sizeof(WorkItem) == sizeof(int2), "copied as it is");
         std::memcpy(host + off_a, tm->work.data(), a_bytes);
@@ -351,6 +354,8 @@ int upload_binding(bs_tilemap *tm, int32_t kind, int32_t gqa_group, hipStream_t 
     d->pair_items = kind == kBindPairPlan ? reinterpret_cast<const int4 *>(b + off_a) : nullptr;
     d->pair_ranges = kind == kBindPairPlan ? reinterpret_cast<const int2 *>(b + off_b) : nullptr;
     d->n_pairs = kind == kBindPairPlan ? (int32_t)plan.items.size() : 0;
+    d->queue_off = kind == kBindPairPlan ? reinterpret_cast<const int32_t *>(b + off_q) : nullptr;
+    d->queue_ctr = kind == kBindPairPlan ? reinterpret_cast<int32_t *>(b + off_q + 64) : nullptr;
     return BS_OK;
 }
 

@@ -835,11 +835,12 @@ void bs_plan_pairs(bs_tilemap *tm, int32_t G)
             }
         }
     }
-    // Launch order.  Heaviest units first (longest-processing-time rule), but in coarse cost
+    // Queue order.  Heaviest units first (longest-processing-time rule), but in coarse cost
     // buckets inside which units of one KV head stay together, walking the same tiles at about
-    // the same time.  Workgroup b runs on XCD b mod 8 (each XCD has its own L2), so the sorted
-    // list is then dealt to the XCDs in blocks of kXcdBlock consecutive units: the units of a
-    // block run side by side on one XCD and find each other's K / V^T tiles in its L2.
+    // the same time.  The sorted list is then dealt to eight queues, one per XCD (each XCD has its
+    // own L2), in blocks of kXcdBlock consecutive units: the units of a block run side by side on
+    // one XCD and find each other's K / V^T tiles in its L2.  The kernel's workgroups take the
+    // units of their XCD's queue in this order (plan.queue_off delimits the queues in plan.items).
     // Block size: 8 for a few thousand units (a bigger block costs load balance at the tail),
     // 16 for tens of thousands (measured on the 36K and 300K workloads).
     constexpr int32_t kCostBucket = 32, kXcds = 8;
@@ -853,16 +854,14 @@ void bs_plan_pairs(bs_tilemap *tm, int32_t G)
     });
     {
         const size_t n = plan.items.size();
-        std::vector<std::pair<int64_t, int32_t>> slot(n);
-        for (size_t p = 0; p < n; ++p) {
-            const int64_t q = (int64_t)p / kXcdBlock, j = (int64_t)p % kXcdBlock;
-            const int64_t x = q % kXcds, r = (q / kXcds) * kXcdBlock + j;   // XCD, rank on that XCD
-            slot[p] = {r * kXcds + x, (int32_t)p};
+        std::vector<bs::PairItem> queues[kXcds];
+        for (size_t p = 0; p < n; ++p) queues[(p / kXcdBlock) % kXcds].push_back(plan.items[p]);
+        plan.items.clear();
+        for (int x = 0; x < kXcds; ++x) {
+            plan.queue_off[x] = (int32_t)plan.items.size();
+            plan.items.insert(plan.items.end(), queues[x].begin(), queues[x].end());
         }
-        std::sort(slot.begin(), slot.end());
-        std::vector<bs::PairItem> dealt(n);
-        for (size_t b = 0; b < n; ++b) dealt[b] = plan.items[slot[b].second];
-        plan.items.swap(dealt);
+        plan.queue_off[kXcds] = (int32_t)plan.items.size();
     }
     for (bs::PairItem &it : plan.items)
         it.classes = tm->head_class[it.head_a] | (it.head_b >= 0 ? tm->head_class[it.head_b] << 8 : 0);

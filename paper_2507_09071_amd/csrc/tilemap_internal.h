@@ -50,7 +50,8 @@ struct PairPlan {
     int32_t gqa_group = 0;  // the plan depends on which heads share a KV head ...
     uint64_t epoch = 0;     // ... and on the class vector (bs_tilemap::class_epoch when it was made)
     std::vector<PairRange> ranges;
-    std::vector<PairItem> items;  // heaviest first
+    std::vector<PairItem> items;  // eight queues, one per XCD, each heaviest first
+    int32_t queue_off[9] = {0, 0, 0, 0, 0, 0, 0, 0, 0};   // queue x = items[queue_off[x] .. queue_off[x + 1])
 };
 
 struct DeviceMap;  // defined by the HIP side
