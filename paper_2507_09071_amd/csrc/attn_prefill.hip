@@ -754,10 +754,12 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(
     // so that units walking the same K / V^T tiles at about the same time share an L2.  A workgroup
     // reads the id of the XCD it runs on from the hardware register (it does not depend on the launch
     // order, which other streams can perturb) and claims the next unit of that queue with an atomic
-    // counter; when the queue is empty it helps out on the next one.  The first wave claims unit u + 1
-    // while unit u is set up (the atomic returns under the prologue's memory waits) and passes it on
-    // through a two-entry mailbox behind the ring.  Every wave reads the same mailbox entry, so the
-    // workgroup leaves the loop together.
+    // counter; when the queue is empty it helps out on the next one.  The first wave takes the ticket
+    // for the next unit two steps before the current one ends -- late, so that the units of a queue
+    // start in queue order (units that start together walk the same tiles together and share them in
+    // L2; a ticket taken a whole unit ahead was measured to cost half of that sharing), early enough
+    // for the atomic to return under the last steps -- and passes the unit on through a mailbox behind
+    // the ring.  Every wave reads the same mailbox entry, so the workgroup leaves the loop together.
     volatile int32_t *mailbox = reinterpret_cast<volatile int32_t *>(lds + 2 * kRing * TILE);
     int xcc;
     asm volatile("s_getreg_b32 %0, hwreg(HW_REG_XCC_ID, 0, 4)" : "=s"(xcc));
@@ -785,6 +787,26 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(
         if (lane == 0) r = atomicAdd(&queue_ctr[xcc], 1);
         return r;
     };
+    // The same without waiting for the answer: lane 0 alone issues the atomic (asm, so that the compiler
+    // does not wait for it on the spot) and the ticket is in lane 0 of the result once the vector-memory
+    // counter has drained (ticket_wait).  Until then the register must not be read.
+    auto take_ticket_async = [&]() __attribute__((always_inline)) {
+        int r;
+        unsigned long long save;
+        int32_t *ctr = queue_ctr + xcc;
+        const int one = 1;
+        asm volatile("s_mov_b64 %[save], exec\n\t"
+                     "s_mov_b64 exec, 1\n\t"
+                     "global_atomic_add %[r], %[ptr], %[one], off sc0\n\t"
+                     "s_mov_b64 exec, %[save]"
+                     : [r] "=&v"(r), [save] "=&s"(save)
+                     : [ptr] "v"(ctr), [one] "v"(one)
+                     : "memory");
+        return r;
+    };
+    auto ticket_wait = [&](int &ticket) __attribute__((always_inline)) {
+        asm volatile("s_waitcnt vmcnt(0)" : "+v"(ticket)::"memory");
+    };
     if (wave8 == 0) {
         const int first = claim_from(xcc, __builtin_amdgcn_readfirstlane(take_ticket()));
         if (lane == 0) mailbox[0] = first;
@@ -792,9 +814,8 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(
     __syncthreads();
     int unit = __builtin_amdgcn_readfirstlane(mailbox[0]);
 
-    for (int parity = 0; unit >= 0; parity ^= 1) {
+    while (unit >= 0) {
         int next_ticket = 0;
-        if (wave8 == 0) next_ticket = take_ticket();   // for the unit after this one; consumed after the prologue
         load_unit(unit);
         reset_unit_state();
         {
@@ -824,12 +845,7 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(
         // Raw barriers: every LDS access of the loop is an LDS-direct load (drained with vmcnt
         // at the end of phase X) or an asm read (drained with lgkmcnt inside phase X), so no fence
         // is wanted there -- a fence would drain loads that are meant to stay in flight.
-        __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): the first tiles, and the ticket
-        if (wave8 == 0) {
-            const int nxt = claim_from(xcc, __builtin_amdgcn_readfirstlane(next_ticket));
-            if (lane == 0) mailbox[parity ^ 1] = nxt;
-            __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): the mailbox write is in LDS before the barrier
-        }
+        __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): the first tiles
         __builtin_amdgcn_s_barrier();
         // ONE barrier per step.  Group 0 runs  X(k) | barrier | Y(k),  group 1  barrier | X(k) Y(k):
         // between two barriers group 0 does Y(k) then X(k+1) while group 1 does X(k) then Y(k), so
@@ -839,7 +855,9 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(
         // after barrier k; a tile written in one interval is waited for (vmcnt) in the next and
         // read in the one after: four slots each.
         if (grp == 0) {
+            const int k_claim = max(n_steps - 2, 0);
             for (int k = 0, slot = 0; k < n_steps; ++k) {
+                if (wave8 == 0 && k == k_claim) next_ticket = take_ticket_async();   // consumed after the loop
                 phase_x(slot);
                 __builtin_amdgcn_s_barrier();
                 phase_y(k);
@@ -855,10 +873,15 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(
         }
         // End of the unit: the refills of its last steps (tiles nobody needs) must have landed
         // before the next unit's first tiles go into the same slots, and every wave must be done
-        // reading the ring.
-        __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0)
+        // reading the ring.  The ticket has returned by then as well.
+        ticket_wait(next_ticket);            // vmcnt(0)
+        if (wave8 == 0) {
+            const int nxt = claim_from(xcc, __builtin_amdgcn_readfirstlane(next_ticket));
+            if (lane == 0) mailbox[0] = nxt;
+            __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): the mailbox write is in LDS before the barrier
+        }
         __builtin_amdgcn_s_barrier();
-        const int next_unit = __builtin_amdgcn_readfirstlane(mailbox[parity ^ 1]);
+        const int next_unit = __builtin_amdgcn_readfirstlane(mailbox[0]);
 
         // epilogue: divide by the running sum, round, store.  Empty rows (l = 0) give zeros.
         const float l_tot = sum_across_halves(l_run);
