@@ -90,16 +90,16 @@ class HipEvents:
         self.hip.hipEventDestroy(e)
 
 
-# HBM traffic per launch of the attention kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
-# runs, scaled by the same counters' reading for a 1 GiB copy (see profiles/).  Bytes.  These are
-# figures from earlier profiled runs of the same command, NOT read in this run; the JSON says so.
-TRAFFIC_SOURCE = "profiles/attn_prefill_bf16_d128_cfg2_36k.md (rocprofv3 --pmc FETCH_SIZE, WRITE_SIZE; not measured in this run)"
+# HBM-side traffic of one attention launch (read + written past the L2s, where they meet the fabric: the
+# 256 MB memory-side cache sits behind that point), from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of
+# this bench with the packed tile map, each counter scaled by its reading for a 1 GiB copy.  These are
+# figures of earlier profiled runs of the same command, NOT read in this run; the JSON says so.
+# Keyed by workload and row order of the map -> (bytes, summary under profiles/).
 MEASURED_TRAFFIC = {
-    # profiles/attn_prefill_bf16_d128_cfg2_36k.md (measured where L2 meets the fabric: the 256 MB
-    # memory-side cache sits behind that point); keyed by workload and row order of the tile map
-    ("cfg2-qwen2vl7b-36k/paper10/seed0", "packed"): 4.65e9,
-    ("cfg2-qwen2vl7b-36k/paper10/seed0", "regrouped"): 4.46e9,
-    ("cfg2-qwen2vl7b-36k/paper10/seed0", "natural"): 4.85e9,
+    ("cfg2-qwen2vl7b-36k/paper10/seed0", "packed"): (4.71e9, "profiles/attn_prefill_bf16_d128_cfg2_36k.md"),
+    ("cfg3-qwen25vl32b-128k/paper10/seed0", "packed"): (67.2e9, "profiles/attn_prefill_bf16_d128_128k_300k.md"),
+    ("cfg4-gemma3-27b-300k/paper10/seed0", "packed"): (403.5e9, "profiles/attn_prefill_bf16_d128_128k_300k.md"),
+    ("cfg5-stress-307200/paper10/seed0", "packed"): (182.5e9, "profiles/attn_prefill_bf16_d128_128k_300k.md"),
 }
 
 
@@ -419,7 +419,7 @@ def main():
     reuse_wall, reuse_host, reuse_idle = reused_map_steps(bs, torch, p, q, k, v, out, args.steps, flags)
 
     achieved = useful_flop / (kern_ms * 1e-3) / 1e12
-    traffic = MEASURED_TRAFFIC.get((p.name, order))
+    traffic, traffic_file = MEASURED_TRAFFIC.get((p.name, order), (None, None))
     res = {
         "metric": "attn prefill ms + useful TFLOP/s (MFMA util), speedup vs all-Dense @36K-300K",
         "value": round(useful_flop / (wall_ms * 1e-3) / 1e12, 3),
@@ -453,7 +453,7 @@ def main():
         "all_dense": dense,
         "roofline": {"bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS,
                      "unit": "TFLOP/s", "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": traffic,
-                     "traffic_source": TRAFFIC_SOURCE if traffic is not None else None,
+                     "traffic_source": (traffic_file + " (rocprofv3 --pmc FETCH_SIZE, WRITE_SIZE; not measured in this run)") if traffic is not None else None,
                      "kernel": "attn_prefill_%s<%d>" % (p.dtype, d),
                      "flop_per_launch": useful_flop, "avg_launch_ms": round(kern_ms, 4),
                      # the same useful FLOP over the device time of the whole call: the K / V^T tile-pack
