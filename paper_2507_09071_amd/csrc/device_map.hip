@@ -56,6 +56,7 @@ std::mutex g_mem_mutex;
 std::vector<CachedBlock> &g_cache = *new std::vector<CachedBlock>();
 StagingBuffer g_staging[kStagingBuffers];
 int g_staging_next = 0;
+std::vector<void *> &g_outgrown = *new std::vector<void *>();   // pinned buffers replaced by larger ones
 
 constexpr size_t kGranule = (size_t)1 << 20;
 size_t round_up(size_t x, size_t g) { return (x + g - 1) / g * g; }
@@ -121,11 +122,21 @@ hipError_t staging_begin(size_t bytes, Staging *out)
     // wait happens outside the lock, the buffer is reserved by in_use
     hipError_t e = wait_for ? hipEventSynchronize(wait_for) : hipSuccess;
     if (e == hipSuccess && sb->cap < bytes) {
-        if (sb->host) (void)hipHostFree(sb->host);
-        sb->host = nullptr; sb->cap = 0;
-        const size_t cap = round_up(bytes, kGranule);
-        e = hipHostMalloc(&sb->host, cap, hipHostMallocDefault);
-        if (e == hipSuccess) sb->cap = cap; else sb->host = nullptr;
+        // Grow in powers of two and keep the outgrown buffer (hipHostFree drains the device, which
+        // would stall the caller behind every kernel it has queued): the buffers a slot has outgrown
+        // add up to less than the one it holds.
+        size_t cap = kGranule;
+        while (cap < bytes) cap *= 2;
+        void *grown = nullptr;
+        e = hipHostMalloc(&grown, cap, hipHostMallocDefault);
+        if (e == hipSuccess) {
+            if (sb->host) {
+                std::lock_guard<std::mutex> lock(g_mem_mutex);
+                g_outgrown.push_back(sb->host);
+            }
+            sb->host = grown;
+            sb->cap = cap;
+        }
     }
     if (e == hipSuccess && !sb->done) {
         e = hipEventCreateWithFlags(&sb->done, hipEventDisableTiming);
