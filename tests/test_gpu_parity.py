@@ -312,3 +312,42 @@ def test_one_map_per_prompt_rebound_per_layer_without_synchronisation():
             want = oracle_rows(base.with_classes(hc), q, k, v)
             for h in range(base.n_q_heads):
                 assert_close(o[h].float().cpu().numpy(), want[h], tol, f"{dtype} layer {li} head {h} class {hc[h]}")
+
+
+def test_two_streams_one_map_and_two_maps_side_by_side():
+    """Streams of equal priority.  (1) One map used alternately on two streams, re-bound in between: the
+    library orders every use behind the previous one, so each call must give what the same binding gives
+    on one stream.  (2) Two prompts with a map each, queued on two streams at the same time: their kernels
+    may overlap on the device and share nothing but the library's block cache."""
+    p = W.config(2)
+    q, k, v = W.make_qkv(p, 5, DEV)
+    rolled = np.roll(p.head_class, 3)
+    ref_a, tm = run_prefill(p, q, k, v, flags=bs.BS_MAP_PACK_KEYS)
+    tm.rebind(rolled)
+    ref_b, _ = run_prefill(p.with_classes(rolled), q, k, v, tm)
+    assert not torch.equal(ref_a, ref_b)
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    outs = [torch.full_like(q, float("nan")) for _ in range(6)]
+    torch.cuda.synchronize()
+    for i, o in enumerate(outs):
+        st = (s1, s2)[i % 2]
+        tm.rebind(p.head_class if i % 3 == 0 else rolled)
+        bs.bs_attn_prefill(q, k, v, o, tm, bs.BS_BF16, p.n_q_heads, p.gqa_group, p.head_dim, p.scale, st.cuda_stream)
+    torch.cuda.synchronize()
+    for i, o in enumerate(outs):
+        assert torch.equal(o, ref_a if i % 3 == 0 else ref_b), f"call {i}"
+
+    p2 = W.config(5, target_len=W.STRESS_LENGTHS[0])
+    q2, k2, v2 = W.make_qkv(p2, 6, DEV)
+    ref_2, tm2 = run_prefill(p2, q2, k2, v2, flags=bs.BS_MAP_PACK_KEYS)
+    tm.rebind(p.head_class)
+    o1 = [torch.full_like(q, float("nan")) for _ in range(3)]
+    o2 = [torch.full_like(q2, float("nan")) for _ in range(3)]
+    torch.cuda.synchronize()
+    for a, b in zip(o1, o2):
+        bs.bs_attn_prefill(q, k, v, a, tm, bs.BS_BF16, p.n_q_heads, p.gqa_group, p.head_dim, p.scale, s1.cuda_stream)
+        bs.bs_attn_prefill(q2, k2, v2, b, tm2, bs.BS_BF16, p2.n_q_heads, p2.gqa_group, p2.head_dim, p2.scale,
+                           s2.cuda_stream)
+    torch.cuda.synchronize()
+    for a, b in zip(o1, o2):
+        assert torch.equal(a, ref_a) and torch.equal(b, ref_2)
