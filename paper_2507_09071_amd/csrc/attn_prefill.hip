@@ -12,6 +12,8 @@
 //  * a workgroup of eight 64-lane waves owns one work unit: two (head, query tile) items that
 //    read the same KV head, four waves each; wave w of a group owns rows 32w..32w+31 of its item
 //    and keeps its Q rows in registers for the whole pass;
+//  * the launch is one workgroup per CU; a workgroup stays resident and claims unit after unit from
+//    the queue of the XCD it runs on (eight queues, filled by the host; see "Work distribution");
 //  * scores are produced transposed, S^T = K Q^T, with 32x32x16 bf16 MFMA tiles, so every lane
 //    holds 16 keys of ONE query per 32-key block: row max / row sum are in-lane reductions plus
 //    one exchange with the lane 32 apart (v_permlane32_swap);
