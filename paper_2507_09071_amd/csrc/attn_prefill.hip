@@ -643,6 +643,14 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(
             mul_one(cur, I2{}, f[2]); read_one(nxt, I2{}, f[2]);
             mul_one(cur, I3{}, f[3]); read_one(nxt, I3{}, f[3]);
         };
+        // The same with two reads behind each MFMA: the refill of its own register (batch `nxt`) and
+        // one read of batch `mid` into the idle set g.
+        auto batch2 = [&](auto cur, auto mid, bf16x8 (&g)[4], auto nxt, bf16x8 (&f)[4]) __attribute__((always_inline)) {
+            mul_one(cur, I0{}, f[0]); read_one(mid, I0{}, g[0]); read_one(nxt, I0{}, f[0]);
+            mul_one(cur, I1{}, f[1]); read_one(mid, I1{}, g[1]); read_one(nxt, I1{}, f[1]);
+            mul_one(cur, I2{}, f[2]); read_one(mid, I2{}, g[2]); read_one(nxt, I2{}, f[2]);
+            mul_one(cur, I3{}, f[3]); read_one(mid, I3{}, g[3]); read_one(nxt, I3{}, f[3]);
+        };
         // Refill addresses: computed while the first operand reads are in flight.
         const char *ksrc = nullptr, *vsrc = nullptr;
         auto refill_prepare = [&]() __attribute__((always_inline)) {
@@ -655,11 +663,14 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(
         };
         if constexpr (D == 128) {
             // batch order: PV0 S0 PV1 S1 PV2 S2 PV3 S3, four reads / MFMAs each
-            read_batch(PvBatch<0>{}, fa); read_batch(ScBatch<0, true>{}, fb); read_batch(PvBatch<1>{}, fc);
+            // Only two batches are read ahead of the first MFMA (the burst of all four waves of a group
+            // costs every wave its share of the LDS time); the third goes out behind the first four
+            // MFMAs together with their refills.
+            read_batch(PvBatch<0>{}, fa); read_batch(ScBatch<0, true>{}, fb);
             refill_prepare();
-            lds_wait<8>(fa); batch(PvBatch<0>{}, ScBatch<1, false>{}, fa);
+            lds_wait<4>(fa); batch2(PvBatch<0>{}, PvBatch<1>{}, fc, ScBatch<1, false>{}, fa);
             lds_wait<8>(fb); batch(ScBatch<0, true>{}, PvBatch<2>{}, fb);
-            lds_wait<8>(fc); batch(PvBatch<1>{}, ScBatch<2, false>{}, fc);
+            lds_wait<5>(fc); batch(PvBatch<1>{}, ScBatch<2, false>{}, fc);   // behind the last PV1 read: one S1 read, four PV2
             lds_wait<8>(fa); batch(ScBatch<1, false>{}, PvBatch<3>{}, fa);
             lds_wait<8>(fb); batch(PvBatch<2>{}, ScBatch<3, false>{}, fb);
             lds_wait<8>(fc); batch(ScBatch<2, false>{}, NoBatch{}, fc);
