@@ -617,7 +617,20 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(
     // issued after the batch waited for.  A register is refilled right after the MFMA that
     // read it has issued (operands are read at issue, LDS data returns later), so the reads
     // issue in the shadow of the MFMAs.
-    auto phase_x = [&](int S) __attribute__((always_inline)) {  // S = k mod 4
+    // text / sink key bits of the tile w0 names (scalar registers, fetched one step ahead)
+    uint64_t tb_cur = 0, sb_cur = 0;
+    // Scalar bookkeeping between two vector phases: w0 moves on to the tile of the coming phase Y and
+    // the key bit masks of that tile are requested.  It runs inside phase X, between two MFMA batches,
+    // where the wave has issue slots to spare (every MFMA keeps the matrix pipe busy for 32 cycles).
+    auto advance_tile = [&]() __attribute__((always_inline)) {
+        __builtin_amdgcn_sched_barrier(0);
+        w0.next();
+        const int nn = min(__builtin_amdgcn_readfirstlane(w0.n), n_k_tiles - 1);
+        tb_cur = map_text_bits[nn];
+        sb_cur = map_sink_bits[nn];
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    auto phase_x = [&](int S, bool advance) __attribute__((always_inline)) {  // S = k mod 4; advance: k > 0
         auto ring = [](int x) { return x >= kRing ? x - kRing : x; };
         const int Sv = ring(S + kRing - 1);                          // V^T(k-1)
         const int Sk_dst = ring(ring(S + 2) + ahead), Sv_dst = ring(S + 1 + ahead);
@@ -672,6 +685,7 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(
             lds_wait<8>(fb); batch(ScBatch<0, true>{}, PvBatch<2>{}, fb);
             lds_wait<5>(fc); batch(PvBatch<1>{}, ScBatch<2, false>{}, fc);   // behind the last PV1 read: one S1 read, four PV2
             lds_wait<8>(fa); batch(ScBatch<1, false>{}, PvBatch<3>{}, fa);
+            if (advance) advance_tile();
             lds_wait<8>(fb); batch(PvBatch<2>{}, ScBatch<3, false>{}, fb);
             lds_wait<8>(fc); batch(ScBatch<2, false>{}, NoBatch{}, fc);
             lds_wait<4>(fa); batch(PvBatch<3>{}, NoBatch{}, fa);
@@ -684,11 +698,15 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(
             lds_wait<6>(fa); batch(PvBatch<0>{}, PvBatch<2>{}, fa);                     // 4 2 | 2
             lds_wait<4>(fb); batch(ScBatch<0, true>{}, ScBatch<1, false>{}, fb);        // 2 2 | 4
             lds_wait<6>(fc); batch(PvBatch<1>{}, PvBatch<3>{}, fc);                     // 2 4 | 2
+            if (advance) advance_tile();
             lds_wait<6>(fa); batch(PvBatch<2>{}, NoBatch{}, fa);
             lds_wait<2>(fb); batch(ScBatch<1, false>{}, NoBatch{}, fb);
             lds_wait<0>(fc); batch(PvBatch<3>{}, NoBatch{}, fc);
             mfma_drain(o[0], o[1]);   // the scores finished two MFMAs earlier
         }
+        // Every LDS read and scalar load of the phase has returned (the last lds_wait was for zero): say so
+        // in a form the compiler sees, or it waits for its own scalar loads in the middle of the next chain.
+        __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0)
         // Refill: this wave's share of K(k+2+ahead) and V^T(k+1+ahead) into the slots of the tiles
         // four steps older, which nobody reads after the last barrier.  Unconditional: past the end of the
         // list a valid tile is fetched again and never used.  Issued after the last MFMA:
@@ -707,8 +725,6 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(
         asm volatile("s_waitcnt vmcnt(%0)" ::"n"(2 * DMA_PER_WAVE));
     };
 
-    // text / sink key bits of the tile w0 names (scalar registers, fetched one step ahead)
-    uint64_t tb_cur = 0, sb_cur = 0;
     // Phase Y of step k: mask (PARTIAL tiles), online softmax, rescale O, round P to bf16.
     auto phase_y = [&](int k) __attribute__((always_inline)) {
         if (k < T) {
@@ -740,11 +756,6 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(
 #pragma unroll
                     for (int v = 0; v < 16; ++v) o[db][v] *= alpha;
             }
-            w0.next();
-            // key bit masks of the next tile: requested now, used one step later
-            const int nn = min(__builtin_amdgcn_readfirstlane(w0.n), n_k_tiles - 1);
-            tb_cur = map_text_bits[nn];
-            sb_cur = map_sink_bits[nn];
         } else {
             // past the last tile: the final phase X adds P(T-1) V(T-1); steps after it (none
             // today) must add nothing
@@ -859,6 +870,7 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(
         // at the end of phase X) or an asm read (drained with lgkmcnt inside phase X), so no fence
         // is wanted there -- a fence would drain loads that are meant to stay in flight.
         __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): the first tiles
+        __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): the unit's scalar loads (none stays pending into the loop)
         __builtin_amdgcn_s_barrier();
         // ONE barrier per step.  Group 0 runs  X(k) | barrier | Y(k),  group 1  barrier | X(k) Y(k):
         // between two barriers group 0 does Y(k) then X(k+1) while group 1 does X(k) then Y(k), so
@@ -871,7 +883,7 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(
             const int k_claim = max(n_steps - 2, 0);
             for (int k = 0, slot = 0; k < n_steps; ++k) {
                 if (wave8 == 0 && k == k_claim) next_ticket = take_ticket_async();   // consumed after the loop
-                phase_x(slot);
+                phase_x(slot, k > 0);
                 __builtin_amdgcn_s_barrier();
                 phase_y(k);
                 slot = slot == kRing - 1 ? 0 : slot + 1;
@@ -879,7 +891,7 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(
         } else {
             for (int k = 0, slot = 0; k < n_steps; ++k) {
                 __builtin_amdgcn_s_barrier();
-                phase_x(slot);
+                phase_x(slot, k > 0);
                 phase_y(k);
                 slot = slot == kRing - 1 ? 0 : slot + 1;
             }
