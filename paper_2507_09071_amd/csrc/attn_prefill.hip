@@ -569,11 +569,18 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(
 
     // LDS-direct loads of packed tiles into ring slots: straight TILE-byte copies.  Each wave
     // instruction moves 1 KB (lane l -> bytes 16l..16l+15); instruction r of wave w (0..7) covers
-    // bytes (8r + w) KB .. +1 KB of the tile, so the eight waves together fetch a tile.
+    // bytes (8r + w) KB .. +1 KB of the tile, so the eight waves together fetch a tile.  The instruction
+    // takes its address as a scalar base (the tile, uniform) plus a vector offset that never changes, and
+    // its LDS destination in M0: nothing of it goes through the vector ALU, which the other wave of the
+    // SIMD keeps busy (asm: the compiler forms a 64-bit vector address with a vector add per load instead).
     const uint32_t dma_lane_off = wave8 * 1024 + lane * 16;
-    auto dma = [&](int r, const char *tile, int slot_byte) {
-        unsigned char *dst = lds + slot_byte + wave8 * 1024 + r * 8 * 1024;
-        __builtin_amdgcn_global_load_lds((global_void_ptr)((tile + r * 8 * 1024) + dma_lane_off), (lds_void_ptr)dst, 16, 0, 0);
+    auto dma = [&](int r, const char *tile, int slot_byte) __attribute__((always_inline)) {
+        const uint32_t dst = ring + slot_byte + wave8 * 1024 + r * 8 * 1024;   // lane 0's 16 bytes
+        const char *src = tile + r * 8 * 1024;
+        asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1"
+                     :
+                     : "v"(dma_lane_off), "s"(src), "s"(dst)
+                     : "memory", "m0");
     };
     auto tile_ptr = [&](const char *base, int n) {
         return base + (size_t)min(n, n_k_tiles - 1) * TILE;  // a walker past its end names no tile
