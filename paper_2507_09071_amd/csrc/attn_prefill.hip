@@ -259,10 +259,38 @@ __device__ inline void softmax_block(floatx16 (&s)[2], float &m_run, float &l_ru
 //   MODE 1  row-uniform PARTIAL tile: a lane's query sees either all 64 keys or none (`drop`).
 //           A dropped row keeps its running max and gets p = 0 through an infinite offset.
 //   MODE 2  general PARTIAL tile: `s` already holds -inf at the masked positions.
+// Fast path (FULL tiles): the probabilities are first formed against the reference point the row already
+// has, without looking for the tile maximum.  Any reference gives the same quotient O / l as long as
+// nothing overflows, so this is exact whenever the row sums of the tile stay below kFastLimit -- which
+// they do on almost every tile after a row's first (scores of neighbouring tiles differ by a few units in
+// the exp2 domain, not by 16).  A wave in which some lane's sum is too large, infinite or NaN (no reference
+// yet: m = -inf) repeats the tile on the general path below, which moves the reference.  Returns whether
+// alpha may differ from 1.
 template <int MODE>
-__device__ inline void softmax_pack(const floatx16 (&s)[2], bf16x8 (&pf)[2][2], float &m_run, float &l_run,
+__device__ inline bool softmax_pack(const floatx16 (&s)[2], bf16x8 (&pf)[2][2], float &m_run, float &l_run,
                                     float &alpha, float c, bool drop)
 {
+    constexpr float kFastLimit = 65536.f;
+    if constexpr (MODE == 0) {   // PARTIAL tiles keep the one path (no registers to spare for two)
+        const float off = -(m_run * c);   // m = -inf: +inf, caught below
+        float sum[4] = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int kb = 0; kb < 2; ++kb)
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const float pv = __builtin_amdgcn_exp2f(fmaf(s[kb][8 * t + e], c, off));
+                    sum[e & 3] += pv;
+                    pf[kb][t][e] = (__bf16)pv;
+                }
+        const float tile_sum = (sum[0] + sum[1]) + (sum[2] + sum[3]);
+        if (!__any(!(tile_sum <= kFastLimit))) {
+            l_run += tile_sum;
+            alpha = 1.f;
+            return false;
+        }
+    }
     // four independent max chains
     float mx[4];
 #pragma unroll
@@ -297,6 +325,7 @@ __device__ inline void softmax_pack(const floatx16 (&s)[2], bf16x8 (&pf)[2][2], 
             }
     l_run = fmaf(l_run, alpha, (sum[0] + sum[1]) + (sum[2] + sum[3]));
     m_run = m_new;
+    return true;
 }
 
 typedef __attribute__((address_space(3))) void *lds_void_ptr;
@@ -541,9 +570,9 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(
     // three walkers over the merged tile list: w0 names the tile of the current step (state),
     // w1 the next tile (V^T refill), w2 the one after (K refill)
     PairWalker w0, w1, w2, wt1, wt2;
-    // the second group's matrix phase k runs one barrier interval before the first group's phase
-    // k + 1, in which the first group fetches the same tiles: it fetches one tile further ahead
-    const int ahead = grp;
+    // Both groups fetch, in the barrier interval k, their shares of K(k+3) and V^T(k+2): the second group
+    // at the end of its matrix phase k, the first group right behind barrier k, before its vector phase.
+    constexpr int ahead = 1;
     auto reset_unit_state = [&]() __attribute__((always_inline)) {
 #pragma unroll
         for (int db = 0; db < NDB; ++db)
@@ -637,10 +666,20 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(
         sb_cur = map_sink_bits[nn];
         __builtin_amdgcn_sched_barrier(0);
     };
-    auto phase_x = [&](int S, bool advance) __attribute__((always_inline)) {  // S = k mod 4; advance: k > 0
+    const char *ksrc = nullptr, *vsrc = nullptr;   // tiles of the coming refill
+    int Sk_dst = 0, Sv_dst = 0;                    // and their ring slots
+    auto issue_refill = [&]() __attribute__((always_inline)) {
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int r = 0; r < DMA_PER_WAVE; ++r) dma(r, ksrc, Sk_dst * TILE);
+#pragma unroll
+        for (int r = 0; r < DMA_PER_WAVE; ++r) dma(r, vsrc, (kRing + Sv_dst) * TILE);
+        __builtin_amdgcn_sched_barrier(0);
+    };
+    auto phase_x = [&](int S, bool advance, auto refill_here) __attribute__((always_inline)) {  // S = k mod 4; advance: k > 0
         auto ring = [](int x) { return x >= kRing ? x - kRing : x; };
         const int Sv = ring(S + kRing - 1);                          // V^T(k-1)
-        const int Sk_dst = ring(ring(S + 2) + ahead), Sv_dst = ring(S + 1 + ahead);
+        Sk_dst = ring(ring(S + 2) + ahead); Sv_dst = ring(S + 1 + ahead);
         kbase = kaddr0 + S * TILE;
         vbase = kaddr0 + (kRing + Sv) * TILE;
         bf16x8 fa[4], fb[4], fc[4];
@@ -672,7 +711,6 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(
             mul_one(cur, I3{}, f[3]); read_one(mid, I3{}, g[3]); read_one(nxt, I3{}, f[3]);
         };
         // Refill addresses: computed while the first operand reads are in flight.
-        const char *ksrc = nullptr, *vsrc = nullptr;
         auto refill_prepare = [&]() __attribute__((always_inline)) {
             __builtin_amdgcn_sched_barrier(0);
             ksrc = tile_ptr(kph, w2.n);
@@ -720,12 +758,7 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(
         // an LDS-direct load issued while the matrix pipe of the SIMD is being fed stalls the
         // wave several times longer (measured both between the MFMAs of this phase and from
         // the other group's vector phase).
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int r = 0; r < DMA_PER_WAVE; ++r) dma(r, ksrc, Sk_dst * TILE);
-#pragma unroll
-        for (int r = 0; r < DMA_PER_WAVE; ++r) dma(r, vsrc, (kRing + Sv_dst) * TILE);
-        __builtin_amdgcn_sched_barrier(0);
+        if constexpr (decltype(refill_here)::value) issue_refill();
         // Wait for the loads issued one step ago (only this step's may stay in flight): after
         // the next barrier every wave has passed this wait, and the tile is read in the interval
         // that follows it.
@@ -741,8 +774,9 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(
             // code path keeps the register allocation of the loop simple.
             const int st = have_item ? w0.state(grp) : 0;
             float alpha;
+            bool rescale;
             if (st == 2) {
-                softmax_pack<0>(s, pf, m_run, l_run, alpha, a.scale_log2e, false);
+                rescale = softmax_pack<0>(s, pf, m_run, l_run, alpha, a.scale_log2e, false);
             } else {
                 const int nu = __builtin_amdgcn_readfirstlane(w0.n);
                 uint64_t allowed = allowed_keys(qv, cls, tb_cur, sb_cur, nu, a.n_prompt_tiles);
@@ -750,14 +784,14 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(
                 if (__all(allowed == 0ull || allowed == ~0ull)) {
                     // every query of the wave sees all 64 keys or none (e.g. a text row and an
                     // image row over keys of another image): no per-score work
-                    softmax_pack<1>(s, pf, m_run, l_run, alpha, a.scale_log2e, allowed == 0ull);
+                    rescale = softmax_pack<1>(s, pf, m_run, l_run, alpha, a.scale_log2e, allowed == 0ull);
                 } else {
                     floatx16 ms[2];
                     apply_mask_tight(s, ms, allowed, hl);
-                    softmax_pack<2>(ms, pf, m_run, l_run, alpha, a.scale_log2e, false);
+                    rescale = softmax_pack<2>(ms, pf, m_run, l_run, alpha, a.scale_log2e, false);
                 }
             }
-            if (__any(alpha != 1.f)) {
+            if (rescale && __any(alpha != 1.f)) {
 #pragma unroll
                 for (int db = 0; db < NDB; ++db)
 #pragma unroll
@@ -863,9 +897,7 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(
             for (int r = 0; r < DMA_PER_WAVE; ++r) dma(r, k1, TILE);
 #pragma unroll
             for (int r = 0; r < DMA_PER_WAVE; ++r) dma(r, v0, kRing * TILE);
-            if (ahead) {
-                // the second group's share of K(2) and V^T(1): the first group fetches its share in
-                // its first matrix phase, which this group has no counterpart for
+            {
                 const char *k2 = tile_ptr(kph, wt2.n), *v1 = tile_ptr(vth, wt1.n);
 #pragma unroll
                 for (int r = 0; r < DMA_PER_WAVE; ++r) dma(r, k2, 2 * TILE);
@@ -890,15 +922,16 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(
             const int k_claim = max(n_steps - 2, 0);
             for (int k = 0, slot = 0; k < n_steps; ++k) {
                 if (wave8 == 0 && k == k_claim) next_ticket = take_ticket_async();   // consumed after the loop
-                phase_x(slot, k > 0);
+                phase_x(slot, k > 0, std::false_type{});
                 __builtin_amdgcn_s_barrier();
+                issue_refill();   // under the second group's head reads, before its chain starts
                 phase_y(k);
                 slot = slot == kRing - 1 ? 0 : slot + 1;
             }
         } else {
             for (int k = 0, slot = 0; k < n_steps; ++k) {
                 __builtin_amdgcn_s_barrier();
-                phase_x(slot, k > 0);
+                phase_x(slot, k > 0, std::true_type{});
                 phase_y(k);
                 slot = slot == kRing - 1 ? 0 : slot + 1;
             }

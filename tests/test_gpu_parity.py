@@ -351,3 +351,28 @@ def test_two_streams_one_map_and_two_maps_side_by_side():
     torch.cuda.synchronize()
     for a, b in zip(o1, o2):
         assert torch.equal(a, ref_a) and torch.equal(b, ref_2)
+
+
+@pytest.mark.parametrize("rise", [0.02, 0.35, 4.0, -0.35])
+def test_scores_that_drift_along_the_keys(rise):
+    """Scores that rise (or fall) steadily with the key position, on top of the usual noise: `rise` is
+    the step per key in the exp2 domain, i.e. 1.3, 22 and 256 per key tile.  The kernel's softmax first
+    tries a tile against the reference point the row already has and only looks for the tile maximum
+    when a row sum passes its limit or overflows: the small rise stays on that path, the middle one
+    passes the limit on every tile, the large one overflows fp32 within a tile (the general path must
+    take over and rescale), the falling one underflows against a reference set by the first tile.
+    All classes, both map layouts."""
+    d = 128
+    p = W.custom_prompt([("T", 40), ("I", 700), ("T", 9), ("I", 900), ("T", 30), ("I", 260), ("T", 77)],
+                        [D, S, I, IS, D, IS], n_kv_heads=2, head_dim=d, dtype="bf16", sink_len=16,
+                        name=f"drift{rise}", value_recipe={"std": 1.0})
+    q, k, v = W.make_qkv(p, 21, DEV)
+    # channel 0 carries the drift: q[.., 0] = 8, k[j, 0] = j * step, so that scale * log2(e) * 8 * step = rise
+    step = rise / (8.0 * p.scale * 1.4426950408889634)
+    q[:, :, 0] = 8.0
+    k[:, :, 0] = (torch.arange(p.seq_len, device=DEV, dtype=torch.float32) * step).to(k.dtype)[None, :]
+    for flags in (0, bs.BS_MAP_PACK_KEYS):
+        out, _ = run_prefill(p, q, k, v, flags=flags)
+        want = oracle_rows(p, q, k, v)
+        for h in range(p.n_q_heads):
+            assert_close(out[h].float().cpu().numpy(), want[h], "bf16", f"rise {rise} flags {flags} head {h} class {p.head_class[h]}")
