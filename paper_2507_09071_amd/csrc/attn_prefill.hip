@@ -752,12 +752,13 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(
         // Every LDS read and scalar load of the phase has returned (the last lds_wait was for zero): say so
         // in a form the compiler sees, or it waits for its own scalar loads in the middle of the next chain.
         __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0)
-        // Refill: this wave's share of K(k+2+ahead) and V^T(k+1+ahead) into the slots of the tiles
-        // four steps older, which nobody reads after the last barrier.  Unconditional: past the end of the
-        // list a valid tile is fetched again and never used.  Issued after the last MFMA:
-        // an LDS-direct load issued while the matrix pipe of the SIMD is being fed stalls the
-        // wave several times longer (measured both between the MFMAs of this phase and from
-        // the other group's vector phase).
+        // Refill: this wave's share of K(k+3) and V^T(k+2) into the slots of the tiles four steps older,
+        // which nobody reads after barrier k.  Unconditional: past the end of the list a valid tile is
+        // fetched again and never used.  An LDS-direct load issued while the other wave of the SIMD issues
+        // matrix or vector instructions stalls this wave several times longer, so each group issues it in a
+        // window in which its mate is quiet: the second group here, after its last MFMA, while the first
+        // group waits for the head reads of its next matrix phase; the first group right behind the barrier
+        // (see the step loop), while the second group waits for its head reads.
         if constexpr (decltype(refill_here)::value) issue_refill();
         // Wait for the loads issued one step ago (only this step's may stay in flight): after
         // the next barrier every wave has passed this wait, and the tile is read in the interval
@@ -911,13 +912,14 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(
         __builtin_amdgcn_s_waitcnt(0x0f70);  // vmcnt(0): the first tiles
         __builtin_amdgcn_s_waitcnt(0xc07f);  // lgkmcnt(0): the unit's scalar loads (none stays pending into the loop)
         __builtin_amdgcn_s_barrier();
-        // ONE barrier per step.  Group 0 runs  X(k) | barrier | Y(k),  group 1  barrier | X(k) Y(k):
+        // ONE barrier per step.  Group 0 runs  X(k) | barrier | refill Y(k),  group 1  barrier | X(k) refill Y(k):
         // between two barriers group 0 does Y(k) then X(k+1) while group 1 does X(k) then Y(k), so
         // the waves of a SIMD are in opposite phases by program order but nothing holds them to a
         // half-step grid.  Between barrier k and k+1 the ring is read at K(k), K(k+1), V^T(k-1),
-        // V^T(k) and written at K(k+3), V^T(k+2), whose slots (of K(k-1), V^T(k-2)) nobody reads
-        // after barrier k; a tile written in one interval is waited for (vmcnt) in the next and
-        // read in the one after: four slots each.
+        // V^T(k) and written by both groups at K(k+3), V^T(k+2), whose slots (of K(k-1), V^T(k-2))
+        // nobody reads after barrier k; a wave waits for its loads of one interval (vmcnt) at the
+        // end of its next matrix phase, i.e. before barrier k + 2 at the latest, and the tiles are read
+        // from the interval after that barrier on: four slots each.
         if (grp == 0) {
             const int k_claim = max(n_steps - 2, 0);
             for (int k = 0, slot = 0; k < n_steps; ++k) {
