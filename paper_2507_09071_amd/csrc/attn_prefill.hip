@@ -917,9 +917,9 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(
         // the waves of a SIMD are in opposite phases by program order but nothing holds them to a
         // half-step grid.  Between barrier k and k+1 the ring is read at K(k), K(k+1), V^T(k-1),
         // V^T(k) and written by both groups at K(k+3), V^T(k+2), whose slots (of K(k-1), V^T(k-2))
-        // nobody reads after barrier k; a wave waits for its loads of one interval (vmcnt) at the
-        // end of its next matrix phase, i.e. before barrier k + 2 at the latest, and the tiles are read
-        // from the interval after that barrier on: four slots each.
+        // nobody reads after barrier k; at the end of every matrix phase a wave lets only its newest
+        // loads stay in flight (vmcnt), so the loads of interval k have landed before barrier k + 2,
+        // and the tiles are read from the interval after that barrier on: four slots each.
         if (grp == 0) {
             const int k_claim = max(n_steps - 2, 0);
             for (int k = 0, slot = 0; k < n_steps; ++k) {
