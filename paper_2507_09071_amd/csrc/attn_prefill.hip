@@ -950,21 +950,49 @@ __global__ __launch_bounds__(kPingPongThreads, 2) void attn_prefill_bf16(
         __builtin_amdgcn_s_barrier();
         const int next_unit = __builtin_amdgcn_readfirstlane(mailbox[0]);
 
-        // epilogue: divide by the running sum, round, store.  Empty rows (l = 0) give zeros.
+        // epilogue: divide by the running sum, round, store.  Empty rows (l = 0) give zeros.  A lane holds
+        // four channels of one row at a time (O^T accumulators), which would make every store instruction
+        // touch 64 rows with 8 bytes each; the tile goes through LDS instead (the ring is free: every wave is
+        // past the barrier above), 64 channels at a time in a wave-private patch, and leaves as 16-byte pieces
+        // of 128-byte row segments.
         const float l_tot = sum_across_halves(l_run);
         const float inv = l_tot > 0.f ? 1.f / l_tot : 0.f;
-        if (have_item && row < L) {
-            __bf16 *orow = reinterpret_cast<__bf16 *>(a.out) + ((size_t)head * R + (row - a.q_begin)) * D;
+        {
+            constexpr int kStageRow = 128 + 16;                 // 64 channels, then the row's position
+            unsigned char *stage = lds + wave8 * (32 * kStageRow);
+            if (hl == 0) *reinterpret_cast<int32_t *>(stage + col * kStageRow + 128) = row;
 #pragma unroll
-            for (int db = 0; db < NDB; ++db)
+            for (int half = 0; half < NDB / 2; ++half) {
 #pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    bf16x4 w;
+                for (int dbl = 0; dbl < 2; ++dbl)
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) w[r] = (__bf16)(o[db][4 * g + r] * inv);
-                    *reinterpret_cast<bf16x4 *>(orow + 32 * db + 8 * g + 4 * hl) = w;
+                    for (int g = 0; g < 4; ++g) {
+                        bf16x4 w;
+#pragma unroll
+                        for (int r = 0; r < 4; ++r) w[r] = (__bf16)(o[2 * half + dbl][4 * g + r] * inv);
+                        *reinterpret_cast<bf16x4 *>(stage + col * kStageRow + (32 * dbl + 8 * g + 4 * hl) * 2) = w;
+                    }
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int r = 8 * j + (lane >> 3), chunk = lane & 7;
+                    const uint4 piece = *reinterpret_cast<const uint4 *>(stage + r * kStageRow + chunk * 16);
+                    const int32_t pos = *reinterpret_cast<const int32_t *>(stage + r * kStageRow + 128);
+                    if (have_item && pos < L) {
+                        __bf16 *orow = reinterpret_cast<__bf16 *>(a.out) + ((size_t)head * R + (pos - a.q_begin)) * D;
+                        *reinterpret_cast<uint4 *>(orow + 64 * half + chunk * 8) = piece;
+                    }
                 }
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                __builtin_amdgcn_wave_barrier();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            }
         }
+        // the patches lie in the ring: nobody loads the next unit's first tiles before every wave is done with its own
+        __builtin_amdgcn_s_waitcnt(0xc07f);   // lgkmcnt(0)
+        __builtin_amdgcn_s_barrier();
         unit = next_unit;
     }
 }
