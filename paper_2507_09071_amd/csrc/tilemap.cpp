@@ -859,6 +859,7 @@ void bs_plan_pairs(bs_tilemap *tm, int32_t G)
         const int64_t for_balance = total / 256 / 64;                     // 256 workgroups
         cost_bucket = (int32_t)std::max<int64_t>(32, std::min(for_locality, for_balance) / 32 * 32);
     }
+    const int32_t kXcdBlock = std::min<int64_t>(16, std::max<int64_t>(8, (int64_t)plan.items.size() / 2048));
     std::stable_sort(plan.items.begin(), plan.items.end(), [G, cost_bucket](const bs::PairItem &a, const bs::PairItem &b) {
         const int32_t ba = a.n_tiles / cost_bucket, bb = b.n_tiles / cost_bucket;
         if (ba != bb) return ba > bb;
