@@ -96,10 +96,10 @@ class HipEvents:
 # figures of earlier profiled runs of the same command, NOT read in this run; the JSON says so.
 # Keyed by workload and row order of the map -> (bytes, summary under profiles/).
 MEASURED_TRAFFIC = {
-    ("cfg2-qwen2vl7b-36k/paper10/seed0", "packed"): (4.78e9, "profiles/attn_prefill_bf16_d128_cfg2_36k.md"),
-    ("cfg3-qwen25vl32b-128k/paper10/seed0", "packed"): (67.6e9, "profiles/attn_prefill_bf16_d128_128k_300k.md"),
-    ("cfg4-gemma3-27b-300k/paper10/seed0", "packed"): (396.0e9, "profiles/attn_prefill_bf16_d128_128k_300k.md"),
-    ("cfg5-stress-307200/paper10/seed0", "packed"): (185.8e9, "profiles/attn_prefill_bf16_d128_128k_300k.md"),
+    ("cfg2-qwen2vl7b-36k/paper10/seed0", "packed"): (4.82e9, "profiles/attn_prefill_bf16_d128_cfg2_36k.md"),
+    ("cfg3-qwen25vl32b-128k/paper10/seed0", "packed"): (62.8e9, "profiles/attn_prefill_bf16_d128_128k_300k.md"),
+    ("cfg4-gemma3-27b-300k/paper10/seed0", "packed"): (374.4e9, "profiles/attn_prefill_bf16_d128_128k_300k.md"),
+    ("cfg5-stress-307200/paper10/seed0", "packed"): (174.5e9, "profiles/attn_prefill_bf16_d128_128k_300k.md"),
 }
 
 
